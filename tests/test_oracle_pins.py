@@ -1,0 +1,395 @@
+"""Pins for the CPU oracle: everything here is fixed by the paper or by mathematics,
+never by the oracle itself and never by the HIP path."""
+import itertools
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from oracle import Dims
+
+RNG = np.random.default_rng(1234)
+
+
+def rnd(*shape):
+    return RNG.standard_normal(shape).astype(np.float32)
+
+
+def ints(*shape, lo=-3, hi=4):
+    return RNG.integers(lo, hi, size=shape).astype(np.float32)
+
+
+# ---------------------------------------------------------------- brute force, by hand
+def test_hand_computed_3x3_by_2x2():
+    # eq. (1): R[r,c] = sum D[r+r', c+c'] K[r', c'], n=3, k=2, m=n-k+1=2
+    x = np.array([[[[1, 2, 3], [4, 5, 6], [7, 8, 10]]]], np.float32)
+    w = np.array([[[[1, -1], [2, 3]]]], np.float32)
+    want = np.array([[1 - 2 + 8 + 15, 2 - 3 + 10 + 18], [4 - 5 + 14 + 24, 5 - 6 + 16 + 30]], float)
+    got = oracle.conv_forward(Dims(1, 1, 3, 3, 1, 2), x, w)
+    assert got.shape == (1, 1, 2, 2)
+    assert np.array_equal(got[0, 0], want)
+
+
+def test_hand_computed_two_groups_integer():
+    # N=1, C=2, O=2, groups=2, 2x2 input, 1x1... use K=2 pad=0 -> single output per channel
+    x = np.array([[[[1, 2], [3, 4]], [[5, 6], [7, 8]]]], np.float32)
+    w = np.array([[[[1, 0], [0, 1]]], [[[2, 1], [1, 2]]]], np.float32)  # O=2, Cg=1
+    b = np.array([10, -10], np.float32)
+    got = oracle.conv_forward(Dims(1, 2, 2, 2, 2, 2, groups=2), x, w, b)
+    # group 0: channel 0 only: 1+4+10 ; group 1: channel 1 only: 10+6+7+16-10
+    assert np.array_equal(got.ravel(), np.array([15.0, 29.0]))
+
+
+def test_hand_computed_channel_sum():
+    # two input channels, one group: the sum over i in eq. (1) runs over both
+    x = np.array([[[[1, 2], [3, 4]], [[5, 6], [7, 8]]]], np.float32)
+    w = np.array([[[[1, 1], [1, 1]], [[1, 0], [0, -1]]]], np.float32)
+    got = oracle.conv_forward(Dims(1, 2, 2, 2, 1, 2), x, w)
+    assert got.ravel()[0] == (1 + 2 + 3 + 4) + (5 - 8)
+
+
+# ---------------------------------------------------------------- 1x1 conv == matrix product
+@pytest.mark.parametrize("N,C,O,H,W", [(2, 5, 7, 4, 3), (1, 8, 2, 5, 5)])
+def test_1x1_is_matmul(N, C, O, H, W):
+    x, w = rnd(N, C, H, W), rnd(O, C, 1, 1)
+    got = oracle.conv_forward(Dims(N, C, H, W, O, 1), x, w)
+    want = np.einsum("oc,nchw->nohw", w[:, :, 0, 0].astype(np.float64), x.astype(np.float64))
+    np.testing.assert_allclose(got, want, rtol=1e-13, atol=1e-13)
+
+
+# ---------------------------------------------------------------- delta kernel (no flip) + padding
+@pytest.mark.parametrize("i0,j0", [(0, 0), (0, 2), (2, 1), (1, 1)])
+def test_delta_kernel_shifts_input(i0, j0):
+    H, W, K, p = 6, 7, 3, 1
+    x = rnd(2, 1, H, W)
+    w = np.zeros((1, 1, K, K), np.float32)
+    w[0, 0, i0, j0] = 1
+    got = oracle.conv_forward(Dims(2, 1, H, W, 1, K, 1, p), x, w)
+    xp = np.pad(x.astype(np.float64), ((0, 0), (0, 0), (p, p), (p, p)))
+    # cross-correlation: y[r,c] = x[r + i0 - p, c + j0 - p]; a flipped kernel would shift the other way
+    want = xp[:, :, i0:i0 + H, j0:j0 + W]
+    assert np.array_equal(got, want)
+
+
+# ---------------------------------------------------------------- all-ones closed form
+@pytest.mark.parametrize("H,W,K,s,p,g", [(7, 9, 3, 1, 1, 1), (10, 10, 3, 2, 0, 2), (11, 8, 5, 2, 2, 1),
+                                         (9, 9, 4, 3, 1, 3)])
+def test_all_ones_counts_in_range_taps(H, W, K, s, p, g):
+    C, O = 6, 6
+    d = Dims(2, C, H, W, O, K, s, p, g)
+    got = oracle.conv_forward(d, np.ones((2, C, H, W), np.float32), np.ones((O, C // g, K, K), np.float32))
+    ho, wo = (H + 2 * p - K) // s + 1, (W + 2 * p - K) // s + 1
+    assert got.shape == (2, O, ho, wo)
+    rows = np.array([sum(0 <= r * s + i - p < H for i in range(K)) for r in range(ho)])
+    cols = np.array([sum(0 <= c * s + j - p < W for j in range(K)) for c in range(wo)])
+    want = (C // g) * np.outer(rows, cols)
+    assert np.array_equal(got, np.broadcast_to(want, got.shape))
+
+
+def test_floor_in_output_size_last_row_unused():
+    # H=10, K=3, s=2, p=0 -> Hout = floor(7/2)+1 = 4; input row 9 never read
+    d = Dims(1, 1, 10, 10, 1, 3, 2, 0)
+    assert oracle.output_dims(d) == (4, 4)
+    x = rnd(1, 1, 10, 10)
+    w = rnd(1, 1, 3, 3)
+    y0 = oracle.conv_forward(d, x, w)
+    x2 = x.copy()
+    x2[:, :, 9, :] = 99
+    x2[:, :, :, 9] = -99
+    assert np.array_equal(oracle.conv_forward(d, x2, w), y0)
+
+
+# ---------------------------------------------------------------- structural identities
+def test_pad_equals_explicit_zero_padding():
+    N, C, H, W, O, K, s, p = 2, 3, 6, 5, 4, 3, 2, 2
+    x, w, b = rnd(N, C, H, W), rnd(O, C, K, K), rnd(O)
+    a = oracle.conv_forward(Dims(N, C, H, W, O, K, s, p), x, w, b)
+    xp = np.pad(x, ((0, 0), (0, 0), (p, p), (p, p)))
+    bb = oracle.conv_forward(Dims(N, C, H + 2 * p, W + 2 * p, O, K, s, 0), xp, w, b)
+    assert np.array_equal(a, bb)
+
+
+def test_stride_equals_subsampled_stride1():
+    N, C, H, W, O, K, s, p = 1, 2, 11, 9, 3, 3, 3, 1
+    x, w = rnd(N, C, H, W), rnd(O, C, K, K)
+    a = oracle.conv_forward(Dims(N, C, H, W, O, K, s, p), x, w)
+    full = oracle.conv_forward(Dims(N, C, H, W, O, K, 1, p), x, w)
+    assert np.array_equal(a, full[:, :, ::s, ::s][:, :, :a.shape[2], :a.shape[3]])
+
+
+def test_groups_equal_independent_convs():
+    N, C, H, W, O, K, g = 2, 6, 5, 5, 4, 3, 2
+    x, w, b = rnd(N, C, H, W), rnd(O, C // g, K, K), rnd(O)
+    a = oracle.conv_forward(Dims(N, C, H, W, O, K, 1, 1, g), x, w, b)
+    parts = []
+    for q in range(g):
+        xs = np.ascontiguousarray(x[:, q * 3:(q + 1) * 3])
+        parts.append(oracle.conv_forward(Dims(N, 3, H, W, 2, K, 1, 1, 1), xs,
+                                         np.ascontiguousarray(w[q * 2:(q + 1) * 2]),
+                                         np.ascontiguousarray(b[q * 2:(q + 1) * 2])))
+    assert np.array_equal(a, np.concatenate(parts, axis=1))
+
+
+def test_linearity_and_bias():
+    d = Dims(2, 3, 6, 6, 4, 3, 1, 1)
+    x1, x2, w = ints(2, 3, 6, 6), ints(2, 3, 6, 6), ints(4, 3, 3, 3)
+    b = ints(4)
+    f = lambda x, bias=None: oracle.conv_forward(d, x, w, bias)
+    assert np.array_equal(f(x1 + 2 * x2), f(x1) + 2 * f(x2))        # small integers: exact
+    assert np.array_equal(f(x1, b), f(x1) + b.astype(np.float64)[None, :, None, None])
+
+
+# ---------------------------------------------------------------- library routines as special cases
+def test_against_scipy_correlate2d():
+    from scipy.signal import correlate2d
+    x, w = rnd(1, 1, 9, 8), rnd(1, 1, 4, 4)
+    got = oracle.conv_forward(Dims(1, 1, 9, 8, 1, 4), x, w)[0, 0]
+    want = correlate2d(x[0, 0].astype(np.float64), w[0, 0].astype(np.float64), mode="valid")
+    np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-12)
+
+
+CASES = [
+    # N, C, H, W, O, K, s, p, g
+    (2, 3, 8, 8, 4, 3, 1, 1, 1),
+    (1, 4, 9, 7, 6, 3, 2, 0, 2),
+    (2, 6, 11, 11, 3, 5, 2, 2, 3),
+    (1, 3, 23, 23, 8, 11, 4, 0, 1),
+    (3, 2, 5, 6, 2, 1, 1, 0, 1),
+    (1, 2, 7, 7, 2, 2, 3, 1, 1),
+    (2, 4, 6, 6, 4, 4, 2, 3, 2),
+]
+
+
+@pytest.mark.parametrize("case", CASES)
+def test_against_torch_conv2d_fp64_with_autograd(case):
+    """torch's CPU conv2d in fp64 and its autograd are an independent implementation of the
+    Caffe-style layer (stride, zero pad, groups, bias) and of its gradients."""
+    import torch
+    import torch.nn.functional as F
+    N, C, H, W, O, K, s, p, g = case
+    d = Dims(N, C, H, W, O, K, s, p, g)
+    x, w, b = rnd(N, C, H, W), rnd(O, C // g, K, K), rnd(O)
+    ho, wo = oracle.output_dims(d)
+    dy = rnd(N, O, ho, wo)
+    tx = torch.from_numpy(x).double().requires_grad_()
+    tw = torch.from_numpy(w).double().requires_grad_()
+    tb = torch.from_numpy(b).double().requires_grad_()
+    ty = F.conv2d(tx, tw, tb, stride=s, padding=p, groups=g)
+    ty.backward(torch.from_numpy(dy).double())
+    np.testing.assert_allclose(oracle.conv_forward(d, x, w, b), ty.detach().numpy(), rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(oracle.conv_backward_data(d, w, dy), tx.grad.numpy(), rtol=1e-11, atol=1e-12)
+    dw, db = oracle.conv_backward_weights(d, x, dy)
+    np.testing.assert_allclose(dw, tw.grad.numpy(), rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(db, tb.grad.numpy(), rtol=1e-11, atol=1e-12)
+
+
+# ---------------------------------------------------------------- the paper's printed formulas
+def paper_vec(a):
+    """vec() of a k x k x d (or k x d, or d) slice; any fixed flattening works as long as the data
+    and kernel sides use the same one (the printed Z_{5i+j} for a 5x2 slice cannot be right)."""
+    return np.asarray(a, np.float64).reshape(-1)
+
+
+def paper_type1(D, Ks):
+    n, k = D.shape[0], Ks[0].shape[0]
+    m = n - k + 1
+    Dh = np.zeros((m * m, k * k * D.shape[2]))
+    for r in range(m):
+        for c in range(m):
+            Dh[c * m + r, :] = paper_vec(D[r:r + k, c:c + k, :])           # D^[cm+r,:] = vec(D[r:r+k,c:c+k,:])
+    out = []
+    for Kt in Ks:
+        Rh = Dh @ paper_vec(Kt)                                             # K^ = vec(K)
+        R = np.zeros((m, m))
+        for r in range(m):
+            for c in range(m):
+                R[r, c] = Rh[c * m + r]                                     # trivial reshape
+        out.append(R)
+    return out
+
+
+def paper_type3(D, Ks):
+    n, k, dd = D.shape[0], Ks[0].shape[0], D.shape[2]
+    m = n - k + 1
+    Dh = np.zeros((n * n, dd))
+    for r in range(n):
+        for c in range(n):
+            Dh[c * n + r, :] = paper_vec(D[r, c, :])                        # D^[cn+r,:] = vec(D[r,c,:])
+    out = []
+    for Kt in Ks:
+        Kh = np.zeros((dd, k * k))
+        for i in range(k):
+            for j in range(k):
+                Kh[:, i * k + j] = paper_vec(Kt[i, j, :])                   # K^[:,ik+j] = vec(K[i,j,:])
+        Rh = Dh @ Kh
+        R = np.zeros((m, m))
+        for r in range(m):
+            for c in range(m):
+                R[r, c] = sum(Rh[(c + j) * n + r + i, i * k + j] for i in range(k) for j in range(k))
+        out.append(R)
+    return out
+
+
+def paper_type2(D, Ks):
+    n, k, dd = D.shape[0], Ks[0].shape[0], D.shape[2]
+    m = n - k + 1
+    Dh = np.zeros((n * n, k * dd))
+    for r in range(n):
+        for c in range(m):                                                  # columns with a full window
+            Dh[c * n + r, :] = paper_vec(D[r, c:c + k, :])                  # D^[cn+r,:] = vec(D[r,c:c+k,:])
+    out = []
+    for Kt in Ks:
+        Kh = np.zeros((k * dd, k))
+        for i in range(k):
+            Kh[:, i] = paper_vec(Kt[i, :, :])                               # K^[:,i] = vec(K[i,:,:])
+        Rh = Dh @ Kh
+        R = np.zeros((m, m))
+        for r in range(m):
+            for c in range(m):
+                R[r, c] = sum(Rh[c * n + r + j, j] for j in range(k))       # R[r,c] = sum_j R^[cn+r+j, j]
+        out.append(R)
+    return out
+
+
+@pytest.mark.parametrize("n,k,dd,o", [(5, 2, 3, 2), (6, 3, 2, 3), (4, 4, 1, 1)])
+def test_paper_printed_lowerings_equal_direct(n, k, dd, o):
+    """Types 1-3 exactly as printed in Sec. 2.1 (channel-last tensors, rows cm+r / cn+r, the
+    printed lifting sums) all reproduce eq. (1), and all agree with the oracle's direct loop."""
+    D = ints(n, n, dd)
+    Ks = [ints(k, k, dd) for _ in range(o)]
+    x = np.ascontiguousarray(D.transpose(2, 0, 1))[None]                    # NCHW
+    w = np.ascontiguousarray(np.stack([Kt.transpose(2, 0, 1) for Kt in Ks]))
+    direct = oracle.conv_forward(Dims(1, dd, n, n, o, k), x, w)[0]
+    for fn in (paper_type1, paper_type2, paper_type3):
+        got = fn(D, Ks)
+        for t in range(o):
+            assert np.array_equal(got[t], direct[t]), fn.__name__
+
+
+@pytest.mark.parametrize("case", CASES)
+@pytest.mark.parametrize("lowering", [1, 2, 3])
+def test_oracle_lowered_route_equals_direct(case, lowering):
+    N, C, H, W, O, K, s, p, g = case
+    d = Dims(N, C, H, W, O, K, s, p, g)
+    x, w, b = ints(N, C, H, W), ints(O, C // g, K, K), ints(O)
+    assert np.array_equal(oracle.conv_forward_lowered(d, lowering, x, w, b), oracle.conv_forward(d, x, w, b))
+
+
+def test_lowering_is_a_pure_copy_with_positive_zero_padding():
+    d = Dims(2, 2, 5, 5, 2, 3, 2, 1, 1)
+    x = (np.arange(2 * 2 * 5 * 5, dtype=np.float32) + 1).reshape(2, 2, 5, 5)   # value names its source
+    for t in (1, 2, 3):
+        dh = oracle.lower_data(d, t, x)
+        vals = set(np.unique(dh).tolist())
+        assert vals <= set(x.ravel().tolist()) | {0.0}
+        assert not np.signbit(dh[dh == 0]).any()
+    d1 = oracle.lower_data(d, 1, x)[0]
+    # row (n=1, r=1, c=2), col (ci=1, i=2, j=0): x[1,1, 1*2+2-1, 2*2+0-1]
+    assert d1[(1 * 3 + 1) * 3 + 2, (1 * 3 + 2) * 3 + 0] == x[1, 1, 3, 3]
+    # top-left window starts in the padding: (i=0,*) and (*,j=0) are zero
+    assert d1[0, 0] == 0 and d1[0, 4] == x[0, 0, 0, 0]
+
+
+# ---------------------------------------------------------------- shape laws
+def test_shape_laws_golden():
+    path = os.path.join(os.path.dirname(__file__), "golden", "caffenet_shapes.txt")
+    seen = 0
+    for line in open(path):
+        if line.startswith("#") or not line.strip():
+            continue
+        f = line.split()
+        C, H, O, K, s, p, g, hout = map(int, f[1:9])
+        want = list(map(int, f[9:15]))
+        d = Dims(1, C, H, H, O, K, s, p, g)
+        assert oracle.output_dims(d) == (hout, hout)
+        got = []
+        for t in (1, 2, 3):
+            rows, cols, rcols = oracle.lowered_shape(d, t)
+            got += [rows, cols]
+            assert rcols == (O // g) * K ** (t - 1)
+        assert got == want, f[0]
+        seen += 1
+    assert seen == 5
+
+
+def test_m_equals_n_minus_k_plus_1():
+    for n, k in itertools.product((5, 13, 27), (1, 3, 5)):
+        assert oracle.output_dims(Dims(1, 1, n, n, 1, k)) == (n - k + 1, n - k + 1)
+
+
+def test_lowered_matrix_grows_linearly_with_batch():
+    # Sec. 2.2: a batch of b images makes the lowered matrix b times larger
+    for t in (1, 2, 3):
+        r1 = oracle.lowered_shape(Dims(1, 4, 9, 9, 4, 3, 1, 1), t)
+        r8 = oracle.lowered_shape(Dims(8, 4, 9, 9, 4, 3, 1, 1), t)
+        assert r8[0] == 8 * r1[0] and r8[1:] == r1[1:]
+
+
+# ---------------------------------------------------------------- backward passes
+@pytest.mark.parametrize("case", CASES)
+def test_adjoint_identities(case):
+    N, C, H, W, O, K, s, p, g = case
+    d = Dims(N, C, H, W, O, K, s, p, g)
+    x, w = ints(N, C, H, W), ints(O, C // g, K, K)
+    ho, wo = oracle.output_dims(d)
+    dy = ints(N, O, ho, wo)
+    lhs = float((dy.astype(np.float64) * oracle.conv_forward(d, x, w)).sum())
+    assert lhs == float((oracle.conv_backward_data(d, w, dy) * x).sum())
+    dw, db = oracle.conv_backward_weights(d, x, dy)
+    assert lhs == float((dw * w).sum())
+    assert np.array_equal(db, dy.astype(np.float64).sum(axis=(0, 2, 3)))
+
+
+def test_finite_differences_of_inner_product():
+    """L(x,w,b) = <dy, y> is linear in each argument, so a central difference with a dyadic step on
+    dyadic data is exact: every gradient entry must match with zero error."""
+    d = Dims(2, 2, 5, 4, 2, 3, 2, 1, 1)
+    x, w, b = ints(2, 2, 5, 4), ints(2, 2, 3, 3), ints(2)
+    ho, wo = oracle.output_dims(d)
+    dy = ints(2, 2, ho, wo).astype(np.float32)
+    L = lambda x_, w_, b_: float((dy.astype(np.float64) * oracle.conv_forward(d, x_, w_, b_)).sum())
+    dx = oracle.conv_backward_data(d, w, dy)
+    dw, db = oracle.conv_backward_weights(d, x, dy)
+    h = np.float32(0.5)
+    for idx in np.ndindex(*x.shape):
+        xp, xm = x.copy(), x.copy()
+        xp[idx] += h
+        xm[idx] -= h
+        assert (L(xp, w, b) - L(xm, w, b)) / (2 * float(h)) == dx[idx]
+    for idx in np.ndindex(*w.shape):
+        wp, wm = w.copy(), w.copy()
+        wp[idx] += h
+        wm[idx] -= h
+        assert (L(x, wp, b) - L(x, wm, b)) / (2 * float(h)) == dw[idx]
+    for o in range(2):
+        bp, bm = b.copy(), b.copy()
+        bp[o] += h
+        bm[o] -= h
+        assert (L(x, w, bp) - L(x, w, bm)) / (2 * float(h)) == db[o]
+
+
+# ---------------------------------------------------------------- sampled entry points == full ones
+def test_sampled_entry_points_match_full():
+    d = Dims(2, 4, 7, 6, 4, 3, 2, 1, 2)
+    x, w, b = rnd(2, 4, 7, 6), rnd(4, 2, 3, 3), rnd(4)
+    ho, wo = oracle.output_dims(d)
+    dy = rnd(2, 4, ho, wo)
+    y = oracle.conv_forward(d, x, w, b)
+    idx = np.arange(y.size)[::3]
+    assert np.array_equal(oracle.conv_forward_at(d, x, w, b, idx), y.ravel()[idx])
+    dx = oracle.conv_backward_data(d, w, dy)
+    idx = np.arange(dx.size)[::5]
+    assert np.array_equal(oracle.conv_backward_data_at(d, w, dy, idx), dx.ravel()[idx])
+    dw, _ = oracle.conv_backward_weights(d, x, dy)
+    idx = np.arange(dw.size)[::2]
+    assert np.array_equal(oracle.conv_backward_weights_at(d, x, dy, idx), dw.ravel()[idx])
+    with pytest.raises(ValueError):
+        oracle.conv_forward_at(d, x, w, b, np.array([y.size]))
+
+
+def test_rejects_bad_shapes():
+    with pytest.raises(ValueError):
+        oracle.output_dims(Dims(1, 3, 4, 4, 2, 3, 1, 0, 2))      # C % groups != 0
+    with pytest.raises(ValueError):
+        oracle.output_dims(Dims(1, 1, 2, 2, 1, 3))               # kernel larger than padded input
