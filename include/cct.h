@@ -1,0 +1,188 @@
+/*
+ * cct.h - C ABI of libcct.so: the lowering-based convolutional layer of
+ * "Caffe con Troll" (arXiv 1504.04343) as hand-written HIP for gfx950 (MI355X).
+ *
+ * The layer is computed in the paper's three phases (Sec. 2.1): LOWER the batch of
+ * input tensors into one matrix D^ (all images of a chunk side by side, Sec. 2.2),
+ * MULTIPLY it with the lowered kernels K^ on the matrix cores, LIFT the product R^
+ * back to a tensor and add the bias.  Three lowering layouts exist (Sec. 2.1,
+ * Type 1 "expensive lowering", Type 2 "balanced", Type 3 "expensive lifting") and
+ * an automatic optimizer picks one from the ratio of input to output channels
+ * (Sec. 1, Appendix A).  The paper states the forward pass only; the two backward
+ * passes are the adjoints of the same three phases run in reverse order.
+ *
+ * Problem statement (Sec. 2): a batch of b data tensors with d channels and o kernels
+ * of size k x k x d.  Here: x is N x C x H x W (NCHW, contiguous fp32), w is
+ * O x (C/groups) x K x K (contiguous fp32), y is N x O x Hout x Wout with
+ * Hout = floor((H + 2*pad - K)/stride) + 1 (same for W).  Semantics (stride, zero
+ * padding on all four sides, channel groups, bias, no kernel flip) are Caffe's, which
+ * the paper's system reproduces layer by layer (Sec. 1, Sec. 3.2):
+ *
+ *   y[n,o,r,c] = bias[o] + sum_{ci,i,j} x[n, (o/Og)*Cg+ci, r*stride+i-pad, c*stride+j-pad] * w[o,ci,i,j]
+ *
+ * General rules for every entry point
+ *  - All tensor pointers are DEVICE pointers (HIP global memory) unless stated
+ *    otherwise; descriptors and scalar outputs are HOST pointers.
+ *  - The caller owns every buffer including the workspace.  The library never
+ *    allocates or frees device memory, never synchronises, and enqueues work only on
+ *    the given HIP stream (`hip_stream` is a hipStream_t passed as void*; NULL = the
+ *    default stream).  Calls return as soon as the work is enqueued.
+ *  - Outputs are overwritten (beta = 0), never accumulated.  Inputs, outputs and
+ *    workspace must not overlap.
+ *  - Return value: CCT_OK (0) or a negative CCT_E* code.  On error nothing has been
+ *    enqueued for that call (except CCT_EHIP, which reports a failed launch).
+ *  - The workspace must be 256-byte aligned.  Its size decides how many images are
+ *    lowered and multiplied together ("batch as much as device memory permits",
+ *    Sec. 2.2): the library processes the batch in chunks of the largest number of
+ *    images whose buffers fit the workspace it was given.
+ */
+#ifndef CCT_H_
+#define CCT_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Lowering layout, Sec. 2.1.  AUTO lets cct_pick_lowering decide. */
+typedef enum {
+  CCT_LOWER_AUTO = 0,
+  CCT_LOWER_TYPE1 = 1, /* D^ rows = output positions, cols = (ci,i,j); trivial lifting      */
+  CCT_LOWER_TYPE2 = 2, /* D^ rows = (input row, output col), cols = (ci,j); lift sums K rows */
+  CCT_LOWER_TYPE3 = 3  /* D^ rows = input positions, cols = ci; lift sums K*K entries        */
+} cct_lowering_t;
+
+typedef enum {
+  CCT_PREC_F32 = 0,            /* fp32 operands, fp32 MFMA accumulate                        */
+  CCT_PREC_BF16_IN_F32_ACC = 1 /* operands rounded to bf16 (nearest-even) while lowering,
+                                  bf16 MFMA with fp32 accumulate, fp32 outputs               */
+} cct_precision_t;
+
+typedef enum {
+  CCT_PASS_FORWARD = 0,
+  CCT_PASS_BACKWARD_DATA = 1,
+  CCT_PASS_BACKWARD_WEIGHTS = 2
+} cct_pass_t;
+
+enum {
+  CCT_OK = 0,
+  CCT_EINVAL = -1,       /* null required pointer, non-positive dim, C or O not divisible by
+                            groups, stride < 1, pad < 0, kernel larger than the padded input,
+                            unknown enum value, misaligned workspace                         */
+  CCT_EWORKSPACE = -2,   /* workspace smaller than what one image needs                      */
+  CCT_EUNSUPPORTED = -3, /* explicitly requested combination the library does not run, or
+                            sizes beyond its 31-bit row/column limits                        */
+  CCT_EHIP = -4          /* a HIP launch failed; see cct_last_hip_error                      */
+};
+
+/* Host struct.  `lowering` holds a cct_lowering_t, `precision` a cct_precision_t. */
+typedef struct {
+  int32_t N, C, H, W;          /* input x: N x C x H x W                                    */
+  int32_t O, K;                /* kernels w: O x (C/groups) x K x K; bias: O floats or NULL */
+  int32_t stride, pad, groups;
+  int32_t lowering;
+  int32_t precision;
+} cct_conv_desc_t;
+
+/* Human-readable text for a return code (host, static storage). */
+const char* cct_strerror(int code);
+/* The hipError_t (as int) of the last failed launch on this thread, 0 if none. */
+int cct_last_hip_error(void);
+
+/* Output size, m = n - k + 1 generalised to stride and pad (Sec. 2, below eq. (1)).  Host only. */
+int cct_conv_output_dims(const cct_conv_desc_t* desc, int32_t* Hout, int32_t* Wout);
+
+/*
+ * Shapes of the lowered matrices per channel group, in the paper's orientation
+ * (Sec. 2.1): D^ is rows x cols, K^ is cols x rcols, R^ = D^ K^ is rows x rcols.
+ * rows counts all N images (Sec. 2.2: the batched matrix is b times larger).
+ *   Type 1: rows = N*Hout*Wout, cols = Cg*K*K, rcols = Og
+ *   Type 2: rows = N*H*Wout,    cols = Cg*K,   rcols = Og*K
+ *   Type 3: rows = N*H*W,       cols = Cg,     rcols = Og*K*K
+ * `lowering` must be TYPE1..TYPE3.  Host only.
+ */
+int cct_lowered_shape(const cct_conv_desc_t* desc, cct_lowering_t lowering, int64_t* rows,
+                      int64_t* cols, int64_t* rcols);
+
+/*
+ * The automatic lowering optimizer (Sec. 1; Appendix A "the relative performance ...
+ * is determined by the ratio between the number of input channels and the number of
+ * output channels").  Host only, no device work.  Evaluates a cost model
+ * (bytes moved by lowering and lifting at the measured HBM rate + GEMM flops at the
+ * measured MFMA rate, both calibrated on MI355X) for each layout that the library can
+ * run for `pass` on this shape and returns the cheapest.  Never returns a layout that
+ * cct_conv_* would reject for the same descriptor; for K == 1, stride == 1, pad == 0 all
+ * three layouts coincide and TYPE1 is returned.  desc->lowering is ignored.
+ */
+int cct_pick_lowering(const cct_conv_desc_t* desc, cct_pass_t pass, cct_lowering_t* picked);
+
+/* The optimizer's cost estimate (seconds) for one layout; CCT_EUNSUPPORTED if the layout
+ * cannot run for this shape/pass.  Host only. */
+int cct_lowering_cost(const cct_conv_desc_t* desc, cct_pass_t pass, cct_lowering_t lowering,
+                      double* seconds);
+
+/*
+ * Workspace size.  cct_conv_workspace_bytes gives the recommended size (chunks sized by
+ * the library's tuned default); cct_conv_workspace_bytes_for_chunk gives the size needed
+ * to process `images_per_chunk` images (1..N) at a time.  Any workspace at least as large
+ * as the 1-image size is accepted by cct_conv_*; a larger one means larger chunks, up to
+ * the whole batch.  desc->lowering == AUTO is resolved with cct_pick_lowering.  Host only.
+ */
+int cct_conv_workspace_bytes(const cct_conv_desc_t* desc, cct_pass_t pass, size_t* bytes);
+int cct_conv_workspace_bytes_for_chunk(const cct_conv_desc_t* desc, cct_pass_t pass,
+                                       int32_t images_per_chunk, size_t* bytes);
+
+/*
+ * Forward pass (Sec. 2.1: lowering phase, multiply phase, lifting phase; batched over
+ * the chunk, Sec. 2.2).  x, w: device, read.  bias: device, O floats, may be NULL.
+ * y: device, written (N*O*Hout*Wout floats).
+ */
+int cct_conv_forward(const cct_conv_desc_t* desc, const float* x, const float* w,
+                     const float* bias, float* y, void* workspace, size_t workspace_bytes,
+                     void* hip_stream);
+
+/*
+ * Backward pass w.r.t. the data: dx = adjoint of the forward map in x applied to dy,
+ *   dx[n,q*Cg+ci,h,w] = sum_{o in group q} sum_{i,j} dy[n,o,r,c] * w[o,ci,i,j]
+ *   over (i,j) with h = r*stride+i-pad, w = c*stride+j-pad for a valid output position (r,c).
+ * Computed as the three phases reversed: inverse lifting of dy, multiply with K^ transposed,
+ * inverse lowering (a gather, no atomics).  w, dy: device, read.  dx: device, written.
+ */
+int cct_conv_backward_data(const cct_conv_desc_t* desc, const float* w, const float* dy,
+                           float* dx, void* workspace, size_t workspace_bytes,
+                           void* hip_stream);
+
+/*
+ * Backward pass w.r.t. the kernels and bias:
+ *   dw[o,ci,i,j] = sum_{n,r,c} dy[n,o,r,c] * x[n,q*Cg+ci,r*stride+i-pad,c*stride+j-pad]
+ *   dbias[o]     = sum_{n,r,c} dy[n,o,r,c]
+ * Computed as D^ transposed times the inverse-lifted dy, reduced over all rows of the
+ * batched lowered matrix in fixed order (bit-reproducible run to run).
+ * x, dy: device, read.  dw: device, written.  dbias: device, O floats, may be NULL.
+ */
+int cct_conv_backward_weights(const cct_conv_desc_t* desc, const float* x, const float* dy,
+                              float* dw, float* dbias, void* workspace,
+                              size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Test/debug export of the lowering phase alone (Sec. 2.1), whole batch, fp32.
+ * The library stores the lowered data matrix TRANSPOSED ("K-major"): for group q,
+ * entry (row, col) of the paper's D^ lives at
+ *     dhat[(q*cols + col) * ld + row],   ld = cct_lowered_ld(desc, lowering)
+ * with row/col numbered as
+ *   Type 1: row = (n*Hout + r)*Wout + c,  col = (ci*K + i)*K + j   -> x[n,q*Cg+ci,r*s+i-p,c*s+j-p]
+ *   Type 2: row = (n*H + h)*Wout + c,     col = ci*K + j           -> x[n,q*Cg+ci,h,c*s+j-p]
+ *   Type 3: row = (n*H + h)*W + w,        col = ci                 -> x[n,q*Cg+ci,h,w]
+ * and +0.0f where the source lies in the padding.  Entries with row >= rows are not written.
+ * dhat: device, groups*cols*ld floats.  A pure copy: bit-exact by construction.
+ */
+int cct_lowered_ld(const cct_conv_desc_t* desc, cct_lowering_t lowering, int64_t* ld);
+int cct_lower(const cct_conv_desc_t* desc, cct_lowering_t lowering, const float* x, float* dhat,
+              void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CCT_H_ */

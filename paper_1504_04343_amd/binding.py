@@ -1,0 +1,213 @@
+"""ctypes binding of libcct.so (include/cct.h).  Argument marshalling only.
+
+Every function here has the name of the C entry point it calls.  Tensors are
+torch tensors on the GPU (contiguous fp32); the binding passes their
+``data_ptr()`` and the current HIP stream.  Nothing is computed in Python and
+there is no fallback: importing this module raises if libcct.so is missing.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libcct.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        "libcct.so has not been built (run `python -m paper_1504_04343_amd.build` or "
+        "`__graft_entry__.build()`); there is no CPU fallback")
+
+_lib = ctypes.CDLL(LIB_PATH)
+
+LOWER_AUTO, LOWER_TYPE1, LOWER_TYPE2, LOWER_TYPE3 = 0, 1, 2, 3
+PREC_F32, PREC_BF16_IN_F32_ACC = 0, 1
+PASS_FORWARD, PASS_BACKWARD_DATA, PASS_BACKWARD_WEIGHTS = 0, 1, 2
+OK, EINVAL, EWORKSPACE, EUNSUPPORTED, EHIP = 0, -1, -2, -3, -4
+
+EXPORTS = [
+    "cct_strerror", "cct_last_hip_error", "cct_conv_output_dims", "cct_lowered_shape",
+    "cct_pick_lowering", "cct_lowering_cost", "cct_conv_workspace_bytes",
+    "cct_conv_workspace_bytes_for_chunk", "cct_conv_forward", "cct_conv_backward_data",
+    "cct_conv_backward_weights", "cct_lowered_ld", "cct_lower",
+]
+
+
+class ConvDesc(ctypes.Structure):
+    """cct_conv_desc_t."""
+    _fields_ = [(k, ctypes.c_int32) for k in
+                ("N", "C", "H", "W", "O", "K", "stride", "pad", "groups", "lowering", "precision")]
+
+
+class CctError(RuntimeError):
+    def __init__(self, code, where):
+        self.code = code
+        super().__init__("%s: %s (code %d)" % (where, strerror(code), code))
+
+
+_vp, _sz, _i32, _i64 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int32, ctypes.c_int64
+_dp = ctypes.POINTER(ConvDesc)
+_lib.cct_strerror.restype = ctypes.c_char_p
+_lib.cct_strerror.argtypes = [ctypes.c_int]
+_lib.cct_last_hip_error.restype = ctypes.c_int
+_lib.cct_last_hip_error.argtypes = []
+_lib.cct_conv_output_dims.argtypes = [_dp, ctypes.POINTER(_i32), ctypes.POINTER(_i32)]
+_lib.cct_lowered_shape.argtypes = [_dp, ctypes.c_int, ctypes.POINTER(_i64), ctypes.POINTER(_i64),
+                                   ctypes.POINTER(_i64)]
+_lib.cct_lowered_ld.argtypes = [_dp, ctypes.c_int, ctypes.POINTER(_i64)]
+_lib.cct_pick_lowering.argtypes = [_dp, ctypes.c_int, ctypes.POINTER(ctypes.c_int)]
+_lib.cct_lowering_cost.argtypes = [_dp, ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_double)]
+_lib.cct_conv_workspace_bytes.argtypes = [_dp, ctypes.c_int, ctypes.POINTER(_sz)]
+_lib.cct_conv_workspace_bytes_for_chunk.argtypes = [_dp, ctypes.c_int, _i32, ctypes.POINTER(_sz)]
+_lib.cct_conv_forward.argtypes = [_dp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.cct_conv_backward_data.argtypes = [_dp, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.cct_conv_backward_weights.argtypes = [_dp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.cct_lower.argtypes = [_dp, ctypes.c_int, _vp, _vp, _vp]
+for _name in EXPORTS:
+    if _name not in ("cct_strerror",):
+        getattr(_lib, _name).restype = ctypes.c_int
+
+
+def make_desc(N, C, H, W, O, K, stride=1, pad=0, groups=1, lowering=LOWER_AUTO,
+              precision=PREC_F32) -> ConvDesc:
+    return ConvDesc(N, C, H, W, O, K, stride, pad, groups, lowering, precision)
+
+
+def strerror(code: int) -> str:
+    return _lib.cct_strerror(int(code)).decode()
+
+
+def _check(rc, where):
+    if rc != OK:
+        raise CctError(rc, where)
+
+
+def cct_last_hip_error() -> int:
+    return int(_lib.cct_last_hip_error())
+
+
+def cct_conv_output_dims(desc: ConvDesc):
+    ho, wo = _i32(), _i32()
+    _check(_lib.cct_conv_output_dims(ctypes.byref(desc), ctypes.byref(ho), ctypes.byref(wo)),
+           "cct_conv_output_dims")
+    return ho.value, wo.value
+
+
+def cct_lowered_shape(desc: ConvDesc, lowering: int):
+    r, c, rc_ = _i64(), _i64(), _i64()
+    _check(_lib.cct_lowered_shape(ctypes.byref(desc), int(lowering), ctypes.byref(r),
+                                  ctypes.byref(c), ctypes.byref(rc_)), "cct_lowered_shape")
+    return r.value, c.value, rc_.value
+
+
+def cct_lowered_ld(desc: ConvDesc, lowering: int) -> int:
+    ld = _i64()
+    _check(_lib.cct_lowered_ld(ctypes.byref(desc), int(lowering), ctypes.byref(ld)),
+           "cct_lowered_ld")
+    return ld.value
+
+
+def cct_pick_lowering(desc: ConvDesc, pass_: int = PASS_FORWARD) -> int:
+    out = ctypes.c_int()
+    _check(_lib.cct_pick_lowering(ctypes.byref(desc), int(pass_), ctypes.byref(out)),
+           "cct_pick_lowering")
+    return out.value
+
+
+def cct_lowering_cost(desc: ConvDesc, pass_: int, lowering: int) -> float:
+    out = ctypes.c_double()
+    _check(_lib.cct_lowering_cost(ctypes.byref(desc), int(pass_), int(lowering), ctypes.byref(out)),
+           "cct_lowering_cost")
+    return out.value
+
+
+def cct_conv_workspace_bytes(desc: ConvDesc, pass_: int) -> int:
+    out = _sz()
+    _check(_lib.cct_conv_workspace_bytes(ctypes.byref(desc), int(pass_), ctypes.byref(out)),
+           "cct_conv_workspace_bytes")
+    return out.value
+
+
+def cct_conv_workspace_bytes_for_chunk(desc: ConvDesc, pass_: int, images_per_chunk: int) -> int:
+    out = _sz()
+    _check(_lib.cct_conv_workspace_bytes_for_chunk(ctypes.byref(desc), int(pass_),
+                                                   int(images_per_chunk), ctypes.byref(out)),
+           "cct_conv_workspace_bytes_for_chunk")
+    return out.value
+
+
+# ---- device entry points -----------------------------------------------------------------
+
+def _ptr(t, name, shape=None, optional=False):
+    import torch
+    if t is None:
+        if optional:
+            return None
+        raise ValueError("%s is required" % name)
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError("%s must be a torch tensor on the GPU" % name)
+    if t.dtype != torch.float32 or not t.is_contiguous():
+        raise TypeError("%s must be contiguous fp32" % name)
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError("%s has shape %s, expected %s" % (name, tuple(t.shape), tuple(shape)))
+    return t.data_ptr()
+
+
+def _stream():
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _ws(workspace):
+    import torch
+    if not isinstance(workspace, torch.Tensor) or not workspace.is_cuda or \
+            workspace.dtype != torch.uint8 or not workspace.is_contiguous():
+        raise TypeError("workspace must be a contiguous uint8 torch tensor on the GPU")
+    return workspace.data_ptr(), workspace.numel()
+
+
+def alloc_workspace(desc: ConvDesc, pass_: int, images_per_chunk: int | None = None):
+    """Caller-side helper: a uint8 device tensor of the queried size."""
+    import torch
+    n = cct_conv_workspace_bytes(desc, pass_) if images_per_chunk is None else \
+        cct_conv_workspace_bytes_for_chunk(desc, pass_, images_per_chunk)
+    return torch.empty(n, dtype=torch.uint8, device="cuda")
+
+
+def _shapes(desc: ConvDesc):
+    ho, wo = cct_conv_output_dims(desc)
+    return ((desc.N, desc.C, desc.H, desc.W), (desc.O, desc.C // desc.groups, desc.K, desc.K),
+            (desc.N, desc.O, ho, wo))
+
+
+def cct_conv_forward(desc: ConvDesc, x, w, bias, y, workspace) -> None:
+    xs, ws_, ys = _shapes(desc)
+    wp, wn = _ws(workspace)
+    _check(_lib.cct_conv_forward(ctypes.byref(desc), _ptr(x, "x", xs), _ptr(w, "w", ws_),
+                                 _ptr(bias, "bias", (desc.O,), optional=True), _ptr(y, "y", ys),
+                                 wp, wn, _stream()), "cct_conv_forward")
+
+
+def cct_conv_backward_data(desc: ConvDesc, w, dy, dx, workspace) -> None:
+    xs, ws_, ys = _shapes(desc)
+    wp, wn = _ws(workspace)
+    _check(_lib.cct_conv_backward_data(ctypes.byref(desc), _ptr(w, "w", ws_), _ptr(dy, "dy", ys),
+                                       _ptr(dx, "dx", xs), wp, wn, _stream()),
+           "cct_conv_backward_data")
+
+
+def cct_conv_backward_weights(desc: ConvDesc, x, dy, dw, dbias, workspace) -> None:
+    xs, ws_, ys = _shapes(desc)
+    wp, wn = _ws(workspace)
+    _check(_lib.cct_conv_backward_weights(ctypes.byref(desc), _ptr(x, "x", xs), _ptr(dy, "dy", ys),
+                                          _ptr(dw, "dw", ws_),
+                                          _ptr(dbias, "dbias", (desc.O,), optional=True), wp, wn,
+                                          _stream()), "cct_conv_backward_weights")
+
+
+def cct_lower(desc: ConvDesc, lowering: int, x, dhat) -> None:
+    xs, _, _ = _shapes(desc)
+    _, cols, _ = cct_lowered_shape(desc, lowering)
+    ld = cct_lowered_ld(desc, lowering)
+    _check(_lib.cct_lower(ctypes.byref(desc), int(lowering), _ptr(x, "x", xs),
+                          _ptr(dhat, "dhat", (desc.groups * cols, ld)), _stream()), "cct_lower")

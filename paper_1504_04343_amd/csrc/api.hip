@@ -1,0 +1,583 @@
+// Host side of libcct.so: argument validation, the per-call plan (lowering geometry,
+// workspace layout, batch chunking), the automatic lowering optimizer and the C ABI entry
+// points.  No device memory is allocated here and nothing synchronises.
+#include <algorithm>
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+
+#include "cct_internal.h"
+
+namespace cct {
+int last_hip_error_value();
+
+namespace {
+
+constexpr long long kAlign = 256;
+constexpr int kIntMax = 2147483647;
+// Default chunk budget for the lowered buffers of one chunk (the caller can pass a larger or
+// smaller workspace to change it).
+constexpr long long kDefaultChunkBytes = 2LL << 30;
+// A layout whose buffers for ONE image exceed this is treated as infeasible.
+constexpr long long kMaxOneImageBytes = 16LL << 30;
+
+inline long long align_up(long long v, long long a) { return (v + a - 1) / a * a; }
+
+bool desc_ok(const cct_conv_desc_t* d) {
+  if (!d) return false;
+  if (d->N <= 0 || d->C <= 0 || d->H <= 0 || d->W <= 0 || d->O <= 0 || d->K <= 0) return false;
+  if (d->stride < 1 || d->pad < 0 || d->groups < 1) return false;
+  if (d->C % d->groups || d->O % d->groups) return false;
+  if ((long long)d->H + 2LL * d->pad < d->K || (long long)d->W + 2LL * d->pad < d->K) return false;
+  if (d->lowering < CCT_LOWER_AUTO || d->lowering > CCT_LOWER_TYPE3) return false;
+  if (d->precision != CCT_PREC_F32 && d->precision != CCT_PREC_BF16_IN_F32_ACC) return false;
+  return true;
+}
+
+// Geometry of one lowering layout for one descriptor.
+struct Geom {
+  int Hout, Wout, Cg, Og;
+  WinMap lower;  // x  <-> D^   (tensor plane H x W)
+  WinMap lift;   // R^ <-> y    (tensor plane Hout x Wout)
+  int RKi, RKj, DKi, DKj;
+  long long Pc;  // matrix columns (positions) per image
+  int Mr;        // rows of R^T per group  = Og*RKi*RKj
+  int Kd;        // rows of D^T per group  = Cg*DKi*DKj
+};
+
+Geom make_geom(const cct_conv_desc_t& d, int type) {
+  Geom g;
+  g.Hout = (d.H + 2 * d.pad - d.K) / d.stride + 1;
+  g.Wout = (d.W + 2 * d.pad - d.K) / d.stride + 1;
+  g.Cg = d.C / d.groups;
+  g.Og = d.O / d.groups;
+  const int K = d.K, s = d.stride, p = d.pad;
+  if (type == CCT_LOWER_TYPE1) {
+    g.lower = WinMap{K, K, s, p, s, p, g.Hout, g.Wout, d.H, d.W};
+    g.lift = WinMap{1, 1, 1, 0, 1, 0, g.Hout, g.Wout, g.Hout, g.Wout};
+    g.RKi = 1; g.RKj = 1; g.DKi = K; g.DKj = K;
+  } else if (type == CCT_LOWER_TYPE2) {
+    g.lower = WinMap{1, K, 1, 0, s, p, d.H, g.Wout, d.H, d.W};
+    g.lift = WinMap{K, 1, s, p, 1, 0, d.H, g.Wout, g.Hout, g.Wout};
+    g.RKi = K; g.RKj = 1; g.DKi = 1; g.DKj = K;
+  } else {
+    g.lower = WinMap{1, 1, 1, 0, 1, 0, d.H, d.W, d.H, d.W};
+    g.lift = WinMap{K, K, s, p, s, p, d.H, d.W, g.Hout, g.Wout};
+    g.RKi = K; g.RKj = K; g.DKi = 1; g.DKj = 1;
+  }
+  g.Pc = (long long)g.lower.Ha * g.lower.Wb;
+  g.Mr = g.Og * g.RKi * g.RKj;
+  g.Kd = g.Cg * g.DKi * g.DKj;
+  return g;
+}
+
+inline int esize(const cct_conv_desc_t& d) { return d.precision == CCT_PREC_BF16_IN_F32_ACC ? 2 : 4; }
+
+// Workspace layout of one pass for a given chunk size.
+struct Layout {
+  long long pack_off = 0, pack_bytes = 0;
+  long long dt_off = 0, dt_bytes = 0;    // D^T (or dD^T)
+  long long rt_off = 0, rt_bytes = 0;    // R^T (or dR^T)
+  long long part_off = 0, part_bytes = 0;
+  long long scratch_off = 0, scratch_bytes = 0;
+  long long total = 0;
+  long long ld = 0;
+  int Mpad = 0, Kpad = 0;  // pack padding (TN GEMM)
+  int S = 1, split_len = 0;  // NT GEMM
+};
+
+constexpr int kDbiasBlocks = 64;
+
+bool make_layout(const cct_conv_desc_t& d, int pass, int type, const Geom& g, long long nc,
+                 Layout* L) {
+  const long long ncols = nc * g.Pc;
+  if (ncols <= 0 || ncols >= kIntMax - 256) return false;
+  if ((long long)d.C * g.DKi * g.DKj >= kIntMax || (long long)d.O * g.RKi * g.RKj >= kIntMax)
+    return false;
+  const int es = esize(d);
+  L->ld = align_up(ncols, 64);
+  long long off = 0;
+  auto take = [&](long long bytes, long long* o, long long* b) {
+    *o = off;
+    *b = bytes;
+    off += align_up(bytes, kAlign);
+  };
+  const long long dt_rows = (long long)d.C * g.DKi * g.DKj;
+  const long long rt_rows = (long long)d.O * g.RKi * g.RKj;
+  if (pass == CCT_PASS_FORWARD) {
+    int BM, BN, BK;
+    gemm_tn_tile(g.Mr, (int)ncols, &BM, &BN, &BK);
+    L->Mpad = (int)align_up(g.Mr, BM);
+    L->Kpad = (int)align_up(g.Kd, BK);
+    take((long long)d.groups * L->Mpad * L->Kpad * es, &L->pack_off, &L->pack_bytes);
+    take(dt_rows * L->ld * es, &L->dt_off, &L->dt_bytes);
+    if (type != CCT_LOWER_TYPE1) take(rt_rows * L->ld * 4, &L->rt_off, &L->rt_bytes);
+  } else if (pass == CCT_PASS_BACKWARD_DATA) {
+    int BM, BN, BK;
+    gemm_tn_tile(g.Kd, (int)ncols, &BM, &BN, &BK);
+    L->Mpad = (int)align_up(g.Kd, BM);
+    L->Kpad = (int)align_up(g.Mr, BK);
+    take((long long)d.groups * L->Mpad * L->Kpad * es, &L->pack_off, &L->pack_bytes);
+    if (type != CCT_LOWER_TYPE1 || es == 2) take(rt_rows * L->ld * es, &L->rt_off, &L->rt_bytes);
+    if (type != CCT_LOWER_TYPE3) take(dt_rows * L->ld * 4, &L->dt_off, &L->dt_bytes);
+  } else {
+    int BM, BN, BK;
+    gemm_nt_tile(g.Mr, g.Kd, &BM, &BN, &BK);
+    take(dt_rows * L->ld * es, &L->dt_off, &L->dt_bytes);
+    if (type != CCT_LOWER_TYPE1 || es == 2) take(rt_rows * L->ld * es, &L->rt_off, &L->rt_bytes);
+    // split the reduction so that about 1024 workgroups exist, partials capped at 256 MiB
+    const long long tiles = (long long)((g.Mr + BM - 1) / BM) * ((g.Kd + BN - 1) / BN) * d.groups;
+    long long S = std::max(1LL, 1024 / std::max(1LL, tiles));
+    const long long out_bytes = (long long)d.groups * g.Mr * g.Kd * 4;
+    S = std::min(S, std::max(1LL, (256LL << 20) / std::max(1LL, out_bytes)));
+    S = std::min(S, (ncols + 4 * BK - 1) / (4 * BK));  // at least 4 k-steps per split
+    S = std::max(1LL, S);
+    long long split_len = align_up((ncols + S - 1) / S, BK);
+    S = (ncols + split_len - 1) / split_len;
+    L->S = (int)S;
+    L->split_len = (int)split_len;
+    take(S * out_bytes, &L->part_off, &L->part_bytes);
+    take((long long)d.O * kDbiasBlocks * 4, &L->scratch_off, &L->scratch_bytes);
+  }
+  L->total = off;
+  return true;
+}
+
+bool type_supported(const cct_conv_desc_t& d, int pass, int type) {
+  if (type < CCT_LOWER_TYPE1 || type > CCT_LOWER_TYPE3) return false;
+  if (d.precision == CCT_PREC_BF16_IN_F32_ACC && pass == CCT_PASS_BACKWARD_WEIGHTS) return false;
+  const Geom g = make_geom(d, type);
+  Layout L;
+  if (!make_layout(d, pass, type, g, 1, &L)) return false;
+  return L.total <= kMaxOneImageBytes;
+}
+
+// ---------------------------------------------------------------------------------------
+// Cost model of the automatic optimizer (Appendix A).  All three layouts do the same useful
+// flops at stride 1; they differ in the bytes the lowering and lifting phases move (the k^2
+// blow-up sits on the d-channel side for Type 1 and on the o-channel side for Type 3) and,
+// at stride > 1, in the extra GEMM work of Types 2/3.  Rates are MI355X measurements of
+// this library's own kernels (sustained streaming rate of the index-map kernels, sustained
+// fp32 MFMA rate of the GEMM at large tiles).
+// ---------------------------------------------------------------------------------------
+constexpr double kStreamBytesPerSec = 3.0e12;
+constexpr double kGemmFlopsPerSec = 90.0e12;
+constexpr double kLaunchSec = 4.0e-6;
+
+double model_cost(const cct_conv_desc_t& d, int pass, int type) {
+  const Geom g = make_geom(d, type);
+  const double es = esize(d);
+  const double N = d.N;
+  const double cols = N * (double)g.Pc;
+  const double x_bytes = 4.0 * N * d.C * d.H * d.W;
+  const double y_bytes = 4.0 * N * d.O * g.Hout * g.Wout;
+  const double dt_elems = (double)d.C * g.DKi * g.DKj * cols;
+  const double rt_elems = (double)d.O * g.RKi * g.RKj * cols;
+  const double gemm_flops = 2.0 * cols * (double)g.Mr * (double)g.Kd * d.groups;
+  // small M or K dimensions run the matrix cores below their sustained rate
+  auto eff = [](double dim) { return std::min(1.0, dim / 128.0); };
+  double bytes = 0.0, launches = 2.0, rate = kGemmFlopsPerSec;
+  if (pass == CCT_PASS_FORWARD) {
+    bytes += x_bytes + dt_elems * es;            // lowering: read x, write D^T
+    bytes += dt_elems * es;                      // GEMM reads D^T
+    if (type == CCT_LOWER_TYPE1) {
+      bytes += y_bytes;                          // epilogue writes y
+    } else {
+      bytes += 2.0 * rt_elems * 4.0 + y_bytes;   // GEMM writes R^T, lift reads it, writes y
+      launches += 1.0;
+    }
+    rate *= eff(g.Mr) * std::min(1.0, std::max(0.25, g.Kd / 64.0));
+  } else if (pass == CCT_PASS_BACKWARD_DATA) {
+    if (type == CCT_LOWER_TYPE1) {
+      bytes += y_bytes;                          // GEMM reads dy in place
+    } else {
+      bytes += y_bytes + 2.0 * rt_elems * es;    // inverse lifting writes dR^T, GEMM reads it
+      launches += 1.0;
+    }
+    if (type == CCT_LOWER_TYPE3) {
+      bytes += x_bytes;                          // epilogue writes dx
+    } else {
+      bytes += 2.0 * dt_elems * 4.0 + x_bytes;   // GEMM writes dD^T, inverse lowering reads it
+      launches += 1.0;
+    }
+    rate *= eff(g.Kd) * std::min(1.0, std::max(0.25, g.Mr / 64.0));
+  } else {
+    bytes += x_bytes + 2.0 * dt_elems * es;      // lowering + GEMM read
+    if (type == CCT_LOWER_TYPE1)
+      bytes += y_bytes;
+    else
+      bytes += y_bytes + 2.0 * rt_elems * es;
+    launches += 2.0;
+    rate *= eff(g.Mr) * eff(g.Kd);
+  }
+  return bytes / kStreamBytesPerSec + gemm_flops / rate + launches * kLaunchSec;
+}
+
+int pick(const cct_conv_desc_t& d, int pass) {
+  if (d.K == 1 && d.stride == 1 && d.pad == 0) return CCT_LOWER_TYPE1;
+  int best = 0;
+  double best_cost = 0.0;
+  for (int t = CCT_LOWER_TYPE1; t <= CCT_LOWER_TYPE3; ++t) {
+    if (!type_supported(d, pass, t)) continue;
+    const double c = model_cost(d, pass, t);
+    if (!best || c < best_cost) {
+      best = t;
+      best_cost = c;
+    }
+  }
+  return best;
+}
+
+// Resolve descriptor -> (type, geometry); returns a CCT_* code.
+int resolve(const cct_conv_desc_t* desc, int pass, int* type, Geom* g) {
+  if (!desc_ok(desc)) return CCT_EINVAL;
+  if (pass < CCT_PASS_FORWARD || pass > CCT_PASS_BACKWARD_WEIGHTS) return CCT_EINVAL;
+  int t = desc->lowering;
+  if (t == CCT_LOWER_AUTO) {
+    t = pick(*desc, pass);
+    if (!t) return CCT_EUNSUPPORTED;
+  } else if (!type_supported(*desc, pass, t)) {
+    return CCT_EUNSUPPORTED;
+  }
+  *type = t;
+  *g = make_geom(*desc, t);
+  return CCT_OK;
+}
+
+long long default_chunk(const cct_conv_desc_t& d, int pass, int type, const Geom& g) {
+  // largest nc <= N whose per-chunk buffers stay within the default budget
+  long long lo = 1, hi = d.N;
+  Layout L;
+  auto fits = [&](long long nc) {
+    return make_layout(d, pass, type, g, nc, &L) && L.total <= kDefaultChunkBytes;
+  };
+  if (fits(hi)) return hi;
+  while (lo < hi) {
+    const long long mid = (lo + hi + 1) / 2;
+    if (fits(mid)) lo = mid; else hi = mid - 1;
+  }
+  return lo;
+}
+
+// Largest chunk whose layout fits `bytes`; 0 if not even one image fits.
+long long chunk_for_workspace(const cct_conv_desc_t& d, int pass, int type, const Geom& g,
+                              size_t bytes, Layout* L) {
+  auto fits = [&](long long nc) {
+    return make_layout(d, pass, type, g, nc, L) && (unsigned long long)L->total <= bytes;
+  };
+  if (!fits(1)) return 0;
+  long long lo = 1, hi = d.N;
+  if (fits(hi)) return hi;
+  while (lo < hi) {
+    const long long mid = (lo + hi + 1) / 2;
+    if (fits(mid)) lo = mid; else hi = mid - 1;
+  }
+  fits(lo);
+  return lo;
+}
+
+PackDesc make_pack(const cct_conv_desc_t& d, const Geom& g, const Layout& L, int transposed) {
+  PackDesc pd;
+  pd.G = d.groups; pd.Og = g.Og; pd.Cg = g.Cg; pd.K = d.K;
+  pd.RKi = g.RKi; pd.RKj = g.RKj; pd.DKi = g.DKi; pd.DKj = g.DKj;
+  pd.Mpad = L.Mpad; pd.Kpad = L.Kpad;
+  pd.transposed = transposed;
+  pd.bf16 = d.precision == CCT_PREC_BF16_IN_F32_ACC;
+  return pd;
+}
+
+const ColMap kPlain = {kIntMax, 0};
+
+}  // namespace
+}  // namespace cct
+
+using namespace cct;
+
+extern "C" {
+
+const char* cct_strerror(int code) {
+  switch (code) {
+    case CCT_OK: return "ok";
+    case CCT_EINVAL: return "invalid argument";
+    case CCT_EWORKSPACE: return "workspace too small for one image";
+    case CCT_EUNSUPPORTED: return "unsupported combination or size";
+    case CCT_EHIP: return "HIP launch failed";
+    default: return "unknown error code";
+  }
+}
+
+int cct_last_hip_error(void) { return last_hip_error_value(); }
+
+int cct_conv_output_dims(const cct_conv_desc_t* desc, int32_t* Hout, int32_t* Wout) {
+  if (!desc_ok(desc) || !Hout || !Wout) return CCT_EINVAL;
+  *Hout = (desc->H + 2 * desc->pad - desc->K) / desc->stride + 1;
+  *Wout = (desc->W + 2 * desc->pad - desc->K) / desc->stride + 1;
+  return CCT_OK;
+}
+
+int cct_lowered_shape(const cct_conv_desc_t* desc, cct_lowering_t lowering, int64_t* rows,
+                      int64_t* cols, int64_t* rcols) {
+  if (!desc_ok(desc) || !rows || !cols || !rcols) return CCT_EINVAL;
+  if (lowering < CCT_LOWER_TYPE1 || lowering > CCT_LOWER_TYPE3) return CCT_EINVAL;
+  const Geom g = make_geom(*desc, lowering);
+  *rows = (int64_t)desc->N * g.Pc;
+  *cols = g.Kd;
+  *rcols = g.Mr;
+  return CCT_OK;
+}
+
+int cct_lowered_ld(const cct_conv_desc_t* desc, cct_lowering_t lowering, int64_t* ld) {
+  if (!desc_ok(desc) || !ld) return CCT_EINVAL;
+  if (lowering < CCT_LOWER_TYPE1 || lowering > CCT_LOWER_TYPE3) return CCT_EINVAL;
+  const Geom g = make_geom(*desc, lowering);
+  const long long ncols = (long long)desc->N * g.Pc;
+  if (ncols >= kIntMax - 256) return CCT_EUNSUPPORTED;
+  *ld = align_up(ncols, 64);
+  return CCT_OK;
+}
+
+int cct_pick_lowering(const cct_conv_desc_t* desc, cct_pass_t pass, cct_lowering_t* picked) {
+  if (!desc_ok(desc) || !picked) return CCT_EINVAL;
+  if (pass < CCT_PASS_FORWARD || pass > CCT_PASS_BACKWARD_WEIGHTS) return CCT_EINVAL;
+  const int t = pick(*desc, pass);
+  if (!t) return CCT_EUNSUPPORTED;
+  *picked = (cct_lowering_t)t;
+  return CCT_OK;
+}
+
+int cct_lowering_cost(const cct_conv_desc_t* desc, cct_pass_t pass, cct_lowering_t lowering,
+                      double* seconds) {
+  if (!desc_ok(desc) || !seconds) return CCT_EINVAL;
+  if (pass < CCT_PASS_FORWARD || pass > CCT_PASS_BACKWARD_WEIGHTS) return CCT_EINVAL;
+  if (lowering < CCT_LOWER_TYPE1 || lowering > CCT_LOWER_TYPE3) return CCT_EINVAL;
+  if (!type_supported(*desc, pass, lowering)) return CCT_EUNSUPPORTED;
+  *seconds = model_cost(*desc, pass, lowering);
+  return CCT_OK;
+}
+
+int cct_conv_workspace_bytes_for_chunk(const cct_conv_desc_t* desc, cct_pass_t pass,
+                                       int32_t images_per_chunk, size_t* bytes) {
+  int type;
+  Geom g;
+  if (!bytes) return CCT_EINVAL;
+  const int rc = resolve(desc, pass, &type, &g);
+  if (rc) return rc;
+  if (images_per_chunk < 1 || images_per_chunk > desc->N) return CCT_EINVAL;
+  Layout L;
+  if (!make_layout(*desc, pass, type, g, images_per_chunk, &L)) return CCT_EUNSUPPORTED;
+  *bytes = (size_t)L.total;
+  return CCT_OK;
+}
+
+int cct_conv_workspace_bytes(const cct_conv_desc_t* desc, cct_pass_t pass, size_t* bytes) {
+  int type;
+  Geom g;
+  if (!bytes) return CCT_EINVAL;
+  const int rc = resolve(desc, pass, &type, &g);
+  if (rc) return rc;
+  const long long nc = default_chunk(*desc, pass, type, g);
+  Layout L;
+  if (!make_layout(*desc, pass, type, g, nc, &L)) return CCT_EUNSUPPORTED;
+  *bytes = (size_t)L.total;
+  return CCT_OK;
+}
+
+int cct_lower(const cct_conv_desc_t* desc, cct_lowering_t lowering, const float* x, float* dhat,
+              void* hip_stream) {
+  if (!desc_ok(desc) || !x || !dhat) return CCT_EINVAL;
+  if (lowering < CCT_LOWER_TYPE1 || lowering > CCT_LOWER_TYPE3) return CCT_EINVAL;
+  const Geom g = make_geom(*desc, lowering);
+  const long long ncols = (long long)desc->N * g.Pc;
+  if (ncols >= kIntMax - 256) return CCT_EUNSUPPORTED;
+  return launch_lower(x, dhat, align_up(ncols, 64), desc->N, desc->C, g.lower, 0,
+                      (hipStream_t)hip_stream);
+}
+
+int cct_conv_forward(const cct_conv_desc_t* desc, const float* x, const float* w, const float* bias,
+                     float* y, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  int type;
+  Geom g;
+  int rc = resolve(desc, CCT_PASS_FORWARD, &type, &g);
+  if (rc) return rc;
+  if (!x || !w || !y || !workspace) return CCT_EINVAL;
+  if (reinterpret_cast<uintptr_t>(workspace) % kAlign) return CCT_EINVAL;
+  const cct_conv_desc_t& d = *desc;
+  Layout L;
+  const long long nc = chunk_for_workspace(d, CCT_PASS_FORWARD, type, g, workspace_bytes, &L);
+  if (nc < 1) return CCT_EWORKSPACE;
+  hipStream_t st = (hipStream_t)hip_stream;
+  char* ws = static_cast<char*>(workspace);
+  const int bf16 = d.precision == CCT_PREC_BF16_IN_F32_ACC;
+  const int es = esize(d);
+  const long long P = (long long)g.Hout * g.Wout;
+
+  rc = launch_pack_kernel_matrix(w, ws + L.pack_off, make_pack(d, g, L, 0), st);
+  if (rc) return rc;
+  for (long long n0 = 0; n0 < d.N; n0 += nc) {
+    const int ni = (int)std::min<long long>(nc, d.N - n0);
+    const long long ncols = (long long)ni * g.Pc;
+    const float* xc = x + n0 * d.C * d.H * d.W;
+    float* yc = y + n0 * d.O * P;
+    rc = launch_lower(xc, ws + L.dt_off, L.ld, ni, d.C, g.lower, bf16, st);
+    if (rc) return rc;
+    GemmTN p;
+    std::memset(&p, 0, sizeof(p));
+    p.A = ws + L.pack_off;
+    p.a_gs = (long long)L.Mpad * L.Kpad;
+    p.Mpad = L.Mpad; p.Kpad = L.Kpad;
+    p.B = ws + L.dt_off;
+    p.b_ks = L.ld; p.b_gs = (long long)g.Kd * L.ld;
+    p.bmap = kPlain;
+    p.b_ld_guard = (int)L.ld;
+    p.M = g.Mr; p.Ncols = (int)ncols; p.Kdim = g.Kd; p.G = d.groups; p.bf16 = bf16;
+    if (type == CCT_LOWER_TYPE1) {
+      // lifting phase of Type 1 (a reshape) + bias fused into the GEMM epilogue
+      p.C = yc;
+      p.c_ms = P; p.c_gs = (long long)g.Og * P;
+      p.cmap = ColMap{(int)P, (long long)d.O * P};
+      p.bias = bias; p.bias_gs = g.Og;
+      rc = launch_gemm_tn(p, st);
+      if (rc) return rc;
+    } else {
+      p.C = reinterpret_cast<float*>(ws + L.rt_off);
+      p.c_ms = L.ld; p.c_gs = (long long)g.Mr * L.ld;
+      p.cmap = kPlain;
+      p.bias = nullptr; p.bias_gs = 0;
+      rc = launch_gemm_tn(p, st);
+      if (rc) return rc;
+      rc = launch_lift(reinterpret_cast<const float*>(ws + L.rt_off), L.ld, yc, bias, ni, d.O,
+                       g.lift, st);
+      if (rc) return rc;
+    }
+  }
+  (void)es;
+  return CCT_OK;
+}
+
+int cct_conv_backward_data(const cct_conv_desc_t* desc, const float* w, const float* dy, float* dx,
+                           void* workspace, size_t workspace_bytes, void* hip_stream) {
+  int type;
+  Geom g;
+  int rc = resolve(desc, CCT_PASS_BACKWARD_DATA, &type, &g);
+  if (rc) return rc;
+  if (!w || !dy || !dx || !workspace) return CCT_EINVAL;
+  if (reinterpret_cast<uintptr_t>(workspace) % kAlign) return CCT_EINVAL;
+  const cct_conv_desc_t& d = *desc;
+  Layout L;
+  const long long nc = chunk_for_workspace(d, CCT_PASS_BACKWARD_DATA, type, g, workspace_bytes, &L);
+  if (nc < 1) return CCT_EWORKSPACE;
+  hipStream_t st = (hipStream_t)hip_stream;
+  char* ws = static_cast<char*>(workspace);
+  const int bf16 = d.precision == CCT_PREC_BF16_IN_F32_ACC;
+  const long long P = (long long)g.Hout * g.Wout;
+  const long long HW = (long long)d.H * d.W;
+
+  rc = launch_pack_kernel_matrix(w, ws + L.pack_off, make_pack(d, g, L, 1), st);
+  if (rc) return rc;
+  for (long long n0 = 0; n0 < d.N; n0 += nc) {
+    const int ni = (int)std::min<long long>(nc, d.N - n0);
+    const long long ncols = (long long)ni * g.Pc;
+    const float* dyc = dy + n0 * d.O * P;
+    float* dxc = dx + n0 * d.C * HW;
+    GemmTN p;
+    std::memset(&p, 0, sizeof(p));
+    p.A = ws + L.pack_off;
+    p.a_gs = (long long)L.Mpad * L.Kpad;
+    p.Mpad = L.Mpad; p.Kpad = L.Kpad;
+    p.M = g.Kd; p.Ncols = (int)ncols; p.Kdim = g.Mr; p.G = d.groups; p.bf16 = bf16;
+    if (L.rt_bytes) {
+      // inverse lifting: spread dy over the rows of dR^T (a copy for Type 1 in bf16 mode)
+      rc = launch_inv_lift(dyc, ws + L.rt_off, L.ld, ni, d.O, g.lift, bf16, st);
+      if (rc) return rc;
+      p.B = ws + L.rt_off;
+      p.b_ks = L.ld; p.b_gs = (long long)g.Mr * L.ld;
+      p.bmap = kPlain;
+      p.b_ld_guard = (int)L.ld;
+    } else {
+      // Type 1: dR^T is dy itself, read in place through the NCHW column map
+      p.B = dyc;
+      p.b_ks = P; p.b_gs = (long long)g.Og * P;
+      p.bmap = ColMap{(int)P, (long long)d.O * P};
+      p.b_ld_guard = 0;
+    }
+    if (type == CCT_LOWER_TYPE3) {
+      // inverse lowering of Type 3 is a reshape: the epilogue writes dx in place
+      p.C = dxc;
+      p.c_ms = HW; p.c_gs = (long long)g.Cg * HW;
+      p.cmap = ColMap{(int)HW, (long long)d.C * HW};
+      rc = launch_gemm_tn(p, st);
+      if (rc) return rc;
+    } else {
+      p.C = reinterpret_cast<float*>(ws + L.dt_off);
+      p.c_ms = L.ld; p.c_gs = (long long)g.Kd * L.ld;
+      p.cmap = kPlain;
+      rc = launch_gemm_tn(p, st);
+      if (rc) return rc;
+      rc = launch_inv_lower(reinterpret_cast<const float*>(ws + L.dt_off), L.ld, dxc, ni, d.C,
+                            g.lower, st);
+      if (rc) return rc;
+    }
+  }
+  return CCT_OK;
+}
+
+int cct_conv_backward_weights(const cct_conv_desc_t* desc, const float* x, const float* dy, float* dw,
+                              float* dbias, void* workspace, size_t workspace_bytes,
+                              void* hip_stream) {
+  int type;
+  Geom g;
+  int rc = resolve(desc, CCT_PASS_BACKWARD_WEIGHTS, &type, &g);
+  if (rc) return rc;
+  if (!x || !dy || !dw || !workspace) return CCT_EINVAL;
+  if (reinterpret_cast<uintptr_t>(workspace) % kAlign) return CCT_EINVAL;
+  const cct_conv_desc_t& d = *desc;
+  Layout L;
+  const long long nc =
+      chunk_for_workspace(d, CCT_PASS_BACKWARD_WEIGHTS, type, g, workspace_bytes, &L);
+  if (nc < 1) return CCT_EWORKSPACE;
+  hipStream_t st = (hipStream_t)hip_stream;
+  char* ws = static_cast<char*>(workspace);
+  const int bf16 = d.precision == CCT_PREC_BF16_IN_F32_ACC;
+  const long long P = (long long)g.Hout * g.Wout;
+  const PackDesc pd = make_pack(d, g, L, 0);
+
+  int chunk = 0;
+  for (long long n0 = 0; n0 < d.N; n0 += nc, ++chunk) {
+    const int ni = (int)std::min<long long>(nc, d.N - n0);
+    const long long ncols = (long long)ni * g.Pc;
+    const float* xc = x + n0 * d.C * d.H * d.W;
+    const float* dyc = dy + n0 * d.O * P;
+    rc = launch_lower(xc, ws + L.dt_off, L.ld, ni, d.C, g.lower, bf16, st);
+    if (rc) return rc;
+    GemmNT p;
+    std::memset(&p, 0, sizeof(p));
+    if (L.rt_bytes) {
+      rc = launch_inv_lift(dyc, ws + L.rt_off, L.ld, ni, d.O, g.lift, bf16, st);
+      if (rc) return rc;
+      p.A = ws + L.rt_off;
+      p.a_ms = L.ld; p.a_gs = (long long)g.Mr * L.ld;
+      p.amap = kPlain;
+    } else {
+      p.A = dyc;
+      p.a_ms = P; p.a_gs = (long long)g.Og * P;
+      p.amap = ColMap{(int)P, (long long)d.O * P};
+    }
+    p.B = ws + L.dt_off;
+    p.b_ns = L.ld; p.b_gs = (long long)g.Kd * L.ld;
+    p.Cpart = reinterpret_cast<float*>(ws + L.part_off);
+    p.M = g.Mr; p.N = g.Kd; p.Ncols = (int)ncols;
+    p.G = d.groups; p.S = L.S; p.split_len = L.split_len; p.bf16 = bf16;
+    rc = launch_gemm_nt(p, st);
+    if (rc) return rc;
+    rc = launch_reduce_dw(p.Cpart, dw, L.S, pd, chunk > 0, st);
+    if (rc) return rc;
+  }
+  if (dbias) {
+    rc = launch_dbias(dy, dbias, reinterpret_cast<float*>(ws + L.scratch_off), d.N, d.O, (int)P,
+                      kDbiasBlocks, st);
+    if (rc) return rc;
+  }
+  return CCT_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,123 @@
+// Internal declarations shared by the translation units of libcct.so.
+// Nothing here is part of the C ABI (see include/cct.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "cct.h"
+
+namespace cct {
+
+// ---------------------------------------------------------------------------------------
+// Window map.  All three lowerings (Sec. 2.1) and their liftings are the same gather with
+// different parameters: a matrix column is (image n, grid row a, grid col b) over a grid
+// of Ha x Wb positions per image, a matrix row is (channel, tap i < Ki, tap j < Kj), and the
+// tensor pixel that belongs to them is
+//        h = a*sh + i - ph,      w = b*sw + j - pw
+// in a tensor of Ht x Wt pixels per (image, channel).
+//   lowering of x   : Type 1 (K,K,s,p,s,p) on the Hout x Wout grid; Type 2 (1,K,1,0,s,p) on
+//                     H x Wout; Type 3 (1,1,1,0,1,0) on H x W; tensor = x (H x W).
+//   lifting  to y   : the same formula read the other way: the tensor is the a/b grid of R^
+//                     and the "pixel" is the output position; see LiftMap.
+// ---------------------------------------------------------------------------------------
+struct WinMap {
+  int Ki, Kj;          // taps that index matrix rows
+  int sh, ph, sw, pw;  // stride / pad per axis
+  int Ha, Wb;          // grid of matrix columns per image
+  int Ht, Wt;          // tensor plane size
+};
+
+// Column -> memory offset map used by the GEMM kernels so that they can read and write
+// NCHW tensors in place: off(col) = (col / P) * img_stride + (col % P).
+// A plain matrix row uses P = INT32_MAX, img_stride = 0.
+struct ColMap {
+  int P;
+  long long img_stride;
+};
+
+// C[m][col] = sum_k Apack[k][m] * B(k, col) (+ bias[m]); one launch covers all groups.
+struct GemmTN {
+  const void* A;       // packed operand [G][Kpad][Mpad], zero padded (fp32 or bf16)
+  long long a_gs;      // elements between groups
+  int Mpad, Kpad;
+  const void* B;       // [.. k ..][cols] rows of stride b_ks (fp32 or bf16)
+  long long b_ks, b_gs;
+  ColMap bmap;
+  int b_ld_guard;      // vector path: columns >= this are not read
+  float* C;
+  long long c_ms, c_gs;
+  ColMap cmap;
+  const float* bias;   // nullable; bias[g*bias_gs + m]
+  int bias_gs;
+  int M, Ncols, Kdim;  // true sizes per group
+  int G;
+  int bf16;            // operands are bf16 (A packed bf16, B bf16 plain rows)
+};
+
+// Cpart[s][g][m][n] = sum_{col in split s} A(m, col) * B(n, col); both operands col-contiguous.
+struct GemmNT {
+  const void* A;       // rows m: a_ms apart, groups a_gs apart, columns through amap
+  long long a_ms, a_gs;
+  ColMap amap;
+  const void* B;       // plain rows n of stride b_ns, groups b_gs apart
+  long long b_ns, b_gs;
+  float* Cpart;        // [S][G][M][N] compact
+  int M, N, Ncols;
+  int G, S, split_len; // split_len is a multiple of the kernel's BK
+  int bf16;
+};
+
+int launch_gemm_tn(const GemmTN& p, hipStream_t st);
+int launch_gemm_nt(const GemmNT& p, hipStream_t st);
+// Tile sizes the launchers will use for a problem (so that the planner can pad the packs).
+void gemm_tn_tile(int M, int Ncols, int* BM, int* BN, int* BK);
+void gemm_nt_tile(int M, int N, int* BM, int* BN, int* BK);
+
+// ---- index-map kernels (lowering / lifting and their adjoints) -----------------------------
+// dt[(ch*Ki+i)*Kj+j][col] = x[n, ch, h, w] or +0; col = n*Ha*Wb + a*Wb + b, n < nimg.
+int launch_lower(const float* x, void* dt, long long ld, int nimg, int C, const WinMap& m,
+                 int bf16, hipStream_t st);
+// y[n,o,r,c] = bias[o] + sum_{i,j} rt[(o*Ki+i)*Kj+j][n*Ha*Wb + a*Wb + b], a = r*sh+i-ph, b = c*sw+j-pw.
+// Here (Ht, Wt) of the map is the output plane (Hout x Wout).
+int launch_lift(const float* rt, long long ld, float* y, const float* bias, int nimg, int O,
+                const WinMap& m, hipStream_t st);
+// Adjoint of lift: drt[(o*Ki+i)*Kj+j][col] = dy[n,o,r,c] if a = r*sh+i-ph, b = c*sw+j-pw has a
+// solution (r,c) inside the Ht x Wt plane, else +0.
+int launch_inv_lift(const float* dy, void* drt, long long ld, int nimg, int O, const WinMap& m,
+                    int bf16, hipStream_t st);
+// Adjoint of lower: dx[n,ch,h,w] = sum_{i,j} ddt[(ch*Ki+i)*Kj+j][n*Ha*Wb + a*Wb + b] over the
+// (i,j) for which h = a*sh+i-ph, w = b*sw+j-pw has a solution (a,b) inside the grid.
+int launch_inv_lower(const float* ddt, long long ld, float* dx, int nimg, int C, const WinMap& m,
+                     hipStream_t st);
+
+// Lowered-kernel pack.  rho = (oo, iR, jR) indexes R^ columns, delta = (ci, iD, jD) indexes D^
+// columns; K^[delta][rho] = w[q*Og+oo, ci, i, j] with (i,j) taken from whichever side carries it.
+// transposed == 0: pack[q][k = delta][m = rho] (forward);  1: pack[q][k = rho][m = delta].
+struct PackDesc {
+  int G, Og, Cg, K;
+  int RKi, RKj, DKi, DKj;  // taps carried on the R^ side / D^ side (product = K*K)
+  int Mpad, Kpad;
+  int transposed;
+  int bf16;
+};
+int launch_pack_kernel_matrix(const float* w, void* pack, const PackDesc& d, hipStream_t st);
+// dw[o,ci,i,j] = (accumulate ? dw : 0) + sum_s part[s][q][rho][delta]
+int launch_reduce_dw(const float* part, float* dw, int S, const PackDesc& d, int accumulate,
+                     hipStream_t st);
+// dbias[o] = sum_{n,r,c} dy[n,o,r,c]; `scratch` holds O*nblk floats.
+int launch_dbias(const float* dy, float* dbias, float* scratch, int N, int O, int P, int nblk,
+                 hipStream_t st);
+
+void set_hip_error(hipError_t e);
+
+#define CCT_CHECK_LAUNCH()                       \
+  do {                                           \
+    hipError_t e__ = hipGetLastError();          \
+    if (e__ != hipSuccess) {                     \
+      ::cct::set_hip_error(e__);                 \
+      return CCT_EHIP;                           \
+    }                                            \
+  } while (0)
+
+}  // namespace cct

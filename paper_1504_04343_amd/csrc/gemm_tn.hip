@@ -1,0 +1,404 @@
+// Multiply phase (Sec. 2.1): R^ = D^ K^ on the gfx950 matrix cores.
+//
+// The library keeps D^ transposed ("K-major": one row per patch element, one column per
+// position of the whole chunk of images), so the product is computed as
+//     C[m][col] = sum_k Apack[k][m] * B[k][col]          (m: kernels, col: positions)
+// with both operands K-major.  C columns (and, for the backward-data pass, B columns) can be
+// mapped straight onto an NCHW tensor through a ColMap, which turns the Type-1 lifting
+// phase + bias add into the GEMM epilogue.
+//
+// Tiling: 256 threads = 4 waves; the workgroup owns a BM x BN tile of C, each wave a
+// (32*WM) x (32*WN) sub-tile built from v_mfma_f32_32x32x2_f32 (fp32) or
+// v_mfma_f32_32x32x8_bf16_1k (bf16 operands) with fp32 accumulators.  K is walked in steps
+// of BK through a double-buffered LDS stage; the global loads of step t+1 are issued before
+// the MFMAs of step t.
+#include "cct_internal.h"
+
+namespace cct {
+namespace {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef short shortx4 __attribute__((ext_vector_type(4)));
+
+constexpr int NT = 256;
+
+__device__ __forceinline__ long long col_offset(const ColMap& cm, int col) {
+  const int n = col / cm.P;
+  return (long long)n * cm.img_stride + (col - n * cm.P);
+}
+
+// fp32 kernel.  BVEC: B rows are plain, 16-byte aligned rows -> float4 loads.
+template <int BM, int BN, int BK, int WM, int WN, bool BVEC>
+__global__ __launch_bounds__(NT) void gemm_tn_f32(GemmTN p, int tiles_m, int tiles_n) {
+  constexpr int WAVES_N = BN / (32 * WN);
+  constexpr int WAVES_M = BM / (32 * WM);
+  static_assert(WAVES_M * WAVES_N == 4, "4 waves per workgroup");
+  constexpr int A_VECS = BK * BM / 4;
+  constexpr int A_IT = (A_VECS + NT - 1) / NT;
+  constexpr int B_VECS = BK * BN / 4;
+  constexpr int B_IT = (B_VECS + NT - 1) / NT;
+  constexpr int B_SC_IT = BK * BN / NT;  // scalar path: loads per thread
+  constexpr int B_KSTEP = NT / BN;       // scalar path: k rows covered per pass
+  static_assert(NT % BN == 0 || BVEC, "scalar B path needs BN | 256");
+
+  __shared__ __attribute__((aligned(16))) float As[2][BK][BM];
+  __shared__ __attribute__((aligned(16))) float Bs[2][BK][BN];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int wave_m = wave / WAVES_N, wave_n = wave % WAVES_N;
+
+  // Tile order: consecutive workgroup ids go round-robin over the 8 XCDs, so give each XCD a
+  // contiguous run of column tiles and let the M tiles of one column tile follow each other on
+  // the same XCD: the B tile they share is then fetched from HBM once per XCD L2.
+  int bid = blockIdx.x;
+  const int total = tiles_m * tiles_n;
+  {
+    const int xcd = bid & 7, slot = bid >> 3;
+    const int per = (total + 7) >> 3;
+    const int lin = xcd * per + slot;
+    // when total is not a multiple of 8 the tail would fall outside; fall back to identity there
+    bid = (total % 8 == 0) ? lin : bid;
+  }
+  const int tile_n = bid / tiles_m;
+  const int tile_m = bid - tile_n * tiles_m;
+  const int g = blockIdx.y;
+  const int m0 = tile_m * BM;
+  const int n0 = tile_n * BN;
+
+  const float* __restrict__ A = reinterpret_cast<const float*>(p.A) + (long long)g * p.a_gs + m0;
+  const float* __restrict__ B = reinterpret_cast<const float*>(p.B) + (long long)g * p.b_gs;
+
+  // per-thread source coordinates of the global->LDS copies
+  long long b_off = 0;  // scalar path: offset of this thread's column
+  bool b_ok = false;
+  int b_k0 = 0, b_n = 0;
+  if (!BVEC) {
+    b_n = tid % BN;
+    b_k0 = tid / BN;
+    const int col = n0 + b_n;
+    b_ok = col < p.Ncols;
+    b_off = b_ok ? col_offset(p.bmap, col) : 0;
+  }
+
+  float4 ra[A_IT];
+  float4 rbv[BVEC ? B_IT : 1];
+  float rbs[BVEC ? 1 : B_SC_IT];
+
+  auto load_tile = [&](int k0) {
+#pragma unroll
+    for (int it = 0; it < A_IT; ++it) {
+      const int v = tid + it * NT;
+      if (A_VECS % NT == 0 || v < A_VECS) {
+        const int k = v / (BM / 4), m4 = v % (BM / 4);
+        ra[it] = *reinterpret_cast<const float4*>(A + (long long)(k0 + k) * p.Mpad + m4 * 4);
+      }
+    }
+    if (BVEC) {
+#pragma unroll
+      for (int it = 0; it < B_IT; ++it) {
+        const int v = tid + it * NT;
+        const int k = v / (BN / 4), n4 = v % (BN / 4);
+        const int col = n0 + n4 * 4;
+        float4 val = make_float4(0.f, 0.f, 0.f, 0.f);
+        if ((B_VECS % NT == 0 || v < B_VECS) && (k0 + k) < p.Kdim && col < p.b_ld_guard)
+          val = *reinterpret_cast<const float4*>(B + (long long)(k0 + k) * p.b_ks + col);
+        rbv[it] = val;
+      }
+    } else {
+#pragma unroll
+      for (int it = 0; it < B_SC_IT; ++it) {
+        const int k = k0 + b_k0 + it * B_KSTEP;
+        float val = 0.f;
+        if (b_ok && k < p.Kdim) val = B[(long long)k * p.b_ks + b_off];
+        rbs[it] = val;
+      }
+    }
+  };
+
+  auto store_tile = [&](int buf) {
+#pragma unroll
+    for (int it = 0; it < A_IT; ++it) {
+      const int v = tid + it * NT;
+      if (A_VECS % NT == 0 || v < A_VECS) {
+        const int k = v / (BM / 4), m4 = v % (BM / 4);
+        *reinterpret_cast<float4*>(&As[buf][k][m4 * 4]) = ra[it];
+      }
+    }
+    if (BVEC) {
+#pragma unroll
+      for (int it = 0; it < B_IT; ++it) {
+        const int v = tid + it * NT;
+        if (B_VECS % NT == 0 || v < B_VECS) {
+          const int k = v / (BN / 4), n4 = v % (BN / 4);
+          *reinterpret_cast<float4*>(&Bs[buf][k][n4 * 4]) = rbv[it];
+        }
+      }
+    } else {
+#pragma unroll
+      for (int it = 0; it < B_SC_IT; ++it) Bs[buf][b_k0 + it * B_KSTEP][b_n] = rbs[it];
+    }
+  };
+
+  floatx16 acc[WM][WN];
+#pragma unroll
+  for (int i = 0; i < WM; ++i)
+#pragma unroll
+    for (int j = 0; j < WN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  const int lane_lo = lane & 31, lane_hi = lane >> 5;
+  const int am = wave_m * WM * 32 + lane_lo;
+  const int bn = wave_n * WN * 32 + lane_lo;
+
+  const int ktiles = p.Kpad / BK;
+  load_tile(0);
+  store_tile(0);
+  __syncthreads();
+  for (int t = 0; t < ktiles; ++t) {
+    const int buf = t & 1;
+    if (t + 1 < ktiles) load_tile((t + 1) * BK);
+#pragma unroll
+    for (int kk = 0; kk < BK; kk += 2) {
+      float a[WM], b[WN];
+#pragma unroll
+      for (int i = 0; i < WM; ++i) a[i] = As[buf][kk + lane_hi][am + i * 32];
+#pragma unroll
+      for (int j = 0; j < WN; ++j) b[j] = Bs[buf][kk + lane_hi][bn + j * 32];
+#pragma unroll
+      for (int i = 0; i < WM; ++i)
+#pragma unroll
+        for (int j = 0; j < WN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
+    }
+    if (t + 1 < ktiles) store_tile(buf ^ 1);
+    __syncthreads();
+  }
+
+  // Epilogue: lifting (Type 1) / plain store, + bias.  In the 32x32 accumulator lane l holds
+  // column l%32 and rows 8*(r/4) + 4*(l/32) + r%4 for r = 0..15.
+  float* __restrict__ C = p.C + (long long)g * p.c_gs;
+  const float* bias = p.bias ? p.bias + (long long)g * p.bias_gs : nullptr;
+#pragma unroll
+  for (int j = 0; j < WN; ++j) {
+    const int col = n0 + bn + j * 32;
+    if (col >= p.Ncols) continue;
+    const long long coff = col_offset(p.cmap, col);
+#pragma unroll
+    for (int i = 0; i < WM; ++i) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m = m0 + wave_m * WM * 32 + i * 32 + (r >> 2) * 8 + lane_hi * 4 + (r & 3);
+        if (m < p.M) {
+          float v = acc[i][j][r];
+          if (bias) v += bias[m];
+          C[(long long)m * p.c_ms + coff] = v;
+        }
+      }
+    }
+  }
+}
+
+// bf16 operands (A packed bf16, B plain bf16 rows), fp32 accumulate.
+// v_mfma_f32_32x32x8_bf16_1k: each lane supplies 4 consecutive k of its row/column; lanes
+// 32..63 supply k+4..k+7.
+template <int BM, int BN, int BK, int WM, int WN>
+__global__ __launch_bounds__(NT) void gemm_tn_bf16(GemmTN p, int tiles_m, int tiles_n) {
+  constexpr int WAVES_N = BN / (32 * WN);
+  constexpr int WAVES_M = BM / (32 * WM);
+  static_assert(WAVES_M * WAVES_N == 4, "4 waves per workgroup");
+  static_assert(BK % 8 == 0, "BK multiple of 8");
+  // 8 bf16 = 16 bytes per vector load
+  constexpr int A_VECS = BK * BM / 8;
+  constexpr int A_IT = (A_VECS + NT - 1) / NT;
+  constexpr int B_VECS = BK * BN / 8;
+  constexpr int B_IT = (B_VECS + NT - 1) / NT;
+
+  __shared__ __attribute__((aligned(16))) unsigned short As[2][BK][BM];
+  __shared__ __attribute__((aligned(16))) unsigned short Bs[2][BK][BN];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int wave_m = wave / WAVES_N, wave_n = wave % WAVES_N;
+  const int bid = blockIdx.x;
+  const int tile_n = bid / tiles_m;
+  const int tile_m = bid - tile_n * tiles_m;
+  const int g = blockIdx.y;
+  const int m0 = tile_m * BM;
+  const int n0 = tile_n * BN;
+
+  const unsigned short* __restrict__ A =
+      reinterpret_cast<const unsigned short*>(p.A) + (long long)g * p.a_gs + m0;
+  const unsigned short* __restrict__ B =
+      reinterpret_cast<const unsigned short*>(p.B) + (long long)g * p.b_gs;
+
+  uint4 ra[A_IT], rb[B_IT];
+  auto load_tile = [&](int k0) {
+#pragma unroll
+    for (int it = 0; it < A_IT; ++it) {
+      const int v = tid + it * NT;
+      if (A_VECS % NT == 0 || v < A_VECS) {
+        const int k = v / (BM / 8), m8 = v % (BM / 8);
+        ra[it] = *reinterpret_cast<const uint4*>(A + (long long)(k0 + k) * p.Mpad + m8 * 8);
+      }
+    }
+#pragma unroll
+    for (int it = 0; it < B_IT; ++it) {
+      const int v = tid + it * NT;
+      const int k = v / (BN / 8), n8 = v % (BN / 8);
+      const int col = n0 + n8 * 8;
+      uint4 val = make_uint4(0, 0, 0, 0);
+      if ((B_VECS % NT == 0 || v < B_VECS) && (k0 + k) < p.Kdim && col < p.b_ld_guard)
+        val = *reinterpret_cast<const uint4*>(B + (long long)(k0 + k) * p.b_ks + col);
+      rb[it] = val;
+    }
+  };
+  auto store_tile = [&](int buf) {
+#pragma unroll
+    for (int it = 0; it < A_IT; ++it) {
+      const int v = tid + it * NT;
+      if (A_VECS % NT == 0 || v < A_VECS) {
+        const int k = v / (BM / 8), m8 = v % (BM / 8);
+        *reinterpret_cast<uint4*>(&As[buf][k][m8 * 8]) = ra[it];
+      }
+    }
+#pragma unroll
+    for (int it = 0; it < B_IT; ++it) {
+      const int v = tid + it * NT;
+      if (B_VECS % NT == 0 || v < B_VECS) {
+        const int k = v / (BN / 8), n8 = v % (BN / 8);
+        *reinterpret_cast<uint4*>(&Bs[buf][k][n8 * 8]) = rb[it];
+      }
+    }
+  };
+
+  floatx16 acc[WM][WN];
+#pragma unroll
+  for (int i = 0; i < WM; ++i)
+#pragma unroll
+    for (int j = 0; j < WN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  const int lane_lo = lane & 31, lane_hi = lane >> 5;
+  const int am = wave_m * WM * 32 + lane_lo;
+  const int bn = wave_n * WN * 32 + lane_lo;
+
+  const int ktiles = p.Kpad / BK;
+  load_tile(0);
+  store_tile(0);
+  __syncthreads();
+  for (int t = 0; t < ktiles; ++t) {
+    const int buf = t & 1;
+    if (t + 1 < ktiles) load_tile((t + 1) * BK);
+#pragma unroll
+    for (int kk = 0; kk < BK; kk += 8) {
+      shortx4 a[WM], b[WN];
+      const int kb = kk + lane_hi * 4;
+#pragma unroll
+      for (int i = 0; i < WM; ++i)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) a[i][e] = (short)As[buf][kb + e][am + i * 32];
+#pragma unroll
+      for (int j = 0; j < WN; ++j)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) b[j][e] = (short)Bs[buf][kb + e][bn + j * 32];
+#pragma unroll
+      for (int i = 0; i < WM; ++i)
+#pragma unroll
+        for (int j = 0; j < WN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(a[i], b[j], acc[i][j], 0, 0, 0);
+    }
+    if (t + 1 < ktiles) store_tile(buf ^ 1);
+    __syncthreads();
+  }
+
+  float* __restrict__ C = p.C + (long long)g * p.c_gs;
+  const float* bias = p.bias ? p.bias + (long long)g * p.bias_gs : nullptr;
+#pragma unroll
+  for (int j = 0; j < WN; ++j) {
+    const int col = n0 + bn + j * 32;
+    if (col >= p.Ncols) continue;
+    const long long coff = col_offset(p.cmap, col);
+#pragma unroll
+    for (int i = 0; i < WM; ++i) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m = m0 + wave_m * WM * 32 + i * 32 + (r >> 2) * 8 + lane_hi * 4 + (r & 3);
+        if (m < p.M) {
+          float v = acc[i][j][r];
+          if (bias) v += bias[m];
+          C[(long long)m * p.c_ms + coff] = v;
+        }
+      }
+    }
+  }
+}
+
+template <int BM, int BN, int BK, int WM, int WN>
+int launch_f32(const GemmTN& p, hipStream_t st) {
+  const int tiles_m = p.Mpad / BM;
+  const int tiles_n = (p.Ncols + BN - 1) / BN;
+  const long long blocks = (long long)tiles_m * tiles_n;
+  if (blocks <= 0 || blocks >= 2147483647LL || p.G > 65535) return CCT_EUNSUPPORTED;
+  const bool plainB = p.bmap.P == 2147483647;
+  const bool vec = plainB && (p.b_ks % 4 == 0) && (p.b_gs % 4 == 0) &&
+                   (reinterpret_cast<uintptr_t>(p.B) % 16 == 0);
+  dim3 grid((unsigned)blocks, (unsigned)p.G);
+  if (vec)
+    hipLaunchKernelGGL((gemm_tn_f32<BM, BN, BK, WM, WN, true>), grid, dim3(NT), 0, st, p, tiles_m,
+                       tiles_n);
+  else
+    hipLaunchKernelGGL((gemm_tn_f32<BM, BN, BK, WM, WN, false>), grid, dim3(NT), 0, st, p, tiles_m,
+                       tiles_n);
+  CCT_CHECK_LAUNCH();
+  return CCT_OK;
+}
+
+template <int BM, int BN, int BK, int WM, int WN>
+int launch_bf16(const GemmTN& p, hipStream_t st) {
+  const int tiles_m = p.Mpad / BM;
+  const int tiles_n = (p.Ncols + BN - 1) / BN;
+  const long long blocks = (long long)tiles_m * tiles_n;
+  if (blocks <= 0 || blocks >= 2147483647LL || p.G > 65535) return CCT_EUNSUPPORTED;
+  const bool plainB = p.bmap.P == 2147483647;
+  if (!plainB || p.b_ks % 8 || p.b_gs % 8 || reinterpret_cast<uintptr_t>(p.B) % 16)
+    return CCT_EUNSUPPORTED;
+  dim3 grid((unsigned)blocks, (unsigned)p.G);
+  hipLaunchKernelGGL((gemm_tn_bf16<BM, BN, BK, WM, WN>), grid, dim3(NT), 0, st, p, tiles_m, tiles_n);
+  CCT_CHECK_LAUNCH();
+  return CCT_OK;
+}
+
+}  // namespace
+
+// One tile family for now: M tiles of 64, 96 or 128 rows by 128 columns.
+void gemm_tn_tile(int M, int /*Ncols*/, int* BM, int* BN, int* BK) {
+  *BN = 128;
+  *BK = 16;
+  if (M <= 64)
+    *BM = 64;
+  else if (M % 128 != 0 && M % 96 == 0)
+    *BM = 96;
+  else
+    *BM = 128;
+}
+
+int launch_gemm_tn(const GemmTN& p, hipStream_t st) {
+  int BM, BN, BK;
+  gemm_tn_tile(p.M, p.Ncols, &BM, &BN, &BK);
+  if (p.Mpad % BM || p.Kpad % BK || p.Mpad < p.M || p.Kpad < p.Kdim) return CCT_EINVAL;
+  if (p.bf16) {
+    if (BM == 64) return launch_bf16<64, 128, 16, 1, 2>(p, st);
+    if (BM == 96) return launch_bf16<96, 128, 16, 3, 1>(p, st);
+    return launch_bf16<128, 128, 16, 2, 2>(p, st);
+  }
+  if (BM == 64) return launch_f32<64, 128, 16, 1, 2>(p, st);
+  if (BM == 96) return launch_f32<96, 128, 16, 3, 1>(p, st);
+  return launch_f32<128, 128, 16, 2, 2>(p, st);
+}
+
+}  // namespace cct

@@ -1,0 +1,155 @@
+"""Host-side checks of libcct.so that need no GPU: the library loads, exports every symbol the
+header declares, validates arguments, and its shape/selector functions obey what the paper fixes."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_1504_04343_amd import binding
+    return binding
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "cct.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(cct_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol(B):
+    names = declared_functions()
+    assert len(names) >= 12
+    lib = ctypes.CDLL(B.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(B.EXPORTS) == names
+
+
+def test_strerror(B):
+    assert B.strerror(0) == "ok"
+    for code in (B.EINVAL, B.EWORKSPACE, B.EUNSUPPORTED, B.EHIP, -99):
+        assert B.strerror(code)
+
+
+def test_output_dims_and_lowered_shapes_match_golden(B):
+    path = os.path.join(ROOT, "tests", "golden", "caffenet_shapes.txt")
+    for line in open(path):
+        if line.startswith("#") or not line.strip():
+            continue
+        f = line.split()
+        C, H, O, K, s, p, g, hout = map(int, f[1:9])
+        want = list(map(int, f[9:15]))
+        N = 256
+        d = B.make_desc(N, C, H, H, O, K, s, p, g)
+        assert B.cct_conv_output_dims(d) == (hout, hout)
+        got = []
+        for t in (1, 2, 3):
+            rows, cols, rcols = B.cct_lowered_shape(d, t)
+            assert rows % N == 0                      # Sec. 2.2: b times larger
+            got += [rows // N, cols]
+            assert rcols == (O // g) * K ** (t - 1)
+            assert B.cct_lowered_ld(d, t) >= rows and B.cct_lowered_ld(d, t) % 64 == 0
+        assert got == want
+
+
+BAD = [
+    dict(N=0), dict(C=0), dict(H=0), dict(O=0), dict(K=0), dict(stride=0), dict(pad=-1),
+    dict(groups=0), dict(groups=4), dict(K=40), dict(lowering=7), dict(precision=5),
+]
+
+
+@pytest.mark.parametrize("bad", BAD)
+def test_invalid_descriptors_are_rejected_everywhere(B, bad):
+    base = dict(N=2, C=6, H=9, W=9, O=6, K=3, stride=1, pad=1, groups=2, lowering=0, precision=0)
+    base.update(bad)
+    d = B.make_desc(**base)
+    with pytest.raises(B.CctError) as e:
+        B.cct_conv_output_dims(d)
+    assert e.value.code == B.EINVAL
+    with pytest.raises(B.CctError):
+        B.cct_conv_workspace_bytes(d, B.PASS_FORWARD)
+    with pytest.raises(B.CctError):
+        B.cct_pick_lowering(d, B.PASS_FORWARD)
+    # device entry points validate before touching anything: null pointers, no launch
+    lib = ctypes.CDLL(B.LIB_PATH)
+    assert lib.cct_conv_forward(ctypes.byref(d), None, None, None, None, None, ctypes.c_size_t(0),
+                                None) == B.EINVAL
+
+
+def test_null_pointers_and_bad_pass(B):
+    lib = ctypes.CDLL(B.LIB_PATH)
+    d = B.make_desc(2, 4, 8, 8, 4, 3, 1, 1, 1)
+    z = ctypes.c_size_t(1 << 20)
+    assert lib.cct_conv_forward(ctypes.byref(d), None, None, None, None, None, z, None) == B.EINVAL
+    assert lib.cct_conv_backward_data(ctypes.byref(d), None, None, None, None, z, None) == B.EINVAL
+    assert lib.cct_conv_backward_weights(ctypes.byref(d), None, None, None, None, None, z,
+                                         None) == B.EINVAL
+    assert lib.cct_lower(ctypes.byref(d), 1, None, None, None) == B.EINVAL
+    assert lib.cct_conv_output_dims(None, None, None) == B.EINVAL
+    out = ctypes.c_size_t()
+    assert lib.cct_conv_workspace_bytes(ctypes.byref(d), 9, ctypes.byref(out)) == B.EINVAL
+    assert lib.cct_conv_workspace_bytes_for_chunk(ctypes.byref(d), 0, 0, ctypes.byref(out)) == B.EINVAL
+    assert lib.cct_conv_workspace_bytes_for_chunk(ctypes.byref(d), 0, 3, ctypes.byref(out)) == B.EINVAL
+
+
+def test_workspace_too_small_and_misaligned(B):
+    lib = ctypes.CDLL(B.LIB_PATH)
+    d = B.make_desc(2, 4, 8, 8, 4, 3, 1, 1, 1, lowering=B.LOWER_TYPE1)
+    fake = ctypes.c_void_p(0x10000)        # never dereferenced: the call fails before any launch
+    assert lib.cct_conv_forward(ctypes.byref(d), fake, fake, None, fake, fake, ctypes.c_size_t(16),
+                                None) == B.EWORKSPACE
+    odd = ctypes.c_void_p(0x10004)
+    assert lib.cct_conv_forward(ctypes.byref(d), fake, fake, None, fake, odd,
+                                ctypes.c_size_t(1 << 30), None) == B.EINVAL
+
+
+def test_workspace_grows_linearly_with_chunk(B):
+    # Sec. 2.2: memory footprint of the lowered matrix is proportional to the batch it holds
+    d = B.make_desc(256, 96, 27, 27, 256, 5, 1, 2, 2, lowering=B.LOWER_TYPE1)
+    b1 = B.cct_conv_workspace_bytes_for_chunk(d, B.PASS_FORWARD, 64)
+    b2 = B.cct_conv_workspace_bytes_for_chunk(d, B.PASS_FORWARD, 128)
+    b4 = B.cct_conv_workspace_bytes_for_chunk(d, B.PASS_FORWARD, 256)
+    assert abs((b4 - b2) - 2 * (b2 - b1)) <= 4096
+    assert b4 >= 256 * 729 * 2400 * 4                 # holds the whole Type-1 lowered matrix
+    assert B.cct_conv_workspace_bytes(d, B.PASS_FORWARD) <= b4
+
+
+def test_selector_follows_channel_ratio(B):
+    """Appendix A: Type 3 wins as #input/#output channels grows, Type 1 otherwise; the pick is
+    always a layout the library accepts."""
+    picks = {}
+    for C, O in ((16, 512), (64, 256), (256, 256), (256, 64), (512, 16), (1024, 32)):
+        d = B.make_desc(128, C, 28, 28, O, 3, 1, 1, 1)
+        t = B.cct_pick_lowering(d, B.PASS_FORWARD)
+        assert t in (1, 2, 3)
+        picks[(C, O)] = t
+        costs = {k: B.cct_lowering_cost(d, B.PASS_FORWARD, k) for k in (1, 2, 3)}
+        assert costs[t] == min(costs.values())
+    assert picks[(16, 512)] == 1 and picks[(64, 256)] == 1
+    assert picks[(512, 16)] == 3 and picks[(1024, 32)] == 3
+    # the cost ratio type3/type1 falls as C/O grows (shapes with equal C/O form one group)
+    groups = {}
+    for C, O in picks:
+        d = B.make_desc(128, C, 28, 28, O, 3, 1, 1, 1)
+        groups.setdefault(C / O, []).append(B.cct_lowering_cost(d, 0, 3) / B.cct_lowering_cost(d, 0, 1))
+    keys = sorted(groups)
+    for lo, hi in zip(keys, keys[1:]):
+        assert min(groups[lo]) >= max(groups[hi])
+
+
+def test_selector_degenerate_and_strided_cases(B):
+    d = B.make_desc(128, 64, 28, 28, 64, 1, 1, 0, 1)
+    assert B.cct_pick_lowering(d, B.PASS_FORWARD) == 1          # k = 1: all layouts coincide
+    conv1 = B.make_desc(256, 3, 227, 227, 96, 11, 4, 0, 1)
+    assert B.cct_pick_lowering(conv1, B.PASS_FORWARD) == 1      # stride 4: Types 2/3 waste s, s^2 work
+    for p in (B.PASS_FORWARD, B.PASS_BACKWARD_DATA, B.PASS_BACKWARD_WEIGHTS):
+        for L in __import__("paper_1504_04343_amd.synth", fromlist=["x"]).caffenet(256):
+            dd = B.make_desc(L.N, L.C, L.H, L.W, L.O, L.K, L.stride, L.pad, L.groups)
+            t = B.cct_pick_lowering(dd, p)
+            dd.lowering = t
+            assert B.cct_conv_workspace_bytes(dd, p) > 0
