@@ -182,6 +182,27 @@ int cct_lowered_ld(const cct_conv_desc_t* desc, cct_lowering_t lowering, int64_t
 int cct_lower(const cct_conv_desc_t* desc, cct_lowering_t lowering, const float* x, float* dhat,
               void* hip_stream);
 
+/*
+ * Measurement aid (used by bench.py for the per-kernel roofline figures).  While enabled,
+ * every kernel launch of the library is bracketed by two HIP events on the launching stream.
+ * This is the one place where the library creates HIP objects (events, host side only); it
+ * still allocates no device memory.  cct_profile_enable(1) clears earlier records and starts
+ * recording, cct_profile_enable(0) stops.  cct_profile_read waits (host) for the recorded
+ * events and returns one entry per kernel name: number of launches, summed event time, and
+ * the summed ALGORITHMIC flops and bytes of those launches (GEMM: 2*M*N*K of the true sizes;
+ * index-map kernels: bytes of the tensor read once + the matrix written once, or vice versa).
+ * entries: host array of max_entries; *n receives the number written.
+ */
+typedef struct {
+  char name[96];
+  int64_t launches;
+  double total_ms;
+  double flops;
+  double bytes;
+} cct_profile_entry_t;
+int cct_profile_enable(int on);
+int cct_profile_read(cct_profile_entry_t* entries, int32_t max_entries, int32_t* n);
+
 #ifdef __cplusplus
 }
 #endif

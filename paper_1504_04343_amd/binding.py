@@ -29,7 +29,8 @@ EXPORTS = [
     "cct_strerror", "cct_last_hip_error", "cct_conv_output_dims", "cct_lowered_shape",
     "cct_pick_lowering", "cct_lowering_cost", "cct_conv_workspace_bytes",
     "cct_conv_workspace_bytes_for_chunk", "cct_conv_forward", "cct_conv_backward_data",
-    "cct_conv_backward_weights", "cct_lowered_ld", "cct_lower",
+    "cct_conv_backward_weights", "cct_lowered_ld", "cct_lower", "cct_profile_enable",
+    "cct_profile_read",
 ]
 
 
@@ -63,6 +64,16 @@ _lib.cct_conv_forward.argtypes = [_dp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.cct_conv_backward_data.argtypes = [_dp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.cct_conv_backward_weights.argtypes = [_dp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.cct_lower.argtypes = [_dp, ctypes.c_int, _vp, _vp, _vp]
+
+
+class ProfileEntry(ctypes.Structure):
+    """cct_profile_entry_t."""
+    _fields_ = [("name", ctypes.c_char * 96), ("launches", _i64), ("total_ms", ctypes.c_double),
+                ("flops", ctypes.c_double), ("bytes", ctypes.c_double)]
+
+
+_lib.cct_profile_enable.argtypes = [ctypes.c_int]
+_lib.cct_profile_read.argtypes = [ctypes.POINTER(ProfileEntry), _i32, ctypes.POINTER(_i32)]
 for _name in EXPORTS:
     if _name not in ("cct_strerror",):
         getattr(_lib, _name).restype = ctypes.c_int
@@ -134,6 +145,20 @@ def cct_conv_workspace_bytes_for_chunk(desc: ConvDesc, pass_: int, images_per_ch
                                                    int(images_per_chunk), ctypes.byref(out)),
            "cct_conv_workspace_bytes_for_chunk")
     return out.value
+
+
+def cct_profile_enable(on: bool) -> None:
+    _check(_lib.cct_profile_enable(1 if on else 0), "cct_profile_enable")
+
+
+def cct_profile_read(max_entries: int = 64):
+    """List of dicts (name, launches, total_ms, flops, bytes), one per kernel name."""
+    arr = (ProfileEntry * max_entries)()
+    n = _i32()
+    _check(_lib.cct_profile_read(arr, max_entries, ctypes.byref(n)), "cct_profile_read")
+    return [dict(name=arr[i].name.decode(), launches=int(arr[i].launches),
+                 total_ms=float(arr[i].total_ms), flops=float(arr[i].flops),
+                 bytes=float(arr[i].bytes)) for i in range(n.value)]
 
 
 # ---- device entry points -----------------------------------------------------------------

@@ -4,6 +4,7 @@
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <string.h>
 
 #include "cct.h"
 
@@ -110,6 +111,20 @@ int launch_dbias(const float* dy, float* dbias, float* scratch, int N, int O, in
                  hipStream_t st);
 
 void set_hip_error(hipError_t e);
+
+// Times the launches issued during its lifetime when cct_profile_enable(1) is active;
+// otherwise does nothing.  flops / bytes are the ALGORITHMIC work of the launch.
+class ProfScope {
+ public:
+  ProfScope(const char* name, double flops, double bytes, hipStream_t st);
+  ~ProfScope();
+  ProfScope(const ProfScope&) = delete;
+  ProfScope& operator=(const ProfScope&) = delete;
+
+ private:
+  hipStream_t st_;
+  long long idx_;
+};
 
 #define CCT_CHECK_LAUNCH()                       \
   do {                                           \

@@ -9,6 +9,8 @@
 // Both operands are contiguous along the reduction dimension.  Tiles are transposed on their
 // way into LDS ([k][row] with an odd row stride, so both the transposing stores and the MFMA
 // operand loads stay nearly conflict free).
+#include <stdio.h>
+
 #include "cct_internal.h"
 
 namespace cct {
@@ -142,6 +144,11 @@ int launch_f32(const GemmNT& p, hipStream_t st) {
     return CCT_EUNSUPPORTED;
   if (p.split_len % BK) return CCT_EINVAL;
   dim3 grid((unsigned)tiles, (unsigned)p.S, (unsigned)p.G);
+  char name[96];
+  snprintf(name, sizeof(name), "gemm_nt_f32<%d, %d, %d, %d, %d>", BM, BN, BK, WM, WN);
+  ProfScope ps(name, 2.0 * p.M * p.N * p.Ncols * p.G,
+               4.0 * ((double)p.M * p.Ncols + (double)p.N * p.Ncols + (double)p.M * p.N * p.S) * p.G,
+               st);
   hipLaunchKernelGGL((gemm_nt_f32<BM, BN, BK, WM, WN>), grid, dim3(NT), 0, st, p, tiles_m, tiles_n);
   CCT_CHECK_LAUNCH();
   return CCT_OK;

@@ -12,6 +12,8 @@
 // v_mfma_f32_32x32x8_bf16_1k (bf16 operands) with fp32 accumulators.  K is walked in steps
 // of BK through a double-buffered LDS stage; the global loads of step t+1 are issued before
 // the MFMAs of step t.
+#include <stdio.h>
+
 #include "cct_internal.h"
 
 namespace cct {
@@ -348,6 +350,12 @@ int launch_f32(const GemmTN& p, hipStream_t st) {
   const bool vec = plainB && (p.b_ks % 4 == 0) && (p.b_gs % 4 == 0) &&
                    (reinterpret_cast<uintptr_t>(p.B) % 16 == 0);
   dim3 grid((unsigned)blocks, (unsigned)p.G);
+  char name[96];
+  snprintf(name, sizeof(name), "gemm_tn_f32<%d, %d, %d, %d, %d, %s>", BM, BN, BK, WM, WN,
+           vec ? "true" : "false");
+  ProfScope ps(name, 2.0 * p.M * p.Ncols * p.Kdim * p.G,
+               4.0 * ((double)p.Kdim * p.Ncols + (double)p.M * p.Ncols + (double)p.M * p.Kdim) * p.G,
+               st);
   if (vec)
     hipLaunchKernelGGL((gemm_tn_f32<BM, BN, BK, WM, WN, true>), grid, dim3(NT), 0, st, p, tiles_m,
                        tiles_n);
@@ -368,6 +376,11 @@ int launch_bf16(const GemmTN& p, hipStream_t st) {
   if (!plainB || p.b_ks % 8 || p.b_gs % 8 || reinterpret_cast<uintptr_t>(p.B) % 16)
     return CCT_EUNSUPPORTED;
   dim3 grid((unsigned)blocks, (unsigned)p.G);
+  char name[96];
+  snprintf(name, sizeof(name), "gemm_tn_bf16<%d, %d, %d, %d, %d>", BM, BN, BK, WM, WN);
+  ProfScope ps(name, 2.0 * p.M * p.Ncols * p.Kdim * p.G,
+               ((double)p.Kdim * p.Ncols * 2.0 + (double)p.M * p.Ncols * 4.0 + (double)p.M * p.Kdim * 2.0) * p.G,
+               st);
   hipLaunchKernelGGL((gemm_tn_bf16<BM, BN, BK, WM, WN>), grid, dim3(NT), 0, st, p, tiles_m, tiles_n);
   CCT_CHECK_LAUNCH();
   return CCT_OK;

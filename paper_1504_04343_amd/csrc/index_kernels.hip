@@ -241,6 +241,8 @@ int launch_lower(const float* x, void* dt, long long ld, int nimg, int C, const 
   const long long nblk_col = (ncols + TPB - 1) / TPB;
   if (ncols >= 2147483647LL || !grid_ok(rows * nblk_col)) return CCT_EUNSUPPORTED;
   dim3 grid((unsigned)(rows * nblk_col));
+  ProfScope ps(bf16 ? "lower_kernel<true>" : "lower_kernel<false>", 0.0,
+               4.0 * nimg * C * m.Ht * m.Wt + (bf16 ? 2.0 : 4.0) * rows * ncols, st);
   if (bf16)
     hipLaunchKernelGGL(lower_kernel<true>, grid, dim3(TPB), 0, st, x, dt, ld, (int)ncols,
                        (int)nblk_col, C, m);
@@ -258,6 +260,8 @@ int launch_inv_lift(const float* dy, void* drt, long long ld, int nimg, int O, c
   const long long nblk_col = (ncols + TPB - 1) / TPB;
   if (ncols >= 2147483647LL || !grid_ok(rows * nblk_col)) return CCT_EUNSUPPORTED;
   dim3 grid((unsigned)(rows * nblk_col));
+  ProfScope ps(bf16 ? "inv_lift_kernel<true>" : "inv_lift_kernel<false>", 0.0,
+               4.0 * nimg * O * m.Ht * m.Wt + (bf16 ? 2.0 : 4.0) * rows * ncols, st);
   if (bf16)
     hipLaunchKernelGGL(inv_lift_kernel<true>, grid, dim3(TPB), 0, st, dy, drt, ld, (int)ncols,
                        (int)nblk_col, O, m);
@@ -273,6 +277,8 @@ int launch_lift(const float* rt, long long ld, float* y, const float* bias, int 
   const long long total = (long long)nimg * O * m.Ht * m.Wt;
   const long long blocks = (total + TPB - 1) / TPB;
   if (!grid_ok(blocks)) return CCT_EUNSUPPORTED;
+  ProfScope ps("lift_kernel", 0.0,
+               4.0 * total + 4.0 * O * m.Ki * m.Kj * (double)nimg * m.Ha * m.Wb, st);
   hipLaunchKernelGGL(lift_kernel, dim3((unsigned)blocks), dim3(TPB), 0, st, rt, ld, y, bias, total, O,
                      m);
   CCT_CHECK_LAUNCH();
@@ -284,6 +290,8 @@ int launch_inv_lower(const float* ddt, long long ld, float* dx, int nimg, int C,
   const long long total = (long long)nimg * C * m.Ht * m.Wt;
   const long long blocks = (total + TPB - 1) / TPB;
   if (!grid_ok(blocks)) return CCT_EUNSUPPORTED;
+  ProfScope ps("inv_lower_kernel", 0.0,
+               4.0 * total + 4.0 * C * m.Ki * m.Kj * (double)nimg * m.Ha * m.Wb, st);
   hipLaunchKernelGGL(inv_lower_kernel, dim3((unsigned)blocks), dim3(TPB), 0, st, ddt, ld, dx, total,
                      C, m);
   CCT_CHECK_LAUNCH();
@@ -294,6 +302,8 @@ int launch_pack_kernel_matrix(const float* w, void* pack, const PackDesc& d, hip
   const long long total = (long long)d.Mpad * d.Kpad * d.G;
   const long long blocks = (total + TPB - 1) / TPB;
   if (!grid_ok(blocks)) return CCT_EUNSUPPORTED;
+  ProfScope ps("pack_kernel", 0.0,
+               4.0 * d.G * d.Og * d.Cg * d.K * d.K + (d.bf16 ? 2.0 : 4.0) * total, st);
   if (d.bf16)
     hipLaunchKernelGGL(pack_kernel<true>, dim3((unsigned)blocks), dim3(TPB), 0, st, w, pack, d);
   else
@@ -307,6 +317,7 @@ int launch_reduce_dw(const float* part, float* dw, int S, const PackDesc& d, int
   const long long total = (long long)d.Og * d.RKi * d.RKj * d.Cg * d.DKi * d.DKj * d.G;
   const long long blocks = (total + TPB - 1) / TPB;
   if (!grid_ok(blocks)) return CCT_EUNSUPPORTED;
+  ProfScope ps("reduce_dw_kernel", 0.0, 4.0 * total * (S + 1), st);
   hipLaunchKernelGGL(reduce_dw_kernel, dim3((unsigned)blocks), dim3(TPB), 0, st, part, dw, S, d,
                      accumulate);
   CCT_CHECK_LAUNCH();
@@ -316,6 +327,7 @@ int launch_reduce_dw(const float* part, float* dw, int S, const PackDesc& d, int
 int launch_dbias(const float* dy, float* dbias, float* scratch, int N, int O, int P, int nblk,
                  hipStream_t st) {
   if (!grid_ok((long long)O * nblk)) return CCT_EUNSUPPORTED;
+  ProfScope ps("dbias_stage1+2", 0.0, 4.0 * N * O * P, st);
   hipLaunchKernelGGL(dbias_stage1, dim3((unsigned)(O * nblk)), dim3(TPB), 0, st, dy, scratch, N, O,
                      P, nblk);
   CCT_CHECK_LAUNCH();
