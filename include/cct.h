@@ -175,7 +175,8 @@ int cct_conv_backward_weights(const cct_conv_desc_t* desc, const float* x, const
  *   Type 1: row = (n*Hout + r)*Wout + c,  col = (ci*K + i)*K + j   -> x[n,q*Cg+ci,r*s+i-p,c*s+j-p]
  *   Type 2: row = (n*H + h)*Wout + c,     col = ci*K + j           -> x[n,q*Cg+ci,h,c*s+j-p]
  *   Type 3: row = (n*H + h)*W + w,        col = ci                 -> x[n,q*Cg+ci,h,w]
- * and +0.0f where the source lies in the padding.  Entries with row >= rows are not written.
+ * and +0.0f where the source lies in the padding.  Entries with row in [rows, ld) are padding
+ * and receive zeros.
  * dhat: device, groups*cols*ld floats.  A pure copy: bit-exact by construction.
  */
 int cct_lowered_ld(const cct_conv_desc_t* desc, cct_lowering_t lowering, int64_t* ld);

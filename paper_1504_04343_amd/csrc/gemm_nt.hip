@@ -12,17 +12,12 @@
 #include <stdio.h>
 
 #include "cct_internal.h"
+#include "gemm_common.h"
 
 namespace cct {
 namespace {
 
-typedef float floatx16 __attribute__((ext_vector_type(16)));
 constexpr int NT = 256;
-
-__device__ __forceinline__ long long col_offset(const ColMap& cm, int col) {
-  const int n = col / cm.P;
-  return (long long)n * cm.img_stride + (col - n * cm.P);
-}
 
 template <int BM, int BN, int BK, int WM, int WN>
 __global__ __launch_bounds__(NT) void gemm_nt_f32(GemmNT p, int tiles_m, int tiles_n) {
@@ -36,8 +31,8 @@ __global__ __launch_bounds__(NT) void gemm_nt_f32(GemmNT p, int tiles_m, int til
   constexpr int B_IT = BN / ROWS_PER_PASS;
   constexpr int LDA = BM + 1, LDB = BN + 1;
 
-  __shared__ float As[2][BK][LDA];
-  __shared__ float Bs[2][BK][LDB];
+  __shared__ float As[2][BK * LDA];
+  __shared__ float Bs[2][BK * LDB];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -52,8 +47,8 @@ __global__ __launch_bounds__(NT) void gemm_nt_f32(GemmNT p, int tiles_m, int til
   const int col_begin = s * p.split_len;
   const int col_end = min(p.Ncols, col_begin + p.split_len);
 
-  const float* __restrict__ A = reinterpret_cast<const float*>(p.A) + (long long)g * p.a_gs;
-  const float* __restrict__ B = reinterpret_cast<const float*>(p.B) + (long long)g * p.b_gs;
+  gptr_f32 A = (gptr_f32)(p.A) + (long long)g * p.a_gs;
+  gptr_f32 B = (gptr_f32)(p.B) + (long long)g * p.b_gs;
 
   const int tk = tid % BK;  // this thread's position along the reduction dimension
   const int tr = tid / BK;  // first tile row it copies
@@ -76,9 +71,9 @@ __global__ __launch_bounds__(NT) void gemm_nt_f32(GemmNT p, int tiles_m, int til
   };
   auto store_tile = [&](int buf) {
 #pragma unroll
-    for (int it = 0; it < A_IT; ++it) As[buf][tk][tr + it * ROWS_PER_PASS] = ra[it];
+    for (int it = 0; it < A_IT; ++it) As[buf][tk * LDA + tr + it * ROWS_PER_PASS] = ra[it];
 #pragma unroll
-    for (int it = 0; it < B_IT; ++it) Bs[buf][tk][tr + it * ROWS_PER_PASS] = rb[it];
+    for (int it = 0; it < B_IT; ++it) Bs[buf][tk * LDB + tr + it * ROWS_PER_PASS] = rb[it];
   };
 
   floatx16 acc[WM][WN];
@@ -102,19 +97,7 @@ __global__ __launch_bounds__(NT) void gemm_nt_f32(GemmNT p, int tiles_m, int til
   for (int t = 0; t < ktiles; ++t) {
     const int buf = t & 1;
     if (t + 1 < ktiles) load_tile(col_begin + (t + 1) * BK);
-#pragma unroll
-    for (int kk = 0; kk < BK; kk += 2) {
-      float a[WM], b[WN];
-#pragma unroll
-      for (int i = 0; i < WM; ++i) a[i] = As[buf][kk + lane_hi][am + i * 32];
-#pragma unroll
-      for (int j = 0; j < WN; ++j) b[j] = Bs[buf][kk + lane_hi][bn + j * 32];
-#pragma unroll
-      for (int i = 0; i < WM; ++i)
-#pragma unroll
-        for (int j = 0; j < WN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
-    }
+    mma_stage<BK, LDA, LDB, WM, WN>(&As[buf][lane_hi * LDA + am], &Bs[buf][lane_hi * LDB + bn], acc);
     if (t + 1 < ktiles) store_tile(buf ^ 1);
     __syncthreads();
   }

@@ -15,21 +15,15 @@
 #include <stdio.h>
 
 #include "cct_internal.h"
+#include "gemm_common.h"
 
 namespace cct {
 namespace {
 
-typedef float floatx16 __attribute__((ext_vector_type(16)));
-typedef short shortx4 __attribute__((ext_vector_type(4)));
 
 constexpr int NT = 256;
 
-__device__ __forceinline__ long long col_offset(const ColMap& cm, int col) {
-  const int n = col / cm.P;
-  return (long long)n * cm.img_stride + (col - n * cm.P);
-}
-
-// fp32 kernel.  BVEC: B rows are plain, 16-byte aligned rows -> float4 loads.
+// fp32 kernel.  BVEC: B rows are plain, 16-byte aligned rows -> 16-byte loads.
 template <int BM, int BN, int BK, int WM, int WN, bool BVEC>
 __global__ __launch_bounds__(NT) void gemm_tn_f32(GemmTN p, int tiles_m, int tiles_n) {
   constexpr int WAVES_N = BN / (32 * WN);
@@ -42,9 +36,10 @@ __global__ __launch_bounds__(NT) void gemm_tn_f32(GemmTN p, int tiles_m, int til
   constexpr int B_SC_IT = BK * BN / NT;  // scalar path: loads per thread
   constexpr int B_KSTEP = NT / BN;       // scalar path: k rows covered per pass
   static_assert(NT % BN == 0 || BVEC, "scalar B path needs BN | 256");
+  static_assert(B_VECS % NT == 0, "B tile is a whole number of 16-byte loads per thread");
 
-  __shared__ __attribute__((aligned(16))) float As[2][BK][BM];
-  __shared__ __attribute__((aligned(16))) float Bs[2][BK][BN];
+  __shared__ __attribute__((aligned(16))) float As[2][BK * BM];
+  __shared__ __attribute__((aligned(16))) float Bs[2][BK * BN];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -56,92 +51,98 @@ __global__ __launch_bounds__(NT) void gemm_tn_f32(GemmTN p, int tiles_m, int til
   // the same XCD: the B tile they share is then fetched from HBM once per XCD L2.
   int bid = blockIdx.x;
   const int total = tiles_m * tiles_n;
-  {
-    const int xcd = bid & 7, slot = bid >> 3;
-    const int per = (total + 7) >> 3;
-    const int lin = xcd * per + slot;
-    // when total is not a multiple of 8 the tail would fall outside; fall back to identity there
-    bid = (total % 8 == 0) ? lin : bid;
-  }
+  if (total % 8 == 0) bid = (bid & 7) * (total >> 3) + (bid >> 3);
   const int tile_n = bid / tiles_m;
   const int tile_m = bid - tile_n * tiles_m;
   const int g = blockIdx.y;
   const int m0 = tile_m * BM;
   const int n0 = tile_n * BN;
 
-  const float* __restrict__ A = reinterpret_cast<const float*>(p.A) + (long long)g * p.a_gs + m0;
-  const float* __restrict__ B = reinterpret_cast<const float*>(p.B) + (long long)g * p.b_gs;
+  // ---- global -> register staging: fixed per-thread coordinates, pointers advance by BK rows
+  gptr_f32 Ag = (gptr_f32)(p.A) + (long long)g * p.a_gs + m0;
+  gptr_f32 Bg = (gptr_f32)(p.B) + (long long)g * p.b_gs;
+  gptr_f32 a_src[A_IT];
+  int a_dst[A_IT];
+#pragma unroll
+  for (int it = 0; it < A_IT; ++it) {
+    const int v = tid + it * NT;
+    const int k = v / (BM / 4), m4 = v % (BM / 4);
+    a_src[it] = Ag + (long long)k * p.Mpad + m4 * 4;
+    a_dst[it] = k * BM + m4 * 4;
+  }
+  const long long a_step = (long long)BK * p.Mpad;
+  const long long b_step = (long long)BK * p.b_ks;
 
-  // per-thread source coordinates of the global->LDS copies
-  long long b_off = 0;  // scalar path: offset of this thread's column
-  bool b_ok = false;
-  int b_k0 = 0, b_n = 0;
-  if (!BVEC) {
-    b_n = tid % BN;
-    b_k0 = tid / BN;
-    const int col = n0 + b_n;
-    b_ok = col < p.Ncols;
-    b_off = b_ok ? col_offset(p.bmap, col) : 0;
+  gptr_f32 b_src[BVEC ? B_IT : 1];
+  int b_dst[BVEC ? B_IT : 1];
+  int b_k[BVEC ? B_IT : 1];
+  bool b_colok[BVEC ? B_IT : 1];
+  gptr_f32 bs_src = nullptr;  // scalar path
+  bool bs_ok = false;
+  int bs_k0 = 0, bs_n = 0;
+  if (BVEC) {
+#pragma unroll
+    for (int it = 0; it < B_IT; ++it) {
+      const int v = tid + it * NT;
+      const int k = v / (BN / 4), n4 = v % (BN / 4);
+      const int col = n0 + n4 * 4;
+      b_k[it] = k;
+      b_colok[it] = col < p.b_ld_guard;
+      b_src[it] = Bg + (long long)k * p.b_ks + col;
+      b_dst[it] = k * BN + n4 * 4;
+    }
+  } else {
+    bs_n = tid % BN;
+    bs_k0 = tid / BN;
+    const int col = n0 + bs_n;
+    bs_ok = col < p.Ncols;
+    bs_src = Bg + (bs_ok ? col_offset(p.bmap, col) : 0) + (long long)bs_k0 * p.b_ks;
   }
 
-  float4 ra[A_IT];
-  float4 rbv[BVEC ? B_IT : 1];
+  f32x4 ra[A_IT];
+  f32x4 rbv[BVEC ? B_IT : 1];
   float rbs[BVEC ? 1 : B_SC_IT];
 
-  auto load_tile = [&](int k0) {
-#pragma unroll
-    for (int it = 0; it < A_IT; ++it) {
-      const int v = tid + it * NT;
-      if (A_VECS % NT == 0 || v < A_VECS) {
-        const int k = v / (BM / 4), m4 = v % (BM / 4);
-        ra[it] = *reinterpret_cast<const float4*>(A + (long long)(k0 + k) * p.Mpad + m4 * 4);
-      }
-    }
-    if (BVEC) {
-#pragma unroll
-      for (int it = 0; it < B_IT; ++it) {
-        const int v = tid + it * NT;
-        const int k = v / (BN / 4), n4 = v % (BN / 4);
-        const int col = n0 + n4 * 4;
-        float4 val = make_float4(0.f, 0.f, 0.f, 0.f);
-        if ((B_VECS % NT == 0 || v < B_VECS) && (k0 + k) < p.Kdim && col < p.b_ld_guard)
-          val = *reinterpret_cast<const float4*>(B + (long long)(k0 + k) * p.b_ks + col);
-        rbv[it] = val;
-      }
-    } else {
-#pragma unroll
-      for (int it = 0; it < B_SC_IT; ++it) {
-        const int k = k0 + b_k0 + it * B_KSTEP;
-        float val = 0.f;
-        if (b_ok && k < p.Kdim) val = B[(long long)k * p.b_ks + b_off];
-        rbs[it] = val;
-      }
-    }
-  };
+#define CCT_LOAD_TILE(K0)                                                                   \
+  {                                                                                         \
+    _Pragma("unroll") for (int it = 0; it < A_IT; ++it) {                                   \
+      if (A_VECS % NT == 0 || tid + it * NT < A_VECS)                                       \
+        ra[it] = *(gptr_f32x4)(a_src[it]);                                                  \
+      a_src[it] += a_step;                                                                  \
+    }                                                                                       \
+    if (BVEC) {                                                                             \
+      _Pragma("unroll") for (int it = 0; it < B_IT; ++it) {                                 \
+        f32x4 val = {0.f, 0.f, 0.f, 0.f};                                                   \
+        if (b_colok[it] && (K0) + b_k[it] < p.Kdim)                                         \
+          val = *(gptr_f32x4)(b_src[it]);                                                   \
+        rbv[it] = val;                                                                      \
+        b_src[it] += b_step;                                                                \
+      }                                                                                     \
+    } else {                                                                                \
+      _Pragma("unroll") for (int it = 0; it < B_SC_IT; ++it) {                              \
+        float val = 0.f;                                                                    \
+        if (bs_ok && (K0) + bs_k0 + it * B_KSTEP < p.Kdim)                                  \
+          val = bs_src[(long long)it * B_KSTEP * p.b_ks];                                   \
+        rbs[it] = val;                                                                      \
+      }                                                                                     \
+      bs_src += b_step;                                                                     \
+    }                                                                                       \
+  }
 
-  auto store_tile = [&](int buf) {
-#pragma unroll
-    for (int it = 0; it < A_IT; ++it) {
-      const int v = tid + it * NT;
-      if (A_VECS % NT == 0 || v < A_VECS) {
-        const int k = v / (BM / 4), m4 = v % (BM / 4);
-        *reinterpret_cast<float4*>(&As[buf][k][m4 * 4]) = ra[it];
-      }
-    }
-    if (BVEC) {
-#pragma unroll
-      for (int it = 0; it < B_IT; ++it) {
-        const int v = tid + it * NT;
-        if (B_VECS % NT == 0 || v < B_VECS) {
-          const int k = v / (BN / 4), n4 = v % (BN / 4);
-          *reinterpret_cast<float4*>(&Bs[buf][k][n4 * 4]) = rbv[it];
-        }
-      }
-    } else {
-#pragma unroll
-      for (int it = 0; it < B_SC_IT; ++it) Bs[buf][b_k0 + it * B_KSTEP][b_n] = rbs[it];
-    }
-  };
+#define CCT_STORE_TILE(BUF)                                                                 \
+  {                                                                                         \
+    _Pragma("unroll") for (int it = 0; it < A_IT; ++it) {                                   \
+      if (A_VECS % NT == 0 || tid + it * NT < A_VECS)                                       \
+        *reinterpret_cast<f32x4*>(&As[BUF][a_dst[it]]) = ra[it];                            \
+    }                                                                                       \
+    if (BVEC) {                                                                             \
+      _Pragma("unroll") for (int it = 0; it < B_IT; ++it)                                   \
+        *reinterpret_cast<f32x4*>(&Bs[BUF][b_dst[it]]) = rbv[it];                           \
+    } else {                                                                                \
+      _Pragma("unroll") for (int it = 0; it < B_SC_IT; ++it)                                \
+        Bs[BUF][(bs_k0 + it * B_KSTEP) * BN + bs_n] = rbs[it];                              \
+    }                                                                                       \
+  }
 
   floatx16 acc[WM][WN];
 #pragma unroll
@@ -154,30 +155,23 @@ __global__ __launch_bounds__(NT) void gemm_tn_f32(GemmTN p, int tiles_m, int til
   const int lane_lo = lane & 31, lane_hi = lane >> 5;
   const int am = wave_m * WM * 32 + lane_lo;
   const int bn = wave_n * WN * 32 + lane_lo;
+  const int a_lds = lane_hi * BM + am;
+  const int b_lds = lane_hi * BN + bn;
 
   const int ktiles = p.Kpad / BK;
-  load_tile(0);
-  store_tile(0);
+  CCT_LOAD_TILE(0);
+  CCT_STORE_TILE(0);
   __syncthreads();
   for (int t = 0; t < ktiles; ++t) {
     const int buf = t & 1;
-    if (t + 1 < ktiles) load_tile((t + 1) * BK);
-#pragma unroll
-    for (int kk = 0; kk < BK; kk += 2) {
-      float a[WM], b[WN];
-#pragma unroll
-      for (int i = 0; i < WM; ++i) a[i] = As[buf][kk + lane_hi][am + i * 32];
-#pragma unroll
-      for (int j = 0; j < WN; ++j) b[j] = Bs[buf][kk + lane_hi][bn + j * 32];
-#pragma unroll
-      for (int i = 0; i < WM; ++i)
-#pragma unroll
-        for (int j = 0; j < WN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
-    }
-    if (t + 1 < ktiles) store_tile(buf ^ 1);
+    const bool more = t + 1 < ktiles;
+    if (more) CCT_LOAD_TILE((t + 1) * BK);
+    mma_stage<BK, BM, BN, WM, WN>(&As[buf][a_lds], &Bs[buf][b_lds], acc);
+    if (more) CCT_STORE_TILE(buf ^ 1);
     __syncthreads();
   }
+#undef CCT_LOAD_TILE
+#undef CCT_STORE_TILE
 
   // Epilogue: lifting (Type 1) / plain store, + bias.  In the 32x32 accumulator lane l holds
   // column l%32 and rows 8*(r/4) + 4*(l/32) + r%4 for r = 0..15.
