@@ -6,9 +6,9 @@
 // (split-K); the partial products are summed afterwards in split order, which keeps the
 // result bit-reproducible (no atomics).
 //
-// Both operands are contiguous along the reduction dimension.  Tiles are transposed on their
-// way into LDS ([k][row] with an odd row stride, so both the transposing stores and the MFMA
-// operand loads stay nearly conflict free).
+// Both operands are contiguous along the reduction dimension, and they stay that way in LDS
+// ([row][k], rows padded by 4 floats): no transposition anywhere, 16-byte global loads, LDS
+// writes and LDS reads.
 #include <stdio.h>
 
 #include "cct_internal.h"
@@ -19,20 +19,61 @@ namespace {
 
 constexpr int NT = 256;
 
-template <int BM, int BN, int BK, int WM, int WN>
+// K-step over 8 reduction indices with operands stored [row][k] in LDS: every lane fetches
+// 4 consecutive k of its row with one 16-byte LDS read (lanes 0..31 take k = 8q..8q+3, lanes
+// 32..63 take k = 8q+4..8q+7) and MFMA e of the group consumes component e.  Any assignment of
+// reduction indices to (lane half, component) is valid as long as A and B use the same one.
+template <int BK, int LDK, int WM, int WN>
+__device__ __forceinline__ void mma_stage_kcontig(const float* __restrict__ as,
+                                                  const float* __restrict__ bs,
+                                                  floatx16 (&acc)[WM][WN]) {
+  f32x4 a[2][WM], b[2][WN];
+#pragma unroll
+  for (int i = 0; i < WM; ++i) a[0][i] = *reinterpret_cast<const f32x4*>(as + i * 32 * LDK);
+#pragma unroll
+  for (int j = 0; j < WN; ++j) b[0][j] = *reinterpret_cast<const f32x4*>(bs + j * 32 * LDK);
+#pragma unroll
+  for (int q = 0; q < BK / 8; ++q) {
+    const int cur = q & 1, nxt = cur ^ 1;
+    if (q + 1 < BK / 8) {
+#pragma unroll
+      for (int i = 0; i < WM; ++i)
+        a[nxt][i] = *reinterpret_cast<const f32x4*>(as + i * 32 * LDK + (q + 1) * 8);
+#pragma unroll
+      for (int j = 0; j < WN; ++j)
+        b[nxt][j] = *reinterpret_cast<const f32x4*>(bs + j * 32 * LDK + (q + 1) * 8);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+#pragma unroll
+      for (int i = 0; i < WM; ++i)
+#pragma unroll
+        for (int j = 0; j < WN; ++j)
+          acc[i][j] =
+              __builtin_amdgcn_mfma_f32_32x32x2f32(a[cur][i][e], b[cur][j][e], acc[i][j], 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
+// AVEC: A rows are plain 16-byte aligned matrix rows (inverse-lifted dy of Types 2/3);
+// otherwise A is dy read in place through the NCHW column map (Type 1), 4-byte loads.
+template <int BM, int BN, int BK, int WM, int WN, bool AVEC>
 __global__ __launch_bounds__(NT) void gemm_nt_f32(GemmNT p, int tiles_m, int tiles_n) {
   constexpr int WAVES_N = BN / (32 * WN);
   constexpr int WAVES_M = BM / (32 * WM);
   static_assert(WAVES_M * WAVES_N == 4, "4 waves per workgroup");
-  static_assert(NT % BK == 0, "BK divides 256");
-  constexpr int ROWS_PER_PASS = NT / BK;
-  static_assert(BM % ROWS_PER_PASS == 0 && BN % ROWS_PER_PASS == 0, "tile rows");
-  constexpr int A_IT = BM / ROWS_PER_PASS;
-  constexpr int B_IT = BN / ROWS_PER_PASS;
-  constexpr int LDA = BM + 1, LDB = BN + 1;
+  static_assert(BK % 8 == 0 && NT % BK == 0, "BK");
+  constexpr int LDK = BK + 4;            // 16-byte aligned rows, conflict-free 16-byte reads
+  constexpr int KQ = BK / 4;             // 16-byte vectors per tile row
+  constexpr int AV_IT = BM * KQ / NT;    // vector loads per thread (A, vector path)
+  constexpr int BV_IT = BN * KQ / NT;
+  constexpr int AS_IT = BM * BK / NT;    // scalar loads per thread (A, scalar path)
+  constexpr int AS_ROWS = NT / BK;       // tile rows covered per scalar pass
+  static_assert((BM * KQ) % NT == 0 && (BN * KQ) % NT == 0, "tile/thread split");
 
-  __shared__ float As[2][BK * LDA];
-  __shared__ float Bs[2][BK * LDB];
+  __shared__ __attribute__((aligned(16))) float As[2][BM * LDK];
+  __shared__ __attribute__((aligned(16))) float Bs[2][BN * LDK];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -50,31 +91,69 @@ __global__ __launch_bounds__(NT) void gemm_nt_f32(GemmNT p, int tiles_m, int til
   gptr_f32 A = (gptr_f32)(p.A) + (long long)g * p.a_gs;
   gptr_f32 B = (gptr_f32)(p.B) + (long long)g * p.b_gs;
 
-  const int tk = tid % BK;  // this thread's position along the reduction dimension
-  const int tr = tid / BK;  // first tile row it copies
+  // Rows beyond M / N are clamped to the last valid row: their products land in rows/columns of
+  // the tile that are never stored.  Columns beyond Ncols inside a plain lowered matrix are zero
+  // padding written by the lowering kernels, so plain rows need no column guard.
+  gptr_f32 b_src[BV_IT];
+  int b_dst[BV_IT];
+#pragma unroll
+  for (int it = 0; it < BV_IT; ++it) {
+    const int v = tid + it * NT;
+    const int row = v / KQ, kq = v % KQ;
+    b_src[it] = B + (long long)min(n0 + row, p.N - 1) * p.b_ns + col_begin + kq * 4;
+    b_dst[it] = row * LDK + kq * 4;
+  }
+  gptr_f32 av_src[AVEC ? AV_IT : 1];
+  int av_dst[AVEC ? AV_IT : 1];
+  const int as_k = tid % BK, as_r0 = tid / BK;
+  if (AVEC) {
+#pragma unroll
+    for (int it = 0; it < AV_IT; ++it) {
+      const int v = tid + it * NT;
+      const int row = v / KQ, kq = v % KQ;
+      av_src[it] = A + (long long)min(m0 + row, p.M - 1) * p.a_ms + col_begin + kq * 4;
+      av_dst[it] = row * LDK + kq * 4;
+    }
+  }
 
-  float ra[A_IT], rb[B_IT];
-  auto load_tile = [&](int c0) {
-    const int col = c0 + tk;
-    const bool ok = col < col_end;
-    const long long aoff = ok ? col_offset(p.amap, col) : 0;
-#pragma unroll
-    for (int it = 0; it < A_IT; ++it) {
-      const int m = m0 + tr + it * ROWS_PER_PASS;
-      ra[it] = (ok && m < p.M) ? A[(long long)m * p.a_ms + aoff] : 0.f;
-    }
-#pragma unroll
-    for (int it = 0; it < B_IT; ++it) {
-      const int n = n0 + tr + it * ROWS_PER_PASS;
-      rb[it] = (ok && n < p.N) ? B[(long long)n * p.b_ns + col] : 0.f;
-    }
-  };
-  auto store_tile = [&](int buf) {
-#pragma unroll
-    for (int it = 0; it < A_IT; ++it) As[buf][tk * LDA + tr + it * ROWS_PER_PASS] = ra[it];
-#pragma unroll
-    for (int it = 0; it < B_IT; ++it) Bs[buf][tk * LDB + tr + it * ROWS_PER_PASS] = rb[it];
-  };
+  f32x4 rb[BV_IT];
+  f32x4 rav[AVEC ? AV_IT : 1];
+  float ras[AVEC ? 1 : AS_IT];
+
+#define CCT_NT_LOAD(C0)                                                                   \
+  {                                                                                       \
+    _Pragma("unroll") for (int it = 0; it < BV_IT; ++it) {                                \
+      rb[it] = *(gptr_f32x4)(b_src[it]);                                                  \
+      b_src[it] += BK;                                                                    \
+    }                                                                                     \
+    if (AVEC) {                                                                           \
+      _Pragma("unroll") for (int it = 0; it < AV_IT; ++it) {                              \
+        rav[it] = *(gptr_f32x4)(av_src[it]);                                              \
+        av_src[it] += BK;                                                                 \
+      }                                                                                   \
+    } else {                                                                              \
+      const int col = (C0) + as_k;                                                        \
+      const bool ok = col < col_end;                                                      \
+      const long long aoff = ok ? col_offset(p.amap, col) : 0;                            \
+      _Pragma("unroll") for (int it = 0; it < AS_IT; ++it) {                              \
+        const int m = min(m0 + as_r0 + it * AS_ROWS, p.M - 1);                            \
+        const float val = A[(long long)m * p.a_ms + aoff];                                \
+        ras[it] = ok ? val : 0.f;                                                         \
+      }                                                                                   \
+    }                                                                                     \
+  }
+#define CCT_NT_STORE(BUF)                                                                 \
+  {                                                                                       \
+    _Pragma("unroll") for (int it = 0; it < BV_IT; ++it)                                  \
+      *reinterpret_cast<f32x4*>(&Bs[BUF][b_dst[it]]) = rb[it];                            \
+    if (AVEC) {                                                                           \
+      _Pragma("unroll") for (int it = 0; it < AV_IT; ++it)                                \
+        *reinterpret_cast<f32x4*>(&As[BUF][av_dst[it]]) = rav[it];                        \
+    } else {                                                                              \
+      _Pragma("unroll") for (int it = 0; it < AS_IT; ++it)                                \
+        As[BUF][(as_r0 + it * AS_ROWS) * LDK + as_k] = ras[it];                           \
+    }                                                                                     \
+  }
 
   floatx16 acc[WM][WN];
 #pragma unroll
@@ -87,20 +166,25 @@ __global__ __launch_bounds__(NT) void gemm_nt_f32(GemmNT p, int tiles_m, int til
   const int lane_lo = lane & 31, lane_hi = lane >> 5;
   const int am = wave_m * WM * 32 + lane_lo;
   const int bn = wave_n * WN * 32 + lane_lo;
+  const int a_lds = am * LDK + lane_hi * 4;
+  const int b_lds = bn * LDK + lane_hi * 4;
 
   const int ktiles = (col_end - col_begin + BK - 1) / BK;  // <= 0 for an empty split
   if (ktiles > 0) {
-    load_tile(col_begin);
-    store_tile(0);
+    CCT_NT_LOAD(col_begin);
+    CCT_NT_STORE(0);
   }
   __syncthreads();
   for (int t = 0; t < ktiles; ++t) {
     const int buf = t & 1;
-    if (t + 1 < ktiles) load_tile(col_begin + (t + 1) * BK);
-    mma_stage<BK, LDA, LDB, WM, WN>(&As[buf][lane_hi * LDA + am], &Bs[buf][lane_hi * LDB + bn], acc);
-    if (t + 1 < ktiles) store_tile(buf ^ 1);
+    const bool more = t + 1 < ktiles;
+    if (more) CCT_NT_LOAD(col_begin + (t + 1) * BK);
+    mma_stage_kcontig<BK, LDK, WM, WN>(&As[buf][a_lds], &Bs[buf][b_lds], acc);
+    if (more) CCT_NT_STORE(buf ^ 1);
     __syncthreads();
   }
+#undef CCT_NT_LOAD
+#undef CCT_NT_STORE
 
   float* __restrict__ C = p.Cpart + ((long long)s * p.G + g) * p.M * p.N;
 #pragma unroll
@@ -126,13 +210,23 @@ int launch_f32(const GemmNT& p, hipStream_t st) {
   if (tiles <= 0 || tiles >= 2147483647LL || p.S < 1 || p.S > 65535 || p.G > 65535)
     return CCT_EUNSUPPORTED;
   if (p.split_len % BK) return CCT_EINVAL;
+  // B must be a plain lowered matrix with 16-byte aligned rows (the lowering kernels write it so)
+  if (p.b_ns % 4 || p.b_gs % 4 || reinterpret_cast<uintptr_t>(p.B) % 16) return CCT_EINVAL;
+  const bool avec = p.amap.P == 2147483647 && p.a_ms % 4 == 0 && p.a_gs % 4 == 0 &&
+                    reinterpret_cast<uintptr_t>(p.A) % 16 == 0;
   dim3 grid((unsigned)tiles, (unsigned)p.S, (unsigned)p.G);
   char name[96];
-  snprintf(name, sizeof(name), "gemm_nt_f32<%d, %d, %d, %d, %d>", BM, BN, BK, WM, WN);
+  snprintf(name, sizeof(name), "gemm_nt_f32<%d, %d, %d, %d, %d, %s>", BM, BN, BK, WM, WN,
+           avec ? "true" : "false");
   ProfScope ps(name, 2.0 * p.M * p.N * p.Ncols * p.G,
                4.0 * ((double)p.M * p.Ncols + (double)p.N * p.Ncols + (double)p.M * p.N * p.S) * p.G,
                st);
-  hipLaunchKernelGGL((gemm_nt_f32<BM, BN, BK, WM, WN>), grid, dim3(NT), 0, st, p, tiles_m, tiles_n);
+  if (avec)
+    hipLaunchKernelGGL((gemm_nt_f32<BM, BN, BK, WM, WN, true>), grid, dim3(NT), 0, st, p, tiles_m,
+                       tiles_n);
+  else
+    hipLaunchKernelGGL((gemm_nt_f32<BM, BN, BK, WM, WN, false>), grid, dim3(NT), 0, st, p, tiles_m,
+                       tiles_n);
   CCT_CHECK_LAUNCH();
   return CCT_OK;
 }
@@ -141,7 +235,7 @@ int launch_f32(const GemmNT& p, hipStream_t st) {
 
 void gemm_nt_tile(int M, int /*N*/, int* BM, int* BN, int* BK) {
   *BN = 128;
-  *BK = 16;
+  *BK = 32;
   if (M <= 64)
     *BM = 64;
   else if (M % 128 != 0 && M % 96 == 0)
@@ -154,9 +248,9 @@ int launch_gemm_nt(const GemmNT& p, hipStream_t st) {
   if (p.bf16) return CCT_EUNSUPPORTED;
   int BM, BN, BK;
   gemm_nt_tile(p.M, p.N, &BM, &BN, &BK);
-  if (BM == 64) return launch_f32<64, 128, 16, 1, 2>(p, st);
-  if (BM == 96) return launch_f32<96, 128, 16, 3, 1>(p, st);
-  return launch_f32<128, 128, 16, 2, 2>(p, st);
+  if (BM == 64) return launch_f32<64, 128, 32, 1, 2>(p, st);
+  if (BM == 96) return launch_f32<96, 128, 32, 3, 1>(p, st);
+  return launch_f32<128, 128, 32, 2, 2>(p, st);
 }
 
 }  // namespace cct
