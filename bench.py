@@ -35,6 +35,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-images", type=int, default=16)
     ap.add_argument("--per-kernel", action="store_true", help="also print the per-kernel table")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="first run one plain 1 GiB device copy (reference row for rocprofv3 --pmc "
+                         "FETCH_SIZE / WRITE_SIZE scaling)")
     return ap.parse_args()
 
 
@@ -50,6 +53,12 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.copy_calibration:
+        src = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")   # 1 GiB
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     prec = B.PREC_F32 if args.precision == "f32" else B.PREC_BF16_IN_F32_ACC
     layers = synth.caffenet(args.batch)
     passes = [B.PASS_FORWARD, B.PASS_BACKWARD_DATA, B.PASS_BACKWARD_WEIGHTS]

@@ -7,9 +7,9 @@
 // channel for those columns:
 //   1. the input rows that these columns can touch are staged in LDS with coalesced loads,
 //      so every tensor element is fetched from HBM/L2 once per workgroup instead of once per tap;
-//   2. every thread decodes its VEC consecutive columns once, then for each tap reads VEC
-//      values from LDS and writes them with one 16-byte store.  Per row the workgroup's stores
-//      are one contiguous, aligned run.
+//   2. every thread decodes its VEC columns once (consecutive lanes own consecutive columns),
+//      then for each tap reads VEC values from LDS and stores them: per tap row every wave
+//      writes contiguous 256-byte runs.
 #include "cct_internal.h"
 #include "index_common.h"
 
@@ -47,18 +47,40 @@ __device__ __forceinline__ void inv_lift_rows(const WinMap& m, const FastDiv& di
   *t_hi = min(m.Ht - 1, fdiv(a_hi + m.ph, divSh));
 }
 
-template <bool BF16, int NTH>
-__global__ __launch_bounds__(NTH) void lower_kernel(const float* __restrict__ x, void* __restrict__ dt,
+// Column assignment inside a workgroup: consecutive lanes own consecutive columns (CPT = 1 for
+// fp32 output, 2 for bf16 so that every lane still stores 4 bytes), which makes the LDS reads of
+// a tap bank-conflict free and the global stores of a wave one contiguous run.
+template <bool BF16>
+__device__ __forceinline__ void store_run(void* base, long long idx, const float* v) {
+  if (BF16) {
+    reinterpret_cast<unsigned*>(reinterpret_cast<unsigned short*>(base) + idx)[0] =
+        (unsigned)f32_to_bf16_rne(v[0]) | ((unsigned)f32_to_bf16_rne(v[1]) << 16);
+  } else {
+    reinterpret_cast<float*>(base)[idx] = v[0];
+  }
+}
+
+template <bool BF16, int VC>
+__global__ __launch_bounds__(TPB) void lower_kernel(const float* __restrict__ x, void* __restrict__ dt,
                                                     long long ld, int ncols, int C, WinMap m,
-                                                    FastDiv divP, FastDiv divW) {
+                                                    FastDiv divP, FastDiv divW, FastDiv divWt,
+                                                    FastDiv divSw) {
   extern __shared__ float tile[];
-  constexpr int NCB = NTH * VEC;
+  constexpr int NTH = TPB;
+  constexpr int NCB = NTH * VC;        // columns per workgroup
+  constexpr int CPT = BF16 ? 2 : 1;    // consecutive columns per lane
+  constexpr int EG = VC / CPT;         // column groups per thread
+  static_assert(VC % CPT == 0, "columns per thread");
   const int tid = threadIdx.x;
   const int ch = blockIdx.z * 32768 + blockIdx.y;
   const int cb = blockIdx.x * NCB;
   const int ce = min(cb + NCB, ncols);
   const int Pc = m.Ha * m.Wb;
-  const int col0 = cb + tid * VEC;
+  // LDS row layout: for stride sw > 1 a tensor row is stored de-interleaved by w mod sw
+  // (residue r at [r*Wq, (r+1)*Wq)), so that the columns b, b+1, ... of one tap, which are sw
+  // pixels apart, sit in consecutive LDS words.
+  const int Wq = (m.Wt + m.sw - 1) / m.sw;
+  const int Wrow = Wq * m.sw;
 
   int len_first = 0, len_full = 0, tlo_first = 0;
   Span sp = {0, -1, 0, 0};
@@ -70,38 +92,62 @@ __global__ __launch_bounds__(NTH) void lower_kernel(const float* __restrict__ x,
       const int a_hi = n == sp.n_last ? sp.a_last : m.Ha - 1;
       int t_lo, t_hi;
       lower_rows(m, a_lo, a_hi, &t_lo, &t_hi);
-      const int len = max(0, t_hi - t_lo + 1) * m.Wt;
+      const int nrows = max(0, t_hi - t_lo + 1);
       const float* src = x + (((long long)n * C + ch) * m.Ht + t_lo) * m.Wt;
-      for (int t = tid; t < len; t += NTH) tile[off + t] = src[t];
+      // 8 independent loads per thread in flight, then the LDS stores
+      const int len = nrows * m.Wt;
+      for (int t0 = tid; t0 < len; t0 += NTH * 8) {
+        float rv[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const int t = t0 + u * NTH;
+          rv[u] = t < len ? src[t] : 0.0f;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const int t = t0 + u * NTH;
+          if (t < len) {
+            if (m.sw == 1) {
+              tile[off + t] = rv[u];
+            } else {
+              const int r = fdiv(t, divWt), w = t - r * m.Wt;
+              const int wq = fdiv(w, divSw), wr = w - wq * m.sw;
+              tile[off + r * Wrow + wr * Wq + wq] = rv[u];
+            }
+          }
+        }
+      }
       if (n == sp.n_first) {
-        len_first = len;
+        len_first = nrows * Wrow;
         tlo_first = t_lo;
       }
-      off += len;
+      off += nrows * Wrow;
     }
     int t_lo, t_hi;
     lower_rows(m, 0, m.Ha - 1, &t_lo, &t_hi);
-    len_full = max(0, t_hi - t_lo + 1) * m.Wt;
+    len_full = max(0, t_hi - t_lo + 1) * Wrow;
   }
   __syncthreads();
-  if (col0 >= ld) return;
 
-  // decode this thread's VEC columns once
-  int base[VEC], hh[VEC], ww[VEC];
-  {
-    int n = fdiv(col0, divP);
-    const int rem = col0 - n * Pc;
+  // decode this thread's columns once
+  int base[VC], hh[VC], bb[VC];
+#pragma unroll
+  for (int e = 0; e < EG; ++e) {
+    const int c0 = cb + (e * NTH + tid) * CPT;
+    int n = fdiv(c0, divP);
+    const int rem = c0 - n * Pc;
     int a = fdiv(rem, divW);
     int b = rem - a * m.Wb;
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) {
+    for (int u = 0; u < CPT; ++u) {
+      const int q = e * CPT + u;
       const bool first = n == sp.n_first;
       const int seg = first ? 0 : len_first + (n - sp.n_first - 1) * len_full;
       const int t_lo = first ? tlo_first : 0;
-      hh[e] = a * m.sh - m.ph;
-      ww[e] = b * m.sw - m.pw;
-      base[e] = seg + (hh[e] - t_lo) * m.Wt + ww[e];
-      if (col0 + e >= ce) hh[e] = -(1 << 30);  // padding column: every tap is out of range
+      hh[q] = a * m.sh - m.ph;
+      bb[q] = b;
+      base[q] = seg + (hh[q] - t_lo) * Wrow + b;
+      if (c0 + u >= ce) hh[q] = -(1 << 30);  // padding column: every tap is out of range
       if (++b == m.Wb) {
         b = 0;
         if (++a == m.Ha) {
@@ -112,33 +158,47 @@ __global__ __launch_bounds__(NTH) void lower_kernel(const float* __restrict__ x,
     }
   }
   const long long row0 = (long long)ch * m.Ki * m.Kj;
-  for (int i = 0; i < m.Ki; ++i) {
-    for (int j = 0; j < m.Kj; ++j) {
-      float v[VEC];
+  for (int j = 0; j < m.Kj; ++j) {
+    // w = b*sw + (j - pw) = (b + qj)*sw + rj with 0 <= rj < sw
+    const int jj = j - m.pw;
+    const int qj = jj >= 0 ? fdiv(jj, divSw) : -fdiv(-jj + m.sw - 1, divSw);
+    const int rj = jj - qj * m.sw;
+    const int joff = rj * Wq + qj;
+    for (int i = 0; i < m.Ki; ++i) {
+      float v[VC];
 #pragma unroll
-      for (int e = 0; e < VEC; ++e) {
-        const bool ok = (unsigned)(hh[e] + i) < (unsigned)m.Ht && (unsigned)(ww[e] + j) < (unsigned)m.Wt;
-        const float t = tile[ok ? base[e] + i * m.Wt + j : 0];
-        v[e] = ok ? t : 0.0f;
+      for (int q = 0; q < VC; ++q) {
+        const bool ok = (unsigned)(hh[q] + i) < (unsigned)m.Ht &&
+                        (unsigned)(bb[q] * m.sw + jj) < (unsigned)m.Wt;
+        const float t = tile[ok ? base[q] + i * Wrow + joff : 0];
+        v[q] = ok ? t : 0.0f;
       }
-      store_vec<BF16>(dt, (row0 + i * m.Kj + j) * ld + col0, v);
+      const long long rbase = (row0 + i * m.Kj + j) * ld;
+#pragma unroll
+      for (int e = 0; e < EG; ++e) {
+        const int c0 = cb + (e * NTH + tid) * CPT;
+        if (c0 < ld) store_run<BF16>(dt, rbase + c0, &v[e * CPT]);
+      }
     }
   }
 }
 
-template <bool BF16, int NTH>
-__global__ __launch_bounds__(NTH) void inv_lift_kernel(const float* __restrict__ dy,
+template <bool BF16, int VC>
+__global__ __launch_bounds__(TPB) void inv_lift_kernel(const float* __restrict__ dy,
                                                        void* __restrict__ drt, long long ld,
                                                        int ncols, int O, WinMap m, FastDiv divP,
                                                        FastDiv divW, FastDiv divSh, FastDiv divSw) {
   extern __shared__ float tile[];
-  constexpr int NCB = NTH * VEC;
+  constexpr int NTH = TPB;
+  constexpr int NCB = NTH * VC;
+  constexpr int CPT = BF16 ? 2 : 1;
+  constexpr int EG = VC / CPT;
+  static_assert(VC % CPT == 0, "columns per thread");
   const int tid = threadIdx.x;
   const int o = blockIdx.z * 32768 + blockIdx.y;
   const int cb = blockIdx.x * NCB;
   const int ce = min(cb + NCB, ncols);
   const int Pc = m.Ha * m.Wb;
-  const int col0 = cb + tid * VEC;
 
   int len_first = 0, len_full = 0, tlo_first = 0, tlo_full = 0;
   Span sp = {0, -1, 0, 0};
@@ -152,7 +212,19 @@ __global__ __launch_bounds__(NTH) void inv_lift_kernel(const float* __restrict__
       inv_lift_rows(m, divSh, a_lo, a_hi, &t_lo, &t_hi);
       const int len = max(0, t_hi - t_lo + 1) * m.Wt;
       const float* src = dy + (((long long)n * O + o) * m.Ht + t_lo) * m.Wt;
-      for (int t = tid; t < len; t += NTH) tile[off + t] = src[t];
+      for (int t0 = tid; t0 < len; t0 += NTH * 8) {
+        float rv[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const int t = t0 + u * NTH;
+          rv[u] = t < len ? src[t] : 0.0f;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const int t = t0 + u * NTH;
+          if (t < len) tile[off + t] = rv[u];
+        }
+      }
       if (n == sp.n_first) {
         len_first = len;
         tlo_first = t_lo;
@@ -164,22 +236,24 @@ __global__ __launch_bounds__(NTH) void inv_lift_kernel(const float* __restrict__
     len_full = max(0, t_hi - tlo_full + 1) * m.Wt;
   }
   __syncthreads();
-  if (col0 >= ld) return;
 
-  int seg[VEC], ha[VEC], wb[VEC];  // ha = a + ph, wb = b + pw; seg already has -t_lo*Wt folded in
-  {
-    int n = fdiv(col0, divP);
-    const int rem = col0 - n * Pc;
+  int seg[VC], ha[VC], wb[VC];  // ha = a + ph, wb = b + pw; seg already has -t_lo*Wt folded in
+#pragma unroll
+  for (int e = 0; e < EG; ++e) {
+    const int c0 = cb + (e * NTH + tid) * CPT;
+    int n = fdiv(c0, divP);
+    const int rem = c0 - n * Pc;
     int a = fdiv(rem, divW);
     int b = rem - a * m.Wb;
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) {
+    for (int u = 0; u < CPT; ++u) {
+      const int q = e * CPT + u;
       const bool first = n == sp.n_first;
-      seg[e] = (first ? 0 : len_first + (n - sp.n_first - 1) * len_full) -
+      seg[q] = (first ? 0 : len_first + (n - sp.n_first - 1) * len_full) -
                (first ? tlo_first : tlo_full) * m.Wt;
-      ha[e] = a + m.ph;
-      wb[e] = b + m.pw;
-      if (col0 + e >= ce) ha[e] = -1;  // padding column
+      ha[q] = a + m.ph;
+      wb[q] = b + m.pw;
+      if (c0 + u >= ce) ha[q] = -1;  // padding column
       if (++b == m.Wb) {
         b = 0;
         if (++a == m.Ha) {
@@ -192,17 +266,22 @@ __global__ __launch_bounds__(NTH) void inv_lift_kernel(const float* __restrict__
   const long long row0 = (long long)o * m.Ki * m.Kj;
   for (int i = 0; i < m.Ki; ++i) {
     for (int j = 0; j < m.Kj; ++j) {
-      float v[VEC];
+      float v[VC];
 #pragma unroll
-      for (int e = 0; e < VEC; ++e) {
+      for (int q = 0; q < VC; ++q) {
         // a = r*sh + i - ph,  b = c*sw + j - pw
-        const int hr = ha[e] - i, wc = wb[e] - j;
+        const int hr = ha[q] - i, wc = wb[q] - j;
         const int r = fdiv(max(hr, 0), divSh), c = fdiv(max(wc, 0), divSw);
         const bool ok = hr >= 0 && wc >= 0 && r * m.sh == hr && c * m.sw == wc && r < m.Ht && c < m.Wt;
-        const float t = tile[ok ? seg[e] + r * m.Wt + c : 0];
-        v[e] = ok ? t : 0.0f;
+        const float t = tile[ok ? seg[q] + r * m.Wt + c : 0];
+        v[q] = ok ? t : 0.0f;
       }
-      store_vec<BF16>(drt, (row0 + i * m.Kj + j) * ld + col0, v);
+      const long long rbase = (row0 + i * m.Kj + j) * ld;
+#pragma unroll
+      for (int e = 0; e < EG; ++e) {
+        const int c0 = cb + (e * NTH + tid) * CPT;
+        if (c0 < ld) store_run<BF16>(drt, rbase + c0, &v[e * CPT]);
+      }
     }
   }
 }
@@ -316,12 +395,13 @@ __global__ __launch_bounds__(TPB) void inv_lift_direct_kernel(const float* __res
 inline long long lower_lds_floats(const WinMap& m, int ncb) {
   const long long Pc = (long long)m.Ha * m.Wb;
   const long long T = (ncb - 1) / Pc + 2, A = (ncb - 1) / m.Wb + 2;
-  const long long full = (long long)m.Ht * m.Wt;
+  const long long Wrow = (long long)((m.Wt + m.sw - 1) / m.sw) * m.sw;  // de-interleaved LDS row
+  const long long full = (long long)m.Ht * Wrow;
   // a run of A_t grid rows inside one image needs (A_t - 1)*sh + Ki tensor rows; with the A rows
   // split over t <= T images that is (A - t)*sh + t*Ki, largest at t = 1 or t = T
   const long long r1 = (A - 1) * m.sh + m.Ki;
   const long long rT = (A > T ? A - T : 0) * m.sh + T * m.Ki;
-  const long long by_rows = (r1 > rT ? r1 : rT) * m.Wt;
+  const long long by_rows = (r1 > rT ? r1 : rT) * Wrow;
   return T * full < by_rows ? T * full : by_rows;
 }
 inline long long inv_lift_lds_floats(const WinMap& m, int ncb) {
@@ -331,17 +411,19 @@ inline long long inv_lift_lds_floats(const WinMap& m, int ncb) {
   const long long by_rows = ((A + T * (m.Ki - 1)) / m.sh + 2 * T) * m.Wt;
   return T * full < by_rows ? T * full : by_rows;
 }
-// Threads per workgroup for the staged kernels: prefer 256 with <= 32 KiB of LDS (keeps several
-// workgroups per CU), then smaller groups, then anything up to 64 KiB; 0 = does not fit.
+// Columns per thread (workgroups are 256 threads) for the staged kernels: the most columns
+// whose staging area fits 32 KiB (several workgroups per CU), else the most that fit 64 KiB;
+// 0 = does not fit.  bf16 output packs two columns per lane, so it needs an even count.
 template <typename F>
-inline int pick_threads(const WinMap& m, F lds_floats, long long* lds_bytes) {
-  const int cand[3] = {256, 128, 64};
+inline int pick_cols(const WinMap& m, F lds_floats, int bf16, long long* lds_bytes) {
+  const int cand[3] = {4, 2, 1};
   for (long long cap : {32768LL, 65536LL})
-    for (int nth : cand) {
-      const long long b = lds_floats(m, nth * VEC) * 4;
+    for (int vc : cand) {
+      if (bf16 && vc < 2) continue;
+      const long long b = lds_floats(m, TPB * vc) * 4;
       if (b <= cap) {
         *lds_bytes = b;
-        return nth;
+        return vc;
       }
     }
   return 0;
@@ -380,21 +462,20 @@ int launch_lower(const float* x, void* dt, long long ld, int nimg, int C, const 
   const FastDiv divP = make_fastdiv(m.Ha * m.Wb), divW = make_fastdiv(m.Wb);
   const double bytes = 4.0 * nimg * C * m.Ht * m.Wt + (bf16 ? 2.0 : 4.0) * rows * ncols;
   long long lds = 0;
-  const int nth = pick_threads(m, lower_lds_floats, &lds);
+  const int vc = pick_cols(m, lower_lds_floats, bf16, &lds);
   dim3 sgrid;
-  if (nth && chan_grid(C, ld, nth * VEC, &sgrid)) {
+  if (vc && chan_grid(C, ld, TPB * vc, &sgrid)) {
     ProfScope ps(bf16 ? "lower_kernel<true>" : "lower_kernel<false>", 0.0, bytes, st);
-#define CCT_LAUNCH_LOWER(BF, NTH)                                                              \
-  hipLaunchKernelGGL((lower_kernel<BF, NTH>), sgrid, dim3(NTH), (size_t)lds, st, x, dt, ld,     \
-                     (int)ncols, C, m, divP, divW)
+#define CCT_LAUNCH_LOWER(BF, VC)                                                               \
+  hipLaunchKernelGGL((lower_kernel<BF, VC>), sgrid, dim3(TPB), (size_t)lds, st, x, dt, ld,      \
+                     (int)ncols, C, m, divP, divW, make_fastdiv(m.Wt), make_fastdiv(m.sw))
     if (bf16) {
-      if (nth == 256) CCT_LAUNCH_LOWER(true, 256);
-      else if (nth == 128) CCT_LAUNCH_LOWER(true, 128);
-      else CCT_LAUNCH_LOWER(true, 64);
+      if (vc == 4) CCT_LAUNCH_LOWER(true, 4);
+      else CCT_LAUNCH_LOWER(true, 2);
     } else {
-      if (nth == 256) CCT_LAUNCH_LOWER(false, 256);
-      else if (nth == 128) CCT_LAUNCH_LOWER(false, 128);
-      else CCT_LAUNCH_LOWER(false, 64);
+      if (vc == 4) CCT_LAUNCH_LOWER(false, 4);
+      else if (vc == 2) CCT_LAUNCH_LOWER(false, 2);
+      else CCT_LAUNCH_LOWER(false, 1);
     }
 #undef CCT_LAUNCH_LOWER
     CCT_CHECK_LAUNCH();
@@ -423,21 +504,20 @@ int launch_inv_lift(const float* dy, void* drt, long long ld, int nimg, int O, c
   const FastDiv divSh = make_fastdiv(m.sh), divSw = make_fastdiv(m.sw);
   const double bytes = 4.0 * nimg * O * m.Ht * m.Wt + (bf16 ? 2.0 : 4.0) * rows * ncols;
   long long lds = 0;
-  const int nth = pick_threads(m, inv_lift_lds_floats, &lds);
+  const int vc = pick_cols(m, inv_lift_lds_floats, bf16, &lds);
   dim3 sgrid;
-  if (nth && chan_grid(O, ld, nth * VEC, &sgrid)) {
+  if (vc && chan_grid(O, ld, TPB * vc, &sgrid)) {
     ProfScope ps(bf16 ? "inv_lift_kernel<true>" : "inv_lift_kernel<false>", 0.0, bytes, st);
-#define CCT_LAUNCH_INV_LIFT(BF, NTH)                                                           \
-  hipLaunchKernelGGL((inv_lift_kernel<BF, NTH>), sgrid, dim3(NTH), (size_t)lds, st, dy, drt, ld, \
+#define CCT_LAUNCH_INV_LIFT(BF, VC)                                                            \
+  hipLaunchKernelGGL((inv_lift_kernel<BF, VC>), sgrid, dim3(TPB), (size_t)lds, st, dy, drt, ld,  \
                      (int)ncols, O, m, divP, divW, divSh, divSw)
     if (bf16) {
-      if (nth == 256) CCT_LAUNCH_INV_LIFT(true, 256);
-      else if (nth == 128) CCT_LAUNCH_INV_LIFT(true, 128);
-      else CCT_LAUNCH_INV_LIFT(true, 64);
+      if (vc == 4) CCT_LAUNCH_INV_LIFT(true, 4);
+      else CCT_LAUNCH_INV_LIFT(true, 2);
     } else {
-      if (nth == 256) CCT_LAUNCH_INV_LIFT(false, 256);
-      else if (nth == 128) CCT_LAUNCH_INV_LIFT(false, 128);
-      else CCT_LAUNCH_INV_LIFT(false, 64);
+      if (vc == 4) CCT_LAUNCH_INV_LIFT(false, 4);
+      else if (vc == 2) CCT_LAUNCH_INV_LIFT(false, 2);
+      else CCT_LAUNCH_INV_LIFT(false, 1);
     }
 #undef CCT_LAUNCH_INV_LIFT
     CCT_CHECK_LAUNCH();
