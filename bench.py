@@ -33,7 +33,7 @@ def parse():
     ap.add_argument("--lowering", type=int, default=0, help="0 = auto (default), 1..3 = force")
     ap.add_argument("--chunk", type=int, default=0, help="images per chunk (0 = library default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-images", type=int, default=16)
+    ap.add_argument("--cpu-sample-images", type=int, default=64)
     ap.add_argument("--per-kernel", action="store_true", help="also print the per-kernel table")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run one plain 1 GiB device copy (reference row for rocprofv3 --pmc "

@@ -14,6 +14,9 @@ int last_hip_error_value();
 namespace {
 
 constexpr long long kAlign = 256;
+// Rows of the lowered matrices are padded to a multiple of this many columns (zero filled), so
+// that the GEMM can read whole 128- or 256-column tiles without guards.
+constexpr long long kLdAlign = 256;
 constexpr int kIntMax = 2147483647;
 // Default chunk budget for the lowered buffers of one chunk (the caller can pass a larger or
 // smaller workspace to change it).
@@ -95,7 +98,7 @@ bool make_layout(const cct_conv_desc_t& d, int pass, int type, const Geom& g, lo
   if ((long long)d.C * g.DKi * g.DKj >= kIntMax || (long long)d.O * g.RKi * g.RKj >= kIntMax)
     return false;
   const int es = esize(d);
-  L->ld = align_up(ncols, 64);
+  L->ld = align_up(ncols, kLdAlign);
   long long off = 0;
   auto take = [&](long long bytes, long long* o, long long* b) {
     *o = off;
@@ -160,8 +163,8 @@ bool type_supported(const cct_conv_desc_t& d, int pass, int type) {
 // this library's own kernels (sustained streaming rate of the index-map kernels, sustained
 // fp32 MFMA rate of the GEMM at large tiles).
 // ---------------------------------------------------------------------------------------
-constexpr double kStreamBytesPerSec = 3.0e12;
-constexpr double kGemmFlopsPerSec = 90.0e12;
+constexpr double kStreamBytesPerSec = 4.0e12;
+constexpr double kGemmFlopsPerSec = 110.0e12;
 constexpr double kLaunchSec = 4.0e-6;
 
 double model_cost(const cct_conv_desc_t& d, int pass, int type) {
@@ -332,7 +335,7 @@ int cct_lowered_ld(const cct_conv_desc_t* desc, cct_lowering_t lowering, int64_t
   const Geom g = make_geom(*desc, lowering);
   const long long ncols = (long long)desc->N * g.Pc;
   if (ncols >= kIntMax - 256) return CCT_EUNSUPPORTED;
-  *ld = align_up(ncols, 64);
+  *ld = align_up(ncols, kLdAlign);
   return CCT_OK;
 }
 
@@ -389,7 +392,7 @@ int cct_lower(const cct_conv_desc_t* desc, cct_lowering_t lowering, const float*
   const Geom g = make_geom(*desc, lowering);
   const long long ncols = (long long)desc->N * g.Pc;
   if (ncols >= kIntMax - 256) return CCT_EUNSUPPORTED;
-  return launch_lower(x, dhat, align_up(ncols, 64), desc->N, desc->C, g.lower, 0,
+  return launch_lower(x, dhat, align_up(ncols, kLdAlign), desc->N, desc->C, g.lower, 0,
                       (hipStream_t)hip_stream);
 }
 

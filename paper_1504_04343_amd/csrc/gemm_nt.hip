@@ -169,19 +169,65 @@ __global__ __launch_bounds__(NT) void gemm_nt_f32(GemmNT p, int tiles_m, int til
   const int a_lds = am * LDK + lane_hi * 4;
   const int b_lds = bn * LDK + lane_hi * 4;
 
+  // Main loop: same software pipeline as the forward GEMM (operand reads one step ahead, the
+  // next tile's LDS writes in the middle of the current tile, the barrier before the last step).
   const int ktiles = (col_end - col_begin + BK - 1) / BK;  // <= 0 for an empty split
+  constexpr int QS = BK / 8;
+  f32x4 a[2][WM], b[2][WN];
   if (ktiles > 0) {
     CCT_NT_LOAD(col_begin);
     CCT_NT_STORE(0);
   }
   __syncthreads();
+  if (ktiles > 1) CCT_NT_LOAD(col_begin + BK);
+  if (ktiles > 0) {
+#pragma unroll
+    for (int i = 0; i < WM; ++i) a[0][i] = *reinterpret_cast<const f32x4*>(&As[0][a_lds + i * 32 * LDK]);
+#pragma unroll
+    for (int j = 0; j < WN; ++j) b[0][j] = *reinterpret_cast<const f32x4*>(&Bs[0][b_lds + j * 32 * LDK]);
+  }
   for (int t = 0; t < ktiles; ++t) {
     const int buf = t & 1;
     const bool more = t + 1 < ktiles;
-    if (more) CCT_NT_LOAD(col_begin + (t + 1) * BK);
-    mma_stage_kcontig<BK, LDK, WM, WN>(&As[buf][a_lds], &Bs[buf][b_lds], acc);
-    if (more) CCT_NT_STORE(buf ^ 1);
-    __syncthreads();
+    const float* as = &As[buf][a_lds];
+    const float* bs = &Bs[buf][b_lds];
+#pragma unroll
+    for (int q = 0; q < QS; ++q) {
+      const int cur = q & 1, nxt = cur ^ 1;
+      if (q + 1 < QS) {
+#pragma unroll
+        for (int i = 0; i < WM; ++i)
+          a[nxt][i] = *reinterpret_cast<const f32x4*>(as + i * 32 * LDK + (q + 1) * 8);
+#pragma unroll
+        for (int j = 0; j < WN; ++j)
+          b[nxt][j] = *reinterpret_cast<const f32x4*>(bs + j * 32 * LDK + (q + 1) * 8);
+      } else {
+        __syncthreads();
+        if (more) {
+#pragma unroll
+          for (int i = 0; i < WM; ++i)
+            a[nxt][i] = *reinterpret_cast<const f32x4*>(&As[buf ^ 1][a_lds + i * 32 * LDK]);
+#pragma unroll
+          for (int j = 0; j < WN; ++j)
+            b[nxt][j] = *reinterpret_cast<const f32x4*>(&Bs[buf ^ 1][b_lds + j * 32 * LDK]);
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+#pragma unroll
+        for (int i = 0; i < WM; ++i)
+#pragma unroll
+          for (int j = 0; j < WN; ++j)
+            acc[i][j] =
+                __builtin_amdgcn_mfma_f32_32x32x2f32(a[cur][i][e], b[cur][j][e], acc[i][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      if (q == QS / 2 - 1 && more) {
+        CCT_NT_STORE(buf ^ 1);
+        if (t + 2 < ktiles) CCT_NT_LOAD(col_begin + (t + 2) * BK);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
   }
 #undef CCT_NT_LOAD
 #undef CCT_NT_STORE

@@ -50,8 +50,12 @@ __global__ __launch_bounds__(NT) void gemm_tn_f32(GemmTN p, int tiles_m, int til
   // contiguous run of column tiles and let the M tiles of one column tile follow each other on
   // the same XCD: the B tile they share is then fetched from HBM once per XCD L2.
   int bid = blockIdx.x;
-  const int total = tiles_m * tiles_n;
-  if (total % 8 == 0) bid = (bid & 7) * (total >> 3) + (bid >> 3);
+  {
+    const int total = tiles_m * tiles_n;
+    const int per = total >> 3, rem = total & 7;
+    const int xcd = bid & 7, slot = bid >> 3;
+    bid = xcd * per + min(xcd, rem) + slot;  // XCD x owns per + (x < rem) consecutive tiles
+  }
   const int tile_n = bid / tiles_m;
   const int tile_m = bid - tile_n * tiles_m;
   const int g = blockIdx.y;
@@ -73,25 +77,25 @@ __global__ __launch_bounds__(NT) void gemm_tn_f32(GemmTN p, int tiles_m, int til
   const long long a_step = (long long)BK * p.Mpad;
   const long long b_step = (long long)BK * p.b_ks;
 
+  // vector path: per-thread (row, 16-byte column group) of each 256-thread slab of the tile.
+  // Columns need no guard: rows of a lowered matrix are padded to a multiple of 256 columns.
   gptr_f32 b_src[BVEC ? B_IT : 1];
   int b_dst[BVEC ? B_IT : 1];
   int b_k[BVEC ? B_IT : 1];
-  bool b_colok[BVEC ? B_IT : 1];
-  gptr_f32 bs_src = nullptr;  // scalar path
-  bool bs_ok = false;
-  int bs_k0 = 0, bs_n = 0;
   if (BVEC) {
 #pragma unroll
     for (int it = 0; it < B_IT; ++it) {
       const int v = tid + it * NT;
       const int k = v / (BN / 4), n4 = v % (BN / 4);
-      const int col = n0 + n4 * 4;
       b_k[it] = k;
-      b_colok[it] = col < p.b_ld_guard;
-      b_src[it] = Bg + (long long)k * p.b_ks + col;
+      b_src[it] = Bg + (long long)k * p.b_ks + n0 + n4 * 4;
       b_dst[it] = k * BN + n4 * 4;
     }
-  } else {
+  }
+  gptr_f32 bs_src = nullptr;  // scalar path
+  bool bs_ok = false;
+  int bs_k0 = 0, bs_n = 0;
+  if (!BVEC) {
     bs_n = tid % BN;
     bs_k0 = tid / BN;
     const int col = n0 + bs_n;
@@ -113,8 +117,7 @@ __global__ __launch_bounds__(NT) void gemm_tn_f32(GemmTN p, int tiles_m, int til
     if (BVEC) {                                                                             \
       _Pragma("unroll") for (int it = 0; it < B_IT; ++it) {                                 \
         f32x4 val = {0.f, 0.f, 0.f, 0.f};                                                   \
-        if (b_colok[it] && (K0) + b_k[it] < p.Kdim)                                         \
-          val = *(gptr_f32x4)(b_src[it]);                                                   \
+        if ((K0) + b_k[it] < p.Kdim) val = *(gptr_f32x4)(b_src[it]);                        \
         rbv[it] = val;                                                                      \
         b_src[it] += b_step;                                                                \
       }                                                                                     \
@@ -158,17 +161,59 @@ __global__ __launch_bounds__(NT) void gemm_tn_f32(GemmTN p, int tiles_m, int til
   const int a_lds = lane_hi * BM + am;
   const int b_lds = lane_hi * BN + bn;
 
+  // Main loop, software pipelined so that no wave waits with an empty MFMA queue:
+  //  - the LDS operands of K-step s+1 are read before the MFMAs of step s are issued;
+  //  - the next tile's registers are written to the other LDS buffer in the middle of the
+  //    current tile (their global loads were issued half a tile earlier), and the loads of the
+  //    tile after that are issued right behind;
+  //  - the barrier that publishes the next tile sits before the LAST K-step, so that this step's
+  //    MFMAs cover the barrier skew and the latency of the next tile's first operand reads.
   const int ktiles = p.Kpad / BK;
   CCT_LOAD_TILE(0);
   CCT_STORE_TILE(0);
   __syncthreads();
+  if (ktiles > 1) CCT_LOAD_TILE(BK);
+  constexpr int KS = BK / 2;
+  float a[2][WM], b[2][WN];
+#pragma unroll
+  for (int i = 0; i < WM; ++i) a[0][i] = As[0][a_lds + i * 32];
+#pragma unroll
+  for (int j = 0; j < WN; ++j) b[0][j] = Bs[0][b_lds + j * 32];
   for (int t = 0; t < ktiles; ++t) {
     const int buf = t & 1;
     const bool more = t + 1 < ktiles;
-    if (more) CCT_LOAD_TILE((t + 1) * BK);
-    mma_stage<BK, BM, BN, WM, WN>(&As[buf][a_lds], &Bs[buf][b_lds], acc);
-    if (more) CCT_STORE_TILE(buf ^ 1);
-    __syncthreads();
+    const float* as = &As[buf][a_lds];
+    const float* bs = &Bs[buf][b_lds];
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      const int cur = s & 1, nxt = cur ^ 1;
+      if (s + 1 < KS) {
+#pragma unroll
+        for (int i = 0; i < WM; ++i) a[nxt][i] = as[(s + 1) * 2 * BM + i * 32];
+#pragma unroll
+        for (int j = 0; j < WN; ++j) b[nxt][j] = bs[(s + 1) * 2 * BN + j * 32];
+      } else {
+        __syncthreads();
+        if (more) {
+#pragma unroll
+          for (int i = 0; i < WM; ++i) a[nxt][i] = As[buf ^ 1][a_lds + i * 32];
+#pragma unroll
+          for (int j = 0; j < WN; ++j) b[nxt][j] = Bs[buf ^ 1][b_lds + j * 32];
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int i = 0; i < WM; ++i)
+#pragma unroll
+        for (int j = 0; j < WN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[cur][i], b[cur][j], acc[i][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      if (s == KS / 2 - 1 && more) {
+        CCT_STORE_TILE(buf ^ 1);
+        if (t + 2 < ktiles) CCT_LOAD_TILE((t + 2) * BK);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
   }
 #undef CCT_LOAD_TILE
 #undef CCT_STORE_TILE
@@ -341,8 +386,10 @@ int launch_f32(const GemmTN& p, hipStream_t st) {
   const long long blocks = (long long)tiles_m * tiles_n;
   if (blocks <= 0 || blocks >= 2147483647LL || p.G > 65535) return CCT_EUNSUPPORTED;
   const bool plainB = p.bmap.P == 2147483647;
+  // vector path: plain 16-byte aligned rows, padded so that a whole column tile can be read
   const bool vec = plainB && (p.b_ks % 4 == 0) && (p.b_gs % 4 == 0) &&
-                   (reinterpret_cast<uintptr_t>(p.B) % 16 == 0);
+                   (reinterpret_cast<uintptr_t>(p.B) % 16 == 0) && p.b_ld_guard % BN == 0 &&
+                   p.b_ld_guard >= p.Ncols && p.b_ks >= p.b_ld_guard;
   dim3 grid((unsigned)blocks, (unsigned)p.G);
   char name[96];
   snprintf(name, sizeof(name), "gemm_tn_f32<%d, %d, %d, %d, %d, %s>", BM, BN, BK, WM, WN,
@@ -383,9 +430,11 @@ int launch_bf16(const GemmTN& p, hipStream_t st) {
 }  // namespace
 
 // One tile family for now: M tiles of 64, 96 or 128 rows by 128 columns.
+// Tile family: M tiles of 64, 96 or 128 rows by 128 columns.  (256-column tiles were measured
+// and bring nothing at the register budget they need.)
 void gemm_tn_tile(int M, int /*Ncols*/, int* BM, int* BN, int* BK) {
-  *BN = 128;
   *BK = 16;
+  *BN = 128;
   if (M <= 64)
     *BM = 64;
   else if (M % 128 != 0 && M % 96 == 0)

@@ -43,36 +43,55 @@ __global__ __launch_bounds__(TPB) void pack_kernel(const float* __restrict__ w, 
   store_elem<BF16>(pack, t, v);
 }
 
-// dw = sum over split-K partials, in split order (deterministic), mapped back to O x Cg x K x K.
+// dw = sum over split-K partials, mapped back to O x Cg x K x K.  A workgroup owns 64 outputs;
+// its 4 thread groups each add up a quarter of the splits (in split order), and the four
+// quarter sums are combined in a fixed order: the result is bit-reproducible run to run.
 __global__ __launch_bounds__(TPB) void reduce_dw_kernel(const float* __restrict__ part,
                                                         float* __restrict__ dw, int S, PackDesc d,
                                                         int accumulate) {
+  __shared__ float red[4][64];
   const int nrho = d.Og * d.RKi * d.RKj, ndelta = d.Cg * d.DKi * d.DKj;
   const long long per_group = (long long)nrho * ndelta;
   const long long total = per_group * d.G;
-  const long long t = (long long)blockIdx.x * TPB + threadIdx.x;
-  if (t >= total) return;
-  const int q = (int)(t / per_group);
-  const long long e = t - q * per_group;
-  const int rho = (int)(e / ndelta), delta = (int)(e % ndelta);
+  const int lane = threadIdx.x & 63, slice = threadIdx.x >> 6;
+  const long long t = (long long)blockIdx.x * 64 + lane;
+  const int per = (S + 3) / 4;
+  const int s0 = slice * per, s1 = min(S, s0 + per);
   float acc = 0.0f;
-  for (int s = 0; s < S; ++s) acc += part[(long long)s * total + t];
-  const long long wi = weight_index(d, q, rho, delta);
-  dw[wi] = accumulate ? dw[wi] + acc : acc;
+  if (t < total) {
+    const float* src = part + t;
+    int sidx = s0;
+    for (; sidx + 8 <= s1; sidx += 8) {
+      float v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = src[(long long)(sidx + u) * total];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) acc += v[u];
+    }
+    for (; sidx < s1; ++sidx) acc += src[(long long)sidx * total];
+  }
+  red[slice][lane] = acc;
+  __syncthreads();
+  if (slice == 0 && t < total) {
+    const float sum = ((red[0][lane] + red[1][lane]) + red[2][lane]) + red[3][lane];
+    const int q = (int)(t / per_group);
+    const long long e = t - q * per_group;
+    const int rho = (int)(e / ndelta), delta = (int)(e % ndelta);
+    const long long wi = weight_index(d, q, rho, delta);
+    dw[wi] = accumulate ? dw[wi] + sum : sum;
+  }
 }
 
-// dbias, stage 1: block (o, blk) sums a slice of the N*P values of channel o.
+// dbias, stage 1: block (o, blk) sums the planes dy[n, o, :, :] of the images n = blk, blk+nblk, ...
 __global__ __launch_bounds__(TPB) void dbias_stage1(const float* __restrict__ dy,
                                                     float* __restrict__ scratch, int N, int O, int P,
                                                     int nblk) {
   __shared__ float red[TPB];
   const int o = blockIdx.x / nblk, blk = blockIdx.x % nblk;
-  const long long total = (long long)N * P;
   float acc = 0.0f;
-  for (long long t = (long long)blk * TPB + threadIdx.x; t < total; t += (long long)nblk * TPB) {
-    const long long n = t / P;
-    const int pix = (int)(t - n * P);
-    acc += dy[(n * O + o) * P + pix];
+  for (int n = blk; n < N; n += nblk) {
+    const float* src = dy + ((long long)n * O + o) * P;
+    for (int t = threadIdx.x; t < P; t += TPB) acc += src[t];
   }
   red[threadIdx.x] = acc;
   __syncthreads();
@@ -111,7 +130,7 @@ int launch_pack_kernel_matrix(const float* w, void* pack, const PackDesc& d, hip
 int launch_reduce_dw(const float* part, float* dw, int S, const PackDesc& d, int accumulate,
                      hipStream_t st) {
   const long long total = (long long)d.Og * d.RKi * d.RKj * d.Cg * d.DKi * d.DKj * d.G;
-  const long long blocks = (total + TPB - 1) / TPB;
+  const long long blocks = (total + 63) / 64;
   if (!grid_ok(blocks)) return CCT_EUNSUPPORTED;
   ProfScope ps("reduce_dw_kernel", 0.0, 4.0 * total * (S + 1), st);
   hipLaunchKernelGGL(reduce_dw_kernel, dim3((unsigned)blocks), dim3(TPB), 0, st, part, dw, S, d,

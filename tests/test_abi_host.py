@@ -53,7 +53,7 @@ def test_output_dims_and_lowered_shapes_match_golden(B):
             assert rows % N == 0                      # Sec. 2.2: b times larger
             got += [rows // N, cols]
             assert rcols == (O // g) * K ** (t - 1)
-            assert B.cct_lowered_ld(d, t) >= rows and B.cct_lowered_ld(d, t) % 64 == 0
+            assert B.cct_lowered_ld(d, t) >= rows and B.cct_lowered_ld(d, t) % 256 == 0
         assert got == want
 
 
