@@ -23,6 +23,21 @@ PEAK_BF16_MFMA_TFLOPS = 2500.0
 PEAK_HBM_GBS = 8000.0
 
 
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic_caffenet_b256_f32.txt")
+
+
+def measured_traffic(kernel):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary (None if absent)."""
+    try:
+        for line in open(TRAFFIC_FILE):
+            f = line.rstrip("\n").split("\t")
+            if not line.startswith("#") and len(f) >= 2 and f[0] == kernel:
+                return int(f[1])
+    except OSError:
+        pass
+    return None
+
+
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -56,7 +71,7 @@ def main():
     if args.copy_calibration:
         src = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")   # 1 GiB
         dst = torch.empty_like(src)
-        dst.copy_(src)
+        B.cct_calibration_copy(src, dst)
         torch.cuda.synchronize()
         del src, dst
     prec = B.PREC_F32 if args.precision == "f32" else B.PREC_BF16_IN_F32_ACC
@@ -120,7 +135,10 @@ def main():
     peak = PEAK_FP32_MFMA_TFLOPS if args.precision == "f32" else PEAK_BF16_MFMA_TFLOPS
     roofline = {
         "bound": "mfma", "kernel": dom["name"], "achieved": round(achieved_tflops, 2), "peak": peak,
-        "unit": "TFLOP/s", "frac": round(achieved_tflops / peak, 4), "traffic": None,
+        "unit": "TFLOP/s", "frac": round(achieved_tflops / peak, 4),
+        "traffic": measured_traffic(dom["name"]) if (args.precision == "f32" and args.batch == 256 and
+                                                     not args.lowering and not args.chunk) else None,
+        "algorithmic_bytes_per_launch": int(dom["bytes"] / dom["launches"]),
         "avg_launch_ms": round(avg_ms, 4), "launches_per_step": dom["launches"] / args.steps,
         "share_of_step_kernel_time": round(dom["total_ms"] / total_kernel_ms, 3),
     }

@@ -204,6 +204,15 @@ typedef struct {
 int cct_profile_enable(int on);
 int cct_profile_read(cct_profile_entry_t* entries, int32_t max_entries, int32_t* n);
 
+/*
+ * Measurement aid: a plain device-to-device copy of `bytes` bytes (multiple of 16, both
+ * pointers 16-byte aligned, device memory, must not overlap) done by one kernel
+ * ("calibration_copy_kernel") that reads every byte once and writes every byte once.  A
+ * profiler run that includes it gives the scale between a hardware counter (FETCH_SIZE,
+ * WRITE_SIZE) and real bytes.
+ */
+int cct_calibration_copy(const void* src, void* dst, size_t bytes, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -30,7 +30,7 @@ EXPORTS = [
     "cct_pick_lowering", "cct_lowering_cost", "cct_conv_workspace_bytes",
     "cct_conv_workspace_bytes_for_chunk", "cct_conv_forward", "cct_conv_backward_data",
     "cct_conv_backward_weights", "cct_lowered_ld", "cct_lower", "cct_profile_enable",
-    "cct_profile_read",
+    "cct_profile_read", "cct_calibration_copy",
 ]
 
 
@@ -72,6 +72,7 @@ class ProfileEntry(ctypes.Structure):
                 ("flops", ctypes.c_double), ("bytes", ctypes.c_double)]
 
 
+_lib.cct_calibration_copy.argtypes = [_vp, _vp, _sz, _vp]
 _lib.cct_profile_enable.argtypes = [ctypes.c_int]
 _lib.cct_profile_read.argtypes = [ctypes.POINTER(ProfileEntry), _i32, ctypes.POINTER(_i32)]
 for _name in EXPORTS:
@@ -159,6 +160,15 @@ def cct_profile_read(max_entries: int = 64):
     return [dict(name=arr[i].name.decode(), launches=int(arr[i].launches),
                  total_ms=float(arr[i].total_ms), flops=float(arr[i].flops),
                  bytes=float(arr[i].bytes)) for i in range(n.value)]
+
+
+def cct_calibration_copy(src, dst) -> None:
+    """Plain device copy of src into dst (same-size contiguous GPU tensors)."""
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes or not (src.is_cuda and dst.is_cuda):
+        raise ValueError("src and dst must be GPU tensors of the same byte size")
+    _check(_lib.cct_calibration_copy(src.data_ptr(), dst.data_ptr(), nbytes, _stream()),
+           "cct_calibration_copy")
 
 
 # ---- device entry points -----------------------------------------------------------------

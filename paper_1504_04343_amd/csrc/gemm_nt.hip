@@ -80,10 +80,21 @@ __global__ __launch_bounds__(NT) void gemm_nt_f32(GemmNT p, int tiles_m, int til
   const int wave = tid >> 6;
   const int wave_m = wave / WAVES_N, wave_n = wave % WAVES_N;
 
-  const int tile = blockIdx.x;
+  // Workgroup order: consecutive ids go round-robin over the 8 XCDs, so give every XCD a
+  // contiguous run of (split, tile) pairs with the tile index fastest: all tiles of one split
+  // read the same column range of A and B and then share it through that XCD's L2.
+  int bid = blockIdx.x;
+  {
+    const int total = tiles_m * tiles_n * p.S;
+    const int per = total >> 3, rem = total & 7;
+    const int xcd = bid & 7, slot = bid >> 3;
+    bid = xcd * per + min(xcd, rem) + slot;
+  }
+  const int ntiles = tiles_m * tiles_n;
+  const int s = bid / ntiles;
+  const int tile = bid - s * ntiles;
   const int tile_m = tile / tiles_n, tile_n = tile - tile_m * tiles_n;
-  const int s = blockIdx.y;
-  const int g = blockIdx.z;
+  const int g = blockIdx.y;
   const int m0 = tile_m * BM, n0 = tile_n * BN;
   const int col_begin = s * p.split_len;
   const int col_end = min(p.Ncols, col_begin + p.split_len);
@@ -253,14 +264,13 @@ int launch_f32(const GemmNT& p, hipStream_t st) {
   const int tiles_m = (p.M + BM - 1) / BM;
   const int tiles_n = (p.N + BN - 1) / BN;
   const long long tiles = (long long)tiles_m * tiles_n;
-  if (tiles <= 0 || tiles >= 2147483647LL || p.S < 1 || p.S > 65535 || p.G > 65535)
-    return CCT_EUNSUPPORTED;
+  if (tiles <= 0 || p.S < 1 || tiles * p.S >= 2147483647LL || p.G > 65535) return CCT_EUNSUPPORTED;
   if (p.split_len % BK) return CCT_EINVAL;
   // B must be a plain lowered matrix with 16-byte aligned rows (the lowering kernels write it so)
   if (p.b_ns % 4 || p.b_gs % 4 || reinterpret_cast<uintptr_t>(p.B) % 16) return CCT_EINVAL;
   const bool avec = p.amap.P == 2147483647 && p.a_ms % 4 == 0 && p.a_gs % 4 == 0 &&
                     reinterpret_cast<uintptr_t>(p.A) % 16 == 0;
-  dim3 grid((unsigned)tiles, (unsigned)p.S, (unsigned)p.G);
+  dim3 grid((unsigned)(tiles * p.S), (unsigned)p.G);
   char name[96];
   snprintf(name, sizeof(name), "gemm_nt_f32<%d, %d, %d, %d, %d, %s>", BM, BN, BK, WM, WN,
            avec ? "true" : "false");

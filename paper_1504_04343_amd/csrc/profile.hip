@@ -59,7 +59,31 @@ ProfScope::~ProfScope() {
 
 using namespace cct;
 
+namespace {
+// One 16-byte load and one 16-byte store per thread: the reference "plain copy of known size"
+// against which hardware-counter readings (FETCH_SIZE / WRITE_SIZE) are scaled.
+__global__ __launch_bounds__(256) void calibration_copy_kernel(const uint4* __restrict__ src,
+                                                               uint4* __restrict__ dst, size_t n) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) dst[i] = src[i];
+}
+}  // namespace
+
 extern "C" {
+
+int cct_calibration_copy(const void* src, void* dst, size_t bytes, void* hip_stream) {
+  if (!src || !dst || bytes == 0 || bytes % 16) return CCT_EINVAL;
+  if (reinterpret_cast<uintptr_t>(src) % 16 || reinterpret_cast<uintptr_t>(dst) % 16)
+    return CCT_EINVAL;
+  const size_t n = bytes / 16;
+  const size_t blocks = (n + 255) / 256;
+  if (blocks >= 2147483647ULL) return CCT_EUNSUPPORTED;
+  hipLaunchKernelGGL(calibration_copy_kernel, dim3((unsigned)blocks), dim3(256), 0,
+                     (hipStream_t)hip_stream, static_cast<const uint4*>(src),
+                     static_cast<uint4*>(dst), n);
+  CCT_CHECK_LAUNCH();
+  return CCT_OK;
+}
 
 int cct_profile_enable(int on) {
   std::lock_guard<std::mutex> lk(g_mu);

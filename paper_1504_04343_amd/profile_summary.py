@@ -3,8 +3,13 @@
 Usage:
   python -m paper_1504_04343_amd.profile_summary stats  <dir>/<prefix>_kernel_stats.csv
   python -m paper_1504_04343_amd.profile_summary pmc    <dir>/<prefix>_counter_collection.csv
+  python -m paper_1504_04343_amd.profile_summary traffic <FETCH_SIZE run>.csv <WRITE_SIZE run>.csv
 
 `stats` prints calls / average / total per kernel (from --kernel-trace --stats).
+`traffic` combines a --pmc FETCH_SIZE run and a --pmc WRITE_SIZE run of `bench.py
+--copy-calibration`: both counters are scaled by what they read for the 1 GiB
+`calibration_copy_kernel` (which moves exactly 1 GiB each way), and one line per kernel gives the
+scaled HBM bytes per dispatch (`name<TAB>bytes`), the format bench.py reads back.
 `pmc` prints, per kernel name, the per-dispatch average of every collected counter (from --pmc),
 plus derived figures when their inputs are present: MFMA utilisation
 (SQ_VALU_MFMA_BUSY_CYCLES over GRBM_GUI_ACTIVE x SIMDs, as rocprofv3's MfmaUtil defines it), and
@@ -20,7 +25,7 @@ XCDS = 8          # GRBM_GUI_ACTIVE is reported summed over the 8 XCDs
 
 
 def short(name):
-    name = name.replace("void ", "").replace("cct::(anonymous namespace)::", "")
+    name = name.replace("void ", "").replace("cct::", "").replace("(anonymous namespace)::", "")
     name = re.sub(r"\(.*$", "", name)
     return name[:60]
 
@@ -57,7 +62,38 @@ def pmc(path):
         print("%-60s dispatches=%d  %s  %s" % (k, n, "  ".join(extra), "  ".join(parts)))
 
 
+def per_dispatch(path, counter):
+    tot = collections.defaultdict(float)
+    disp = collections.defaultdict(set)
+    for r in csv.DictReader(open(path)):
+        if r["Counter_Name"] != counter:
+            continue
+        k = short(r["Kernel_Name"])
+        tot[k] += float(r["Counter_Value"])
+        disp[k].add(r["Dispatch_Id"])
+    return {k: tot[k] / len(disp[k]) for k in tot}, {k: len(disp[k]) for k in tot}
+
+
+def traffic(fetch_csv, write_csv):
+    fetch, nd = per_dispatch(fetch_csv, "FETCH_SIZE")      # KiB per dispatch
+    write, _ = per_dispatch(write_csv, "WRITE_SIZE")
+    cal = "calibration_copy_kernel"
+    if cal not in fetch or cal not in write:
+        sys.exit("no %s dispatch in the runs: use bench.py --copy-calibration" % cal)
+    gib_kib = float(1 << 20)
+    fs, ws = gib_kib / fetch[cal], gib_kib / write[cal]
+    print("# HBM traffic per dispatch = FETCH_SIZE*%.4f + WRITE_SIZE*%.4f KiB (scales from the 1 GiB "
+          "%s: FETCH_SIZE read %.0f KiB, WRITE_SIZE read %.0f KiB)" % (fs, ws, cal, fetch[cal], write[cal]))
+    print("# kernel<TAB>bytes_per_dispatch<TAB>dispatches<TAB>fetch_MiB_scaled<TAB>write_MiB_scaled")
+    for k in sorted(fetch, key=lambda k: -(fetch[k] * fs + write.get(k, 0.0) * ws)):
+        f, w = fetch[k] * fs, write.get(k, 0.0) * ws
+        print("%s\t%d\t%d\t%.1f\t%.1f" % (k, int((f + w) * 1024), nd[k], f / 1024, w / 1024))
+
+
 if __name__ == "__main__":
-    if len(sys.argv) != 3 or sys.argv[1] not in ("stats", "pmc"):
+    if len(sys.argv) == 4 and sys.argv[1] == "traffic":
+        traffic(sys.argv[2], sys.argv[3])
+    elif len(sys.argv) == 3 and sys.argv[1] in ("stats", "pmc"):
+        (stats if sys.argv[1] == "stats" else pmc)(sys.argv[2])
+    else:
         sys.exit(__doc__)
-    (stats if sys.argv[1] == "stats" else pmc)(sys.argv[2])
