@@ -77,8 +77,6 @@ def main():
     prec = B.PREC_F32 if args.precision == "f32" else B.PREC_BF16_IN_F32_ACC
     layers = synth.caffenet(args.batch)
     passes = [B.PASS_FORWARD, B.PASS_BACKWARD_DATA, B.PASS_BACKWARD_WEIGHTS]
-    if prec != B.PREC_F32:
-        passes = passes[:2]   # the bf16-operand variant covers forward and backward-data
 
     # ---- resident inputs -------------------------------------------------------------------
     state = []

@@ -148,7 +148,6 @@ bool make_layout(const cct_conv_desc_t& d, int pass, int type, const Geom& g, lo
 
 bool type_supported(const cct_conv_desc_t& d, int pass, int type) {
   if (type < CCT_LOWER_TYPE1 || type > CCT_LOWER_TYPE3) return false;
-  if (d.precision == CCT_PREC_BF16_IN_F32_ACC && pass == CCT_PASS_BACKWARD_WEIGHTS) return false;
   const Geom g = make_geom(d, type);
   Layout L;
   if (!make_layout(d, pass, type, g, 1, &L)) return false;

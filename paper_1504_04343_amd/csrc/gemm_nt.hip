@@ -259,6 +259,155 @@ __global__ __launch_bounds__(NT) void gemm_nt_f32(GemmNT p, int tiles_m, int til
   }
 }
 
+// bf16 operands (both plain lowered matrices written in bf16 by the lowering kernels), fp32
+// accumulate.  Same structure as the fp32 kernel; a lane feeds v_mfma_f32_32x32x8_bf16_1k with 4
+// consecutive reduction indices of its row, i.e. one 8-byte LDS read (lanes 32..63 take the
+// next 4), and LDS rows hold BK + 8 bf16 so that 16-byte writes stay aligned.
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+typedef const u32x4 __attribute__((address_space(1)))* gptr_u32x4;
+template <int BM, int BN, int BK, int WM, int WN>
+__global__ __launch_bounds__(NT) void gemm_nt_bf16(GemmNT p, int tiles_m, int tiles_n) {
+  constexpr int WAVES_N = BN / (32 * WN);
+  constexpr int WAVES_M = BM / (32 * WM);
+  static_assert(WAVES_M * WAVES_N == 4, "4 waves per workgroup");
+  static_assert(BK % 8 == 0, "BK");
+  constexpr int LDK = BK + 8;            // bf16 elements per LDS row
+  constexpr int KV = BK / 8;             // 16-byte vectors per tile row
+  constexpr int AV_IT = (BM * KV + NT - 1) / NT;
+  constexpr int BV_IT = (BN * KV + NT - 1) / NT;
+
+  __shared__ __attribute__((aligned(16))) unsigned short As[2][BM * LDK];
+  __shared__ __attribute__((aligned(16))) unsigned short Bs[2][BN * LDK];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int wave_m = wave / WAVES_N, wave_n = wave % WAVES_N;
+  int bid = blockIdx.x;
+  {
+    const int total = tiles_m * tiles_n * p.S;
+    const int per = total >> 3, rem = total & 7;
+    const int xcd = bid & 7, slot = bid >> 3;
+    bid = xcd * per + min(xcd, rem) + slot;
+  }
+  const int ntiles = tiles_m * tiles_n;
+  const int s = bid / ntiles;
+  const int tile = bid - s * ntiles;
+  const int tile_m = tile / tiles_n, tile_n = tile - tile_m * tiles_n;
+  const int g = blockIdx.y;
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+  const int col_begin = s * p.split_len;
+  const int col_end = min(p.Ncols, col_begin + p.split_len);
+
+  const unsigned short* A = reinterpret_cast<const unsigned short*>(p.A) + (long long)g * p.a_gs;
+  const unsigned short* B = reinterpret_cast<const unsigned short*>(p.B) + (long long)g * p.b_gs;
+  const unsigned short* a_src[AV_IT];
+  const unsigned short* b_src[BV_IT];
+  int a_dst[AV_IT], b_dst[BV_IT];
+#pragma unroll
+  for (int it = 0; it < AV_IT; ++it) {
+    const int v = min(tid + it * NT, BM * KV - 1);
+    const int row = v / KV, kv = v % KV;
+    a_src[it] = A + (long long)min(m0 + row, p.M - 1) * p.a_ms + col_begin + kv * 8;
+    a_dst[it] = row * LDK + kv * 8;
+  }
+#pragma unroll
+  for (int it = 0; it < BV_IT; ++it) {
+    const int v = min(tid + it * NT, BN * KV - 1);
+    const int row = v / KV, kv = v % KV;
+    b_src[it] = B + (long long)min(n0 + row, p.N - 1) * p.b_ns + col_begin + kv * 8;
+    b_dst[it] = row * LDK + kv * 8;
+  }
+  u32x4 ra[AV_IT], rb[BV_IT];
+
+  floatx16 acc[WM][WN];
+#pragma unroll
+  for (int i = 0; i < WM; ++i)
+#pragma unroll
+    for (int j = 0; j < WN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  const int lane_lo = lane & 31, lane_hi = lane >> 5;
+  const int am = wave_m * WM * 32 + lane_lo;
+  const int bn = wave_n * WN * 32 + lane_lo;
+  const int a_lds = am * LDK + lane_hi * 4;
+  const int b_lds = bn * LDK + lane_hi * 4;
+
+  const int ktiles = (col_end - col_begin + BK - 1) / BK;
+  for (int t = 0; t < ktiles; ++t) {
+#pragma unroll
+    for (int it = 0; it < AV_IT; ++it) {
+      ra[it] = *(gptr_u32x4)(a_src[it]);
+      a_src[it] += BK;
+    }
+#pragma unroll
+    for (int it = 0; it < BV_IT; ++it) {
+      rb[it] = *(gptr_u32x4)(b_src[it]);
+      b_src[it] += BK;
+    }
+    const int buf = t & 1;
+#pragma unroll
+    for (int it = 0; it < AV_IT; ++it) *reinterpret_cast<u32x4*>(&As[buf][a_dst[it]]) = ra[it];
+#pragma unroll
+    for (int it = 0; it < BV_IT; ++it) *reinterpret_cast<u32x4*>(&Bs[buf][b_dst[it]]) = rb[it];
+    __syncthreads();  // two buffers: the next iteration writes the other one
+#pragma unroll
+    for (int q = 0; q < BK / 8; ++q) {
+      shortx4 a[WM], b[WN];
+#pragma unroll
+      for (int i = 0; i < WM; ++i)
+        a[i] = *reinterpret_cast<const shortx4*>(&As[buf][a_lds + i * 32 * LDK + q * 8]);
+#pragma unroll
+      for (int j = 0; j < WN; ++j)
+        b[j] = *reinterpret_cast<const shortx4*>(&Bs[buf][b_lds + j * 32 * LDK + q * 8]);
+#pragma unroll
+      for (int i = 0; i < WM; ++i)
+#pragma unroll
+        for (int j = 0; j < WN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(a[i], b[j], acc[i][j], 0, 0, 0);
+    }
+  }
+
+  float* __restrict__ C = p.Cpart + ((long long)s * p.G + g) * p.M * p.N;
+#pragma unroll
+  for (int j = 0; j < WN; ++j) {
+    const int n = n0 + bn + j * 32;
+    if (n >= p.N) continue;
+#pragma unroll
+    for (int i = 0; i < WM; ++i) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m = m0 + wave_m * WM * 32 + i * 32 + (r >> 2) * 8 + lane_hi * 4 + (r & 3);
+        if (m < p.M) C[(long long)m * p.N + n] = acc[i][j][r];
+      }
+    }
+  }
+}
+
+template <int BM, int BN, int BK, int WM, int WN>
+int launch_bf16(const GemmNT& p, hipStream_t st) {
+  const int tiles_m = (p.M + BM - 1) / BM;
+  const int tiles_n = (p.N + BN - 1) / BN;
+  const long long tiles = (long long)tiles_m * tiles_n;
+  if (tiles <= 0 || p.S < 1 || tiles * p.S >= 2147483647LL || p.G > 65535) return CCT_EUNSUPPORTED;
+  if (p.split_len % BK) return CCT_EINVAL;
+  // both operands must be plain bf16 lowered matrices with 16-byte aligned rows
+  if (p.amap.P != 2147483647 || p.a_ms % 8 || p.a_gs % 8 || p.b_ns % 8 || p.b_gs % 8 ||
+      reinterpret_cast<uintptr_t>(p.A) % 16 || reinterpret_cast<uintptr_t>(p.B) % 16)
+    return CCT_EINVAL;
+  dim3 grid((unsigned)(tiles * p.S), (unsigned)p.G);
+  char name[96];
+  snprintf(name, sizeof(name), "gemm_nt_bf16<%d, %d, %d, %d, %d>", BM, BN, BK, WM, WN);
+  ProfScope ps(name, 2.0 * p.M * p.N * p.Ncols * p.G,
+               (2.0 * ((double)p.M * p.Ncols + (double)p.N * p.Ncols) + 4.0 * (double)p.M * p.N * p.S) *
+                   p.G,
+               st);
+  hipLaunchKernelGGL((gemm_nt_bf16<BM, BN, BK, WM, WN>), grid, dim3(NT), 0, st, p, tiles_m, tiles_n);
+  CCT_CHECK_LAUNCH();
+  return CCT_OK;
+}
+
 template <int BM, int BN, int BK, int WM, int WN>
 int launch_f32(const GemmNT& p, hipStream_t st) {
   const int tiles_m = (p.M + BM - 1) / BM;
@@ -301,9 +450,13 @@ void gemm_nt_tile(int M, int /*N*/, int* BM, int* BN, int* BK) {
 }
 
 int launch_gemm_nt(const GemmNT& p, hipStream_t st) {
-  if (p.bf16) return CCT_EUNSUPPORTED;
   int BM, BN, BK;
   gemm_nt_tile(p.M, p.N, &BM, &BN, &BK);
+  if (p.bf16) {
+    if (BM == 64) return launch_bf16<64, 128, 32, 1, 2>(p, st);
+    if (BM == 96) return launch_bf16<96, 128, 32, 3, 1>(p, st);
+    return launch_bf16<128, 128, 32, 2, 2>(p, st);
+  }
   if (BM == 64) return launch_f32<64, 128, 32, 1, 2>(p, st);
   if (BM == 96) return launch_f32<96, 128, 32, 3, 1>(p, st);
   return launch_f32<128, 128, 32, 2, 2>(p, st);

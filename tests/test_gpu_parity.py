@@ -170,6 +170,27 @@ def test_bf16_variant(B, L, lowering):
     assert rel_err(got, oracle.conv_forward(od, x, w, b)) <= TOL_BF16
     got = gpu_backward_data(B, L, w, dy, lowering, B.PREC_BF16_IN_F32_ACC)
     assert rel_err(got, oracle.conv_backward_data(od, w, dy)) <= TOL_BF16
+    dw_want, db_want = oracle.conv_backward_weights(od, x, dy)
+    dw, db = gpu_backward_weights(B, L, x, dy, lowering, B.PREC_BF16_IN_F32_ACC)
+    assert rel_err(dw, dw_want) <= TOL_BF16
+    assert rel_err(db, db_want) <= TOL_F32          # dbias is summed from the fp32 dy
+
+
+# ------------------------------------------------------------------ trade-off sweep shapes (Appendix A)
+SWEEP = [L.with_batch(4) for L in synth.tradeoff_sweep()]
+
+
+@pytest.mark.parametrize("L", SWEEP, ids=[L.name for L in SWEEP])
+def test_tradeoff_sweep_shapes_all_layouts(B, L):
+    """The #input/#output-channel sweep of the lowering trade-off study, at a small batch: every
+    layout and the selector's pick give the oracle's result."""
+    x, w, b, _ = inputs(L, 2)
+    idx = synth.sample_indices(L.N * L.O * L.Hout * L.Wout, 3000, 4)
+    want = oracle.conv_forward_at(odims(oracle, L), x, w, b, idx)
+    scale = np.abs(want).max()
+    for lowering in (1, 2, 3, B.LOWER_AUTO):
+        got = gpu_forward(B, L, x, w, b, lowering).ravel()[idx]
+        assert np.abs(got - want).max() / scale <= TOL_F32, lowering
 
 
 # ------------------------------------------------------------------ error paths on the device entry points
