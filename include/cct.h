@@ -46,12 +46,16 @@
 extern "C" {
 #endif
 
-/* Lowering layout, Sec. 2.1.  AUTO lets cct_pick_lowering decide. */
+/* Lowering layout, Sec. 2.1.  AUTO lets cct_pick_lowering decide (it may also pick FUSED). */
 typedef enum {
   CCT_LOWER_AUTO = 0,
   CCT_LOWER_TYPE1 = 1, /* D^ rows = output positions, cols = (ci,i,j); trivial lifting      */
   CCT_LOWER_TYPE2 = 2, /* D^ rows = (input row, output col), cols = (ci,j); lift sums K rows */
-  CCT_LOWER_TYPE3 = 3  /* D^ rows = input positions, cols = ci; lift sums K*K entries        */
+  CCT_LOWER_TYPE3 = 3, /* D^ rows = input positions, cols = ci; lift sums K*K entries        */
+  CCT_LOWER_FUSED = 4  /* the fusion of Sec. 2.1 ("Fusion"): lowering, multiply and lifting in
+                          one kernel, D^ (Type-1 layout) is never materialised: the GEMM gathers
+                          its operand tiles from x.  Forward pass, fp32 only; other passes /
+                          precisions return CCT_EUNSUPPORTED when it is requested explicitly.   */
 } cct_lowering_t;
 
 typedef enum {
@@ -101,7 +105,7 @@ int cct_conv_output_dims(const cct_conv_desc_t* desc, int32_t* Hout, int32_t* Wo
  *   Type 1: rows = N*Hout*Wout, cols = Cg*K*K, rcols = Og
  *   Type 2: rows = N*H*Wout,    cols = Cg*K,   rcols = Og*K
  *   Type 3: rows = N*H*W,       cols = Cg,     rcols = Og*K*K
- * `lowering` must be TYPE1..TYPE3.  Host only.
+ * `lowering` must be TYPE1..TYPE3 (FUSED has no materialised matrices).  Host only.
  */
 int cct_lowered_shape(const cct_conv_desc_t* desc, cct_lowering_t lowering, int64_t* rows,
                       int64_t* cols, int64_t* rcols);

@@ -20,7 +20,7 @@ if not os.path.exists(LIB_PATH):
 
 _lib = ctypes.CDLL(LIB_PATH)
 
-LOWER_AUTO, LOWER_TYPE1, LOWER_TYPE2, LOWER_TYPE3 = 0, 1, 2, 3
+LOWER_AUTO, LOWER_TYPE1, LOWER_TYPE2, LOWER_TYPE3, LOWER_FUSED = 0, 1, 2, 3, 4
 PREC_F32, PREC_BF16_IN_F32_ACC = 0, 1
 PASS_FORWARD, PASS_BACKWARD_DATA, PASS_BACKWARD_WEIGHTS = 0, 1, 2
 OK, EINVAL, EWORKSPACE, EUNSUPPORTED, EHIP = 0, -1, -2, -3, -4

@@ -32,7 +32,7 @@ bool desc_ok(const cct_conv_desc_t* d) {
   if (d->stride < 1 || d->pad < 0 || d->groups < 1) return false;
   if (d->C % d->groups || d->O % d->groups) return false;
   if ((long long)d->H + 2LL * d->pad < d->K || (long long)d->W + 2LL * d->pad < d->K) return false;
-  if (d->lowering < CCT_LOWER_AUTO || d->lowering > CCT_LOWER_TYPE3) return false;
+  if (d->lowering < CCT_LOWER_AUTO || d->lowering > CCT_LOWER_FUSED) return false;
   if (d->precision != CCT_PREC_F32 && d->precision != CCT_PREC_BF16_IN_F32_ACC) return false;
   return true;
 }
@@ -55,7 +55,7 @@ Geom make_geom(const cct_conv_desc_t& d, int type) {
   g.Cg = d.C / d.groups;
   g.Og = d.O / d.groups;
   const int K = d.K, s = d.stride, p = d.pad;
-  if (type == CCT_LOWER_TYPE1) {
+  if (type == CCT_LOWER_TYPE1 || type == CCT_LOWER_FUSED) {
     g.lower = WinMap{K, K, s, p, s, p, g.Hout, g.Wout, d.H, d.W};
     g.lift = WinMap{1, 1, 1, 0, 1, 0, g.Hout, g.Wout, g.Hout, g.Wout};
     g.RKi = 1; g.RKj = 1; g.DKi = K; g.DKj = K;
@@ -113,8 +113,10 @@ bool make_layout(const cct_conv_desc_t& d, int pass, int type, const Geom& g, lo
     L->Mpad = (int)align_up(g.Mr, BM);
     L->Kpad = (int)align_up(g.Kd, BK);
     take((long long)d.groups * L->Mpad * L->Kpad * es, &L->pack_off, &L->pack_bytes);
-    take(dt_rows * L->ld * es, &L->dt_off, &L->dt_bytes);
-    if (type != CCT_LOWER_TYPE1) take(rt_rows * L->ld * 4, &L->rt_off, &L->rt_bytes);
+    if (type != CCT_LOWER_FUSED) {  // the fused layout has no D^T
+      take(dt_rows * L->ld * es, &L->dt_off, &L->dt_bytes);
+      if (type != CCT_LOWER_TYPE1) take(rt_rows * L->ld * 4, &L->rt_off, &L->rt_bytes);
+    }
   } else if (pass == CCT_PASS_BACKWARD_DATA) {
     int BM, BN, BK;
     gemm_tn_tile(g.Kd, (int)ncols, &BM, &BN, &BK);
@@ -147,7 +149,11 @@ bool make_layout(const cct_conv_desc_t& d, int pass, int type, const Geom& g, lo
 }
 
 bool type_supported(const cct_conv_desc_t& d, int pass, int type) {
-  if (type < CCT_LOWER_TYPE1 || type > CCT_LOWER_TYPE3) return false;
+  if (type < CCT_LOWER_TYPE1 || type > CCT_LOWER_FUSED) return false;
+  if (type == CCT_LOWER_FUSED) {
+    if (pass != CCT_PASS_FORWARD || d.precision != CCT_PREC_F32) return false;
+    if ((long long)d.C * d.H * d.W >= kIntMax) return false;  // 32-bit offsets inside one image
+  }
   const Geom g = make_geom(d, type);
   Layout L;
   if (!make_layout(d, pass, type, g, 1, &L)) return false;
@@ -165,6 +171,7 @@ bool type_supported(const cct_conv_desc_t& d, int pass, int type) {
 constexpr double kStreamBytesPerSec = 4.0e12;
 constexpr double kGemmFlopsPerSec = 110.0e12;
 constexpr double kLaunchSec = 4.0e-6;
+constexpr double kFusedGemmFactor = 0.85;  // gather-fed GEMM vs GEMM on a materialised matrix
 
 double model_cost(const cct_conv_desc_t& d, int pass, int type) {
   const Geom g = make_geom(d, type);
@@ -178,8 +185,18 @@ double model_cost(const cct_conv_desc_t& d, int pass, int type) {
   const double gemm_flops = 2.0 * cols * (double)g.Mr * (double)g.Kd * d.groups;
   // small M or K dimensions run the matrix cores below their sustained rate
   auto eff = [](double dim) { return std::min(1.0, dim / 128.0); };
+  // a GEMM with fewer than ~2 workgroups (128 x 128 tiles) per CU cannot fill the chip
+  auto fill = [&](double rows) {
+    const double tiles = std::ceil(rows / 128.0) * std::ceil(cols / 128.0) * d.groups;
+    return std::min(1.0, tiles / 512.0);
+  };
   double bytes = 0.0, launches = 2.0, rate = kGemmFlopsPerSec;
-  if (pass == CCT_PASS_FORWARD) {
+  if (pass == CCT_PASS_FORWARD && type == CCT_LOWER_FUSED) {
+    // no lowered matrix at all; the gathered 4-byte operand loads cost the GEMM some of its rate
+    bytes += x_bytes + y_bytes;
+    launches = 2.0;
+    rate *= kFusedGemmFactor * eff(g.Mr) * fill(g.Mr) * std::min(1.0, std::max(0.25, g.Kd / 64.0));
+  } else if (pass == CCT_PASS_FORWARD) {
     bytes += x_bytes + dt_elems * es;            // lowering: read x, write D^T
     bytes += dt_elems * es;                      // GEMM reads D^T
     if (type == CCT_LOWER_TYPE1) {
@@ -188,7 +205,7 @@ double model_cost(const cct_conv_desc_t& d, int pass, int type) {
       bytes += 2.0 * rt_elems * 4.0 + y_bytes;   // GEMM writes R^T, lift reads it, writes y
       launches += 1.0;
     }
-    rate *= eff(g.Mr) * std::min(1.0, std::max(0.25, g.Kd / 64.0));
+    rate *= eff(g.Mr) * fill(g.Mr) * std::min(1.0, std::max(0.25, g.Kd / 64.0));
   } else if (pass == CCT_PASS_BACKWARD_DATA) {
     if (type == CCT_LOWER_TYPE1) {
       bytes += y_bytes;                          // GEMM reads dy in place
@@ -202,7 +219,7 @@ double model_cost(const cct_conv_desc_t& d, int pass, int type) {
       bytes += 2.0 * dt_elems * 4.0 + x_bytes;   // GEMM writes dD^T, inverse lowering reads it
       launches += 1.0;
     }
-    rate *= eff(g.Kd) * std::min(1.0, std::max(0.25, g.Mr / 64.0));
+    rate *= eff(g.Kd) * fill(g.Kd) * std::min(1.0, std::max(0.25, g.Mr / 64.0));
   } else {
     bytes += x_bytes + 2.0 * dt_elems * es;      // lowering + GEMM read
     if (type == CCT_LOWER_TYPE1)
@@ -219,7 +236,7 @@ int pick(const cct_conv_desc_t& d, int pass) {
   if (d.K == 1 && d.stride == 1 && d.pad == 0) return CCT_LOWER_TYPE1;
   int best = 0;
   double best_cost = 0.0;
-  for (int t = CCT_LOWER_TYPE1; t <= CCT_LOWER_TYPE3; ++t) {
+  for (int t = CCT_LOWER_TYPE1; t <= CCT_LOWER_FUSED; ++t) {
     if (!type_supported(d, pass, t)) continue;
     const double c = model_cost(d, pass, t);
     if (!best || c < best_cost) {
@@ -351,7 +368,7 @@ int cct_lowering_cost(const cct_conv_desc_t* desc, cct_pass_t pass, cct_lowering
                       double* seconds) {
   if (!desc_ok(desc) || !seconds) return CCT_EINVAL;
   if (pass < CCT_PASS_FORWARD || pass > CCT_PASS_BACKWARD_WEIGHTS) return CCT_EINVAL;
-  if (lowering < CCT_LOWER_TYPE1 || lowering > CCT_LOWER_TYPE3) return CCT_EINVAL;
+  if (lowering < CCT_LOWER_TYPE1 || lowering > CCT_LOWER_FUSED) return CCT_EINVAL;
   if (!type_supported(*desc, pass, lowering)) return CCT_EUNSUPPORTED;
   *seconds = model_cost(*desc, pass, lowering);
   return CCT_OK;
@@ -420,6 +437,29 @@ int cct_conv_forward(const cct_conv_desc_t* desc, const float* x, const float* w
     const long long ncols = (long long)ni * g.Pc;
     const float* xc = x + n0 * d.C * d.H * d.W;
     float* yc = y + n0 * d.O * P;
+    if (type == CCT_LOWER_FUSED) {
+      // lowering, multiply and lifting in one kernel: the GEMM gathers its B tiles from x
+      GemmTN p;
+      std::memset(&p, 0, sizeof(p));
+      p.A = ws + L.pack_off;
+      p.a_gs = (long long)L.Mpad * L.Kpad;
+      p.Mpad = L.Mpad; p.Kpad = L.Kpad;
+      p.B = xc;
+      p.bmap = ColMap{1, 0};  // not a plain matrix
+      p.gather = 1;
+      p.gC = d.C; p.gH = d.H; p.gW = d.W; p.gHout = g.Hout; p.gWout = g.Wout;
+      p.gs = d.stride; p.gp = d.pad; p.gCg = g.Cg; p.gK = d.K; p.gKK = d.K * d.K;
+      make_fastdiv_parts(p.gKK, &p.g_divKK_M, &p.g_divKK_sh);
+      make_fastdiv_parts(p.gK, &p.g_divK_M, &p.g_divK_sh);
+      p.M = g.Mr; p.Ncols = (int)ncols; p.Kdim = g.Kd; p.G = d.groups;
+      p.C = yc;
+      p.c_ms = P; p.c_gs = (long long)g.Og * P;
+      p.cmap = ColMap{(int)P, (long long)d.O * P};
+      p.bias = bias; p.bias_gs = g.Og;
+      rc = launch_gemm_tn(p, st);
+      if (rc) return rc;
+      continue;
+    }
     rc = launch_lower(xc, ws + L.dt_off, L.ld, ni, d.C, g.lower, bf16, st);
     if (rc) return rc;
     GemmTN p;

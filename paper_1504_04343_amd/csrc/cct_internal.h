@@ -54,7 +54,21 @@ struct GemmTN {
   int M, Ncols, Kdim;  // true sizes per group
   int G;
   int bf16;            // operands are bf16 (A packed bf16, B bf16 plain rows)
+  // Fused lowering (gather != 0): B is the NCHW tensor x itself and the kernel builds the Type-1
+  // lowered tile on the fly: B(k, col) = x[n, q*Cg + ci, r*s + i - p, c*s + j - p] or 0, with
+  // (ci, i, j) decoded from k = (ci*K + i)*K + j and (n, r, c) from col.
+  int gather;
+  int gC, gH, gW, gHout, gWout, gs, gp, gCg, gK, gKK;
+  unsigned g_divKK_M, g_divK_M;  // fast division by K*K and by K
+  int g_divKK_sh, g_divK_sh;
 };
+// n / d == (n * M) >> sh for 0 <= n < 2^31
+inline void make_fastdiv_parts(int d, unsigned* M, int* sh) {
+  int s = 0;
+  while ((1LL << s) < d) ++s;
+  *sh = 31 + s;
+  *M = (unsigned)(((1ULL << *sh) + (unsigned long long)d - 1) / (unsigned long long)d);
+}
 
 // Cpart[s][g][m][n] = sum_{col in split s} A(m, col) * B(n, col); both operands col-contiguous.
 struct GemmNT {

@@ -13,6 +13,11 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef const float __attribute__((address_space(1)))* gptr_f32;
 typedef const f32x4 __attribute__((address_space(1)))* gptr_f32x4;
 
+// n / d for n < 2^31 with M = ceil(2^sh / d), sh = 31 + ceil(log2 d) (see make_fastdiv_parts)
+__device__ __forceinline__ int fdiv_u(int n, unsigned M, int sh) {
+  return (int)(((unsigned long long)(unsigned)n * M) >> sh);
+}
+
 __device__ __forceinline__ long long col_offset(const ColMap& cm, int col) {
   const int n = col / cm.P;
   return (long long)n * cm.img_stride + (col - n * cm.P);

@@ -23,9 +23,17 @@ namespace {
 
 constexpr int NT = 256;
 
-// fp32 kernel.  BVEC: B rows are plain, 16-byte aligned rows -> 16-byte loads.
-template <int BM, int BN, int BK, int WM, int WN, bool BVEC>
+// fp32 kernel.  BMODE 0: B rows are plain, 16-byte aligned rows -> 16-byte loads.
+// BMODE 1: B columns go through a column map (an NCHW tensor read in place), 4-byte loads.
+// BMODE 2: fused lowering, B tiles are gathered from x (see GemmTN::gather), 4-byte loads; the
+//          (ci, i, j) -> offset table of all K rows is built once per workgroup in LDS.
+// BMODE 3: same, but the taps are decoded arithmetically (for K too long for the LDS table).
+template <int BM, int BN, int BK, int WM, int WN, int BMODE>
 __global__ __launch_bounds__(NT) void gemm_tn_f32(GemmTN p, int tiles_m, int tiles_n) {
+  constexpr bool BVEC = BMODE == 0;
+  constexpr bool GATHER = BMODE >= 2;
+  constexpr bool TAPS_LDS = BMODE == 2;
+  extern __shared__ int2 tap_tab[];  // BMODE 2: {(ci*H + i)*W + j, (i << 16) | j} per row k
   constexpr int WAVES_N = BN / (32 * WN);
   constexpr int WAVES_M = BM / (32 * WM);
   static_assert(WAVES_M * WAVES_N == 4, "4 waves per workgroup");
@@ -95,12 +103,34 @@ __global__ __launch_bounds__(NT) void gemm_tn_f32(GemmTN p, int tiles_m, int til
   gptr_f32 bs_src = nullptr;  // scalar path
   bool bs_ok = false;
   int bs_k0 = 0, bs_n = 0;
+  int g_hh = 0, g_ww = 0;  // gather: top-left tensor pixel of this thread's column
   if (!BVEC) {
     bs_n = tid % BN;
     bs_k0 = tid / BN;
     const int col = n0 + bs_n;
     bs_ok = col < p.Ncols;
-    bs_src = Bg + (bs_ok ? col_offset(p.bmap, col) : 0) + (long long)bs_k0 * p.b_ks;
+    if (GATHER) {
+      const int P = p.gHout * p.gWout;
+      const int cc = bs_ok ? col : 0;
+      const int n = cc / P, pix = cc - n * P;
+      const int r = pix / p.gWout, c = pix - r * p.gWout;
+      g_hh = r * p.gs - p.gp;
+      g_ww = c * p.gs - p.gp;
+      bs_src = (gptr_f32)(p.B) + (((long long)n * p.gC + (long long)g * p.gCg) * p.gH + g_hh) * p.gW + g_ww;
+    } else {
+      bs_src = Bg + (bs_ok ? col_offset(p.bmap, col) : 0) + (long long)bs_k0 * p.b_ks;
+    }
+  }
+
+  if (TAPS_LDS) {
+    for (int k = tid; k < p.Kpad; k += NT) {
+      const int ci = k / p.gKK, rem = k - ci * p.gKK;
+      const int ti = rem / p.gK, tj = rem - ti * p.gK;
+      // rows >= Kdim get a row offset that fails every bounds check
+      tap_tab[k] = k < p.Kdim ? make_int2((ci * p.gH + ti) * p.gW + tj, (ti << 16) | tj)
+                              : make_int2(0, 0x7fff << 16);
+    }
+    __syncthreads();
   }
 
   f32x4 ra[A_IT];
@@ -120,6 +150,29 @@ __global__ __launch_bounds__(NT) void gemm_tn_f32(GemmTN p, int tiles_m, int til
         if ((K0) + b_k[it] < p.Kdim) val = *(gptr_f32x4)(b_src[it]);                        \
         rbv[it] = val;                                                                      \
         b_src[it] += b_step;                                                                \
+      }                                                                                     \
+    } else if (TAPS_LDS) {                                                                  \
+      _Pragma("unroll") for (int it = 0; it < B_SC_IT; ++it) {                              \
+        const int2 tp = tap_tab[(K0) + bs_k0 + it * B_KSTEP];                               \
+        float val = 0.f;                                                                    \
+        if (bs_ok && (unsigned)(g_hh + (tp.y >> 16)) < (unsigned)p.gH &&                    \
+            (unsigned)(g_ww + (tp.y & 0xffff)) < (unsigned)p.gW)                            \
+          val = bs_src[tp.x];                                                               \
+        rbs[it] = val;                                                                      \
+      }                                                                                     \
+    } else if (GATHER) {                                                                    \
+      _Pragma("unroll") for (int it = 0; it < B_SC_IT; ++it) {                              \
+        /* row k of the Type-1 lowered matrix = tap (ci, i, j); decoded arithmetically */   \
+        const int k = (K0) + bs_k0 + it * B_KSTEP;                                          \
+        const int ci = fdiv_u(k, p.g_divKK_M, p.g_divKK_sh);                                \
+        const int rem = k - ci * p.gKK;                                                     \
+        const int ti = fdiv_u(rem, p.g_divK_M, p.g_divK_sh);                                \
+        const int tj = rem - ti * p.gK;                                                     \
+        float val = 0.f;                                                                    \
+        if (bs_ok && k < p.Kdim && (unsigned)(g_hh + ti) < (unsigned)p.gH &&                \
+            (unsigned)(g_ww + tj) < (unsigned)p.gW)                                         \
+          val = bs_src[(ci * p.gH + ti) * p.gW + tj];                                       \
+        rbs[it] = val;                                                                      \
       }                                                                                     \
     } else {                                                                                \
       _Pragma("unroll") for (int it = 0; it < B_SC_IT; ++it) {                              \
@@ -392,16 +445,27 @@ int launch_f32(const GemmTN& p, hipStream_t st) {
                    p.b_ld_guard >= p.Ncols && p.b_ks >= p.b_ld_guard;
   dim3 grid((unsigned)blocks, (unsigned)p.G);
   char name[96];
-  snprintf(name, sizeof(name), "gemm_tn_f32<%d, %d, %d, %d, %d, %s>", BM, BN, BK, WM, WN,
-           vec ? "true" : "false");
+  // fused lowering: tap table in LDS when it fits 24 KiB (and the kernel size fits 15 bits)
+  const size_t tab_bytes = (size_t)p.Kpad * sizeof(int2);
+  const bool tab_ok = tab_bytes <= 24576 && p.gK < 32768;
+  const int bmode = p.gather ? (tab_ok ? 2 : 3) : (vec ? 0 : 1);
+  snprintf(name, sizeof(name), "gemm_tn_f32<%d, %d, %d, %d, %d, %d>", BM, BN, BK, WM, WN, bmode);
+  // algorithmic bytes: operands once + result once (fused lowering: the tensor x, not D^)
+  const double b_bytes = p.gather ? 4.0 * ((double)p.Ncols / (p.gHout * p.gWout)) * p.gC * p.gH * p.gW
+                                  : 4.0 * (double)p.Kdim * p.Ncols * p.G;
   ProfScope ps(name, 2.0 * p.M * p.Ncols * p.Kdim * p.G,
-               4.0 * ((double)p.Kdim * p.Ncols + (double)p.M * p.Ncols + (double)p.M * p.Kdim) * p.G,
-               st);
-  if (vec)
-    hipLaunchKernelGGL((gemm_tn_f32<BM, BN, BK, WM, WN, true>), grid, dim3(NT), 0, st, p, tiles_m,
+               b_bytes + 4.0 * ((double)p.M * p.Ncols + (double)p.M * p.Kdim) * p.G, st);
+  if (bmode == 2)
+    hipLaunchKernelGGL((gemm_tn_f32<BM, BN, BK, WM, WN, 2>), grid, dim3(NT), tab_bytes, st, p,
+                       tiles_m, tiles_n);
+  else if (bmode == 3)
+    hipLaunchKernelGGL((gemm_tn_f32<BM, BN, BK, WM, WN, 3>), grid, dim3(NT), 0, st, p, tiles_m,
+                       tiles_n);
+  else if (bmode == 0)
+    hipLaunchKernelGGL((gemm_tn_f32<BM, BN, BK, WM, WN, 0>), grid, dim3(NT), 0, st, p, tiles_m,
                        tiles_n);
   else
-    hipLaunchKernelGGL((gemm_tn_f32<BM, BN, BK, WM, WN, false>), grid, dim3(NT), 0, st, p, tiles_m,
+    hipLaunchKernelGGL((gemm_tn_f32<BM, BN, BK, WM, WN, 1>), grid, dim3(NT), 0, st, p, tiles_m,
                        tiles_n);
   CCT_CHECK_LAUNCH();
   return CCT_OK;

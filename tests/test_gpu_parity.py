@@ -36,6 +36,9 @@ SMALL = [
     layer("pad_gt_k", 1, 2, 6, 6, 3, 2, 1, 3, 1),                # windows entirely in the padding
     layer("stride3_g3", 2, 6, 14, 11, 9, 4, 3, 1, 3),
     layer("single_pixel_out", 2, 3, 5, 5, 4, 5, 1, 0, 1),        # Hout = Wout = 1
+    layer("long_k", 1, 352, 6, 6, 8, 3, 1, 1, 1),                # 3168 patch rows: beyond the fused kernel's LDS tap table
+    layer("depthwise", 2, 8, 9, 9, 8, 3, 1, 1, 8),               # groups = C = O: one channel per group
+    layer("tiny", 1, 1, 1, 1, 1, 1, 1, 0, 1),                    # everything is 1
 ]
 IDS = [L.name for L in SMALL]
 
@@ -81,7 +84,7 @@ def test_lowering_map_names_its_source(B):
 
 # ------------------------------------------------------------------ forward
 @pytest.mark.parametrize("L", SMALL, ids=IDS)
-@pytest.mark.parametrize("lowering", [1, 2, 3])
+@pytest.mark.parametrize("lowering", [1, 2, 3, 4])
 def test_forward_matches_oracle(B, L, lowering):
     x, w, b, _ = inputs(L)
     want = oracle.conv_forward(odims(oracle, L), x, w, b)
@@ -98,7 +101,7 @@ def test_forward_auto_and_no_bias(B, L):
     assert rel_err(got, want) <= TOL_F32
 
 
-@pytest.mark.parametrize("lowering", [1, 2, 3])
+@pytest.mark.parametrize("lowering", [1, 2, 3, 4])
 @pytest.mark.parametrize("chunk", [1, 3])
 def test_forward_chunked_batch(B, lowering, chunk):
     """A small workspace makes the library lower and multiply the batch in several chunks
@@ -188,7 +191,7 @@ def test_tradeoff_sweep_shapes_all_layouts(B, L):
     idx = synth.sample_indices(L.N * L.O * L.Hout * L.Wout, 3000, 4)
     want = oracle.conv_forward_at(odims(oracle, L), x, w, b, idx)
     scale = np.abs(want).max()
-    for lowering in (1, 2, 3, B.LOWER_AUTO):
+    for lowering in (1, 2, 3, B.LOWER_FUSED, B.LOWER_AUTO):
         got = gpu_forward(B, L, x, w, b, lowering).ravel()[idx]
         assert np.abs(got - want).max() / scale <= TOL_F32, lowering
 
@@ -205,3 +208,12 @@ def test_unsupported_and_workspace_errors(B):
     assert e.value.code == B.EWORKSPACE
     with pytest.raises(ValueError):
         B.cct_conv_forward(d, dev(x)[:2], dev(w), dev(b), y, B.alloc_workspace(d, 0))
+    # the fused layout exists for the forward pass only
+    df = desc_of(B, L, B.LOWER_FUSED)
+    for p in (B.PASS_BACKWARD_DATA, B.PASS_BACKWARD_WEIGHTS):
+        with pytest.raises(B.CctError) as e:
+            B.cct_conv_workspace_bytes(df, p)
+        assert e.value.code == B.EUNSUPPORTED
+    with pytest.raises(B.CctError) as e:
+        B.cct_lowered_shape(df, B.LOWER_FUSED)
+    assert e.value.code == B.EINVAL

@@ -41,7 +41,7 @@ def time_forward(B, L, lowering, reps=5):
 def measured(B, L):
     d = desc_of(B, L)
     costs = {}
-    for t in (1, 2, 3):
+    for t in (1, 2, 3, 4):
         try:
             costs[t] = B.cct_lowering_cost(d, B.PASS_FORWARD, t)
         except B.CctError:
@@ -67,6 +67,6 @@ def test_measured_winner_follows_channel_ratio(B):
         winners[(L.C, L.O)] = min(times, key=times.get)
         pick = B.cct_pick_lowering(desc_of(B, L), B.PASS_FORWARD)
         assert times[pick] <= (1 + REGRET) * min(times.values()), (L.name, pick, times)
-    assert winners[(16, 512)] == 1                  # few input, many output channels: Type 1
+    assert winners[(16, 512)] in (1, 4)             # few input, many output channels: Type 1 (or its fusion)
     assert winners[(1024, 32)] in (2, 3)            # many input, few output channels: not Type 1
     assert winners[(512, 16)] in (2, 3)
