@@ -171,7 +171,7 @@ bool type_supported(const cct_conv_desc_t& d, int pass, int type) {
 constexpr double kStreamBytesPerSec = 4.0e12;
 constexpr double kGemmFlopsPerSec = 110.0e12;
 constexpr double kLaunchSec = 4.0e-6;
-constexpr double kFusedGemmFactor = 0.85;  // gather-fed GEMM vs GEMM on a materialised matrix
+constexpr double kFusedGemmFactor = 0.9;  // fused kernels vs the GEMM on a materialised matrix
 
 double model_cost(const cct_conv_desc_t& d, int pass, int type) {
   const Geom g = make_geom(d, type);
@@ -456,7 +456,8 @@ int cct_conv_forward(const cct_conv_desc_t* desc, const float* x, const float* w
       p.c_ms = P; p.c_gs = (long long)g.Og * P;
       p.cmap = ColMap{(int)P, (long long)d.O * P};
       p.bias = bias; p.bias_gs = g.Og;
-      rc = launch_gemm_tn(p, st);
+      rc = launch_conv_fused(p, st);                            // LDS-staged lowering
+      if (rc == CCT_EUNSUPPORTED) rc = launch_gemm_tn(p, st);  // else gather-fed GEMM
       if (rc) return rc;
       continue;
     }

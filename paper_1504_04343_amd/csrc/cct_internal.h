@@ -85,6 +85,9 @@ struct GemmNT {
 
 int launch_gemm_tn(const GemmTN& p, hipStream_t st);
 int launch_gemm_nt(const GemmNT& p, hipStream_t st);
+// Fused forward with LDS-staged lowering (p.gather must be set).  CCT_EUNSUPPORTED = the shape
+// does not fit its staging area and nothing was launched: use launch_gemm_tn instead.
+int launch_conv_fused(const GemmTN& p, hipStream_t st);
 // Tile sizes the launchers will use for a problem (so that the planner can pad the packs).
 void gemm_tn_tile(int M, int Ncols, int* BM, int* BN, int* BK);
 void gemm_nt_tile(int M, int N, int* BM, int* BN, int* BK);
