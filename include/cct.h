@@ -54,8 +54,10 @@ typedef enum {
   CCT_LOWER_TYPE3 = 3, /* D^ rows = input positions, cols = ci; lift sums K*K entries        */
   CCT_LOWER_FUSED = 4  /* the fusion of Sec. 2.1 ("Fusion"): lowering, multiply and lifting in
                           one kernel, D^ (Type-1 layout) is never materialised: the GEMM gathers
-                          its operand tiles from x.  Forward pass, fp32 only; other passes /
-                          precisions return CCT_EUNSUPPORTED when it is requested explicitly.   */
+                          its operand tiles from x (through LDS when they fit).  fp32 only;
+                          forward pass, and backward-data pass of stride-1 layers (computed as
+                          the convolution of dy with the flipped kernels); other passes, strides
+                          and precisions return CCT_EUNSUPPORTED when it is requested explicitly. */
 } cct_lowering_t;
 
 typedef enum {

@@ -117,6 +117,14 @@ bool make_layout(const cct_conv_desc_t& d, int pass, int type, const Geom& g, lo
       take(dt_rows * L->ld * es, &L->dt_off, &L->dt_bytes);
       if (type != CCT_LOWER_TYPE1) take(rt_rows * L->ld * 4, &L->rt_off, &L->rt_bytes);
     }
+  } else if (pass == CCT_PASS_BACKWARD_DATA && type == CCT_LOWER_FUSED) {
+    // a stride-1 convolution of dy with the flipped kernels: M = Cg, K dim = Og*K*K
+    if (nc * d.H * d.W >= kIntMax - 256) return false;
+    int BM, BN, BK;
+    gemm_tn_tile(g.Cg, (int)(nc * d.H * d.W), &BM, &BN, &BK);
+    L->Mpad = (int)align_up(g.Cg, BM);
+    L->Kpad = (int)align_up((long long)g.Og * d.K * d.K, BK);
+    take((long long)d.groups * L->Mpad * L->Kpad * 4, &L->pack_off, &L->pack_bytes);
   } else if (pass == CCT_PASS_BACKWARD_DATA) {
     int BM, BN, BK;
     gemm_tn_tile(g.Kd, (int)ncols, &BM, &BN, &BK);
@@ -151,7 +159,10 @@ bool make_layout(const cct_conv_desc_t& d, int pass, int type, const Geom& g, lo
 bool type_supported(const cct_conv_desc_t& d, int pass, int type) {
   if (type < CCT_LOWER_TYPE1 || type > CCT_LOWER_FUSED) return false;
   if (type == CCT_LOWER_FUSED) {
-    if (pass != CCT_PASS_FORWARD || d.precision != CCT_PREC_F32) return false;
+    if (d.precision != CCT_PREC_F32) return false;
+    if (pass == CCT_PASS_BACKWARD_WEIGHTS) return false;
+    // backward-data is fused as a convolution of dy with the flipped kernels: stride 1 only
+    if (pass == CCT_PASS_BACKWARD_DATA && (d.stride != 1 || d.pad > d.K - 1)) return false;
     if ((long long)d.C * d.H * d.W >= kIntMax) return false;  // 32-bit offsets inside one image
   }
   const Geom g = make_geom(d, type);
@@ -168,11 +179,15 @@ bool type_supported(const cct_conv_desc_t& d, int pass, int type) {
 // this library's own kernels (sustained streaming rate of the index-map kernels, sustained
 // fp32 MFMA rate of the GEMM at large tiles).
 // ---------------------------------------------------------------------------------------
-constexpr double kStreamBytesPerSec = 4.0e12;
+constexpr double kStreamBytesPerSec = 4.0e12;   // index-map kernels (lower, lift and adjoints)
+constexpr double kGemmBytesPerSec = 5.0e12;     // operand / result streaming inside a GEMM
 constexpr double kGemmFlopsPerSec = 110.0e12;
 constexpr double kLaunchSec = 4.0e-6;
 constexpr double kFusedGemmFactor = 0.9;  // fused kernels vs the GEMM on a materialised matrix
 
+// time = sum over index-map kernels of bytes / stream rate
+//      + max(GEMM flops / MFMA rate, GEMM bytes / GEMM stream rate)     (loads overlap the MFMAs)
+//      + launches * launch latency
 double model_cost(const cct_conv_desc_t& d, int pass, int type) {
   const Geom g = make_geom(d, type);
   const double es = esize(d);
@@ -182,54 +197,69 @@ double model_cost(const cct_conv_desc_t& d, int pass, int type) {
   const double y_bytes = 4.0 * N * d.O * g.Hout * g.Wout;
   const double dt_elems = (double)d.C * g.DKi * g.DKj * cols;
   const double rt_elems = (double)d.O * g.RKi * g.RKj * cols;
-  const double gemm_flops = 2.0 * cols * (double)g.Mr * (double)g.Kd * d.groups;
+  double gemm_flops = 2.0 * cols * (double)g.Mr * (double)g.Kd * d.groups;
   // small M or K dimensions run the matrix cores below their sustained rate
   auto eff = [](double dim) { return std::min(1.0, dim / 128.0); };
+  auto short_k = [](double k) { return std::min(1.0, std::max(0.25, k / 64.0)); };
   // a GEMM with fewer than ~2 workgroups (128 x 128 tiles) per CU cannot fill the chip
-  auto fill = [&](double rows) {
-    const double tiles = std::ceil(rows / 128.0) * std::ceil(cols / 128.0) * d.groups;
+  auto fill = [&](double rows, double ncols) {
+    const double tiles = std::ceil(rows / 128.0) * std::ceil(ncols / 128.0) * d.groups;
     return std::min(1.0, tiles / 512.0);
   };
-  double bytes = 0.0, launches = 2.0, rate = kGemmFlopsPerSec;
+  double index_bytes = 0.0, gemm_bytes = 0.0, launches = 2.0, rate = kGemmFlopsPerSec;
   if (pass == CCT_PASS_FORWARD && type == CCT_LOWER_FUSED) {
-    // no lowered matrix at all; the gathered 4-byte operand loads cost the GEMM some of its rate
-    bytes += x_bytes + y_bytes;
-    launches = 2.0;
-    rate *= kFusedGemmFactor * eff(g.Mr) * fill(g.Mr) * std::min(1.0, std::max(0.25, g.Kd / 64.0));
+    // no lowered matrix at all; building the operand in the kernel costs the GEMM some of its rate
+    gemm_bytes = x_bytes + y_bytes;
+    rate *= kFusedGemmFactor * eff(g.Mr) * fill(g.Mr, cols) * short_k(g.Kd);
   } else if (pass == CCT_PASS_FORWARD) {
-    bytes += x_bytes + dt_elems * es;            // lowering: read x, write D^T
-    bytes += dt_elems * es;                      // GEMM reads D^T
+    index_bytes += x_bytes + dt_elems * es;      // lowering: read x, write D^T
+    gemm_bytes += dt_elems * es;                 // GEMM reads D^T
     if (type == CCT_LOWER_TYPE1) {
-      bytes += y_bytes;                          // epilogue writes y
+      gemm_bytes += y_bytes;                     // epilogue writes y
     } else {
-      bytes += 2.0 * rt_elems * 4.0 + y_bytes;   // GEMM writes R^T, lift reads it, writes y
+      gemm_bytes += rt_elems * 4.0;              // GEMM writes R^T
+      index_bytes += rt_elems * 4.0 + y_bytes;   // lifting reads it, writes y
       launches += 1.0;
     }
-    rate *= eff(g.Mr) * fill(g.Mr) * std::min(1.0, std::max(0.25, g.Kd / 64.0));
+    rate *= eff(g.Mr) * fill(g.Mr, cols) * short_k(g.Kd);
+  } else if (pass == CCT_PASS_BACKWARD_DATA && type == CCT_LOWER_FUSED) {
+    // a convolution of dy with the flipped kernels: Cg output rows per group, one column per pixel
+    const double pos = N * d.H * d.W;
+    gemm_bytes = x_bytes + y_bytes;
+    gemm_flops = 2.0 * pos * (double)g.Cg * (double)g.Og * d.K * d.K * d.groups;
+    const double mt = g.Cg <= 64 ? 64.0 : ((g.Cg % 128 != 0 && g.Cg % 96 == 0) ? 96.0 : 128.0);
+    const double util = g.Cg / (std::ceil(g.Cg / mt) * mt);  // tiles of 64 / 96 / 128 rows
+    rate *= kFusedGemmFactor * util * fill(g.Cg, pos);
   } else if (pass == CCT_PASS_BACKWARD_DATA) {
     if (type == CCT_LOWER_TYPE1) {
-      bytes += y_bytes;                          // GEMM reads dy in place
+      gemm_bytes += y_bytes;                     // GEMM reads dy in place
     } else {
-      bytes += y_bytes + 2.0 * rt_elems * es;    // inverse lifting writes dR^T, GEMM reads it
+      index_bytes += y_bytes + rt_elems * es;    // inverse lifting writes dR^T
+      gemm_bytes += rt_elems * es;               // GEMM reads it
       launches += 1.0;
     }
     if (type == CCT_LOWER_TYPE3) {
-      bytes += x_bytes;                          // epilogue writes dx
+      gemm_bytes += x_bytes;                     // epilogue writes dx
     } else {
-      bytes += 2.0 * dt_elems * 4.0 + x_bytes;   // GEMM writes dD^T, inverse lowering reads it
+      gemm_bytes += dt_elems * 4.0;              // GEMM writes dD^T
+      index_bytes += dt_elems * 4.0 + x_bytes;   // inverse lowering reads it, writes dx
       launches += 1.0;
     }
-    rate *= eff(g.Kd) * fill(g.Kd) * std::min(1.0, std::max(0.25, g.Mr / 64.0));
+    rate *= eff(g.Kd) * fill(g.Kd, cols) * short_k(g.Mr);
   } else {
-    bytes += x_bytes + 2.0 * dt_elems * es;      // lowering + GEMM read
-    if (type == CCT_LOWER_TYPE1)
-      bytes += y_bytes;
-    else
-      bytes += y_bytes + 2.0 * rt_elems * es;
+    index_bytes += x_bytes + dt_elems * es;      // lowering
+    gemm_bytes += dt_elems * es;
+    if (type == CCT_LOWER_TYPE1) {
+      gemm_bytes += y_bytes;
+    } else {
+      index_bytes += y_bytes + rt_elems * es;    // inverse lifting
+      gemm_bytes += rt_elems * es;
+    }
     launches += 2.0;
     rate *= eff(g.Mr) * eff(g.Kd);
   }
-  return bytes / kStreamBytesPerSec + gemm_flops / rate + launches * kLaunchSec;
+  return index_bytes / kStreamBytesPerSec +
+         std::max(gemm_flops / rate, gemm_bytes / kGemmBytesPerSec) + launches * kLaunchSec;
 }
 
 int pick(const cct_conv_desc_t& d, int pass) {
@@ -515,6 +545,32 @@ int cct_conv_backward_data(const cct_conv_desc_t* desc, const float* w, const fl
   const long long P = (long long)g.Hout * g.Wout;
   const long long HW = (long long)d.H * d.W;
 
+  if (type == CCT_LOWER_FUSED) {
+    // one kernel: dx = convolution of dy (O channels, Hout x Wout) with the flipped kernels,
+    // stride 1, pad K-1-p; lowering of dy happens in LDS (or as a gather), never in HBM
+    rc = launch_pack_flipped(w, reinterpret_cast<float*>(ws + L.pack_off), d.groups, g.Og, g.Cg, d.K,
+                             L.Mpad, L.Kpad, st);
+    if (rc) return rc;
+    GemmTN p;
+    std::memset(&p, 0, sizeof(p));
+    p.A = ws + L.pack_off;
+    p.a_gs = (long long)L.Mpad * L.Kpad;
+    p.Mpad = L.Mpad; p.Kpad = L.Kpad;
+    p.B = dy;
+    p.bmap = ColMap{1, 0};
+    p.gather = 1;
+    p.gC = d.O; p.gH = g.Hout; p.gW = g.Wout; p.gHout = d.H; p.gWout = d.W;
+    p.gs = 1; p.gp = d.K - 1 - d.pad; p.gCg = g.Og; p.gK = d.K; p.gKK = d.K * d.K;
+    make_fastdiv_parts(p.gKK, &p.g_divKK_M, &p.g_divKK_sh);
+    make_fastdiv_parts(p.gK, &p.g_divK_M, &p.g_divK_sh);
+    p.M = g.Cg; p.Ncols = (int)((long long)d.N * HW); p.Kdim = g.Og * d.K * d.K; p.G = d.groups;
+    p.C = dx;
+    p.c_ms = HW; p.c_gs = (long long)g.Cg * HW;
+    p.cmap = ColMap{(int)HW, (long long)d.C * HW};
+    rc = launch_conv_fused(p, st);
+    if (rc == CCT_EUNSUPPORTED) rc = launch_gemm_tn(p, st);
+    return rc;
+  }
   rc = launch_pack_kernel_matrix(w, ws + L.pack_off, make_pack(d, g, L, 1), st);
   if (rc) return rc;
   for (long long n0 = 0; n0 < d.N; n0 += nc) {

@@ -120,6 +120,9 @@ struct PackDesc {
   int bf16;
 };
 int launch_pack_kernel_matrix(const float* w, void* pack, const PackDesc& d, hipStream_t st);
+// pack[q][(oo,i',j')][ci] = w[q*Og+oo, ci, K-1-i', K-1-j'] (fp32), zero padded to Kpad x Mpad.
+int launch_pack_flipped(const float* w, float* pack, int G, int Og, int Cg, int K, int Mpad,
+                        int Kpad, hipStream_t st);
 // dw[o,ci,i,j] = (accumulate ? dw : 0) + sum_s part[s][q][rho][delta]
 int launch_reduce_dw(const float* part, float* dw, int S, const PackDesc& d, int accumulate,
                      hipStream_t st);

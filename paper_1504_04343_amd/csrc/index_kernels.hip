@@ -43,6 +43,26 @@ __global__ __launch_bounds__(TPB) void pack_kernel(const float* __restrict__ w, 
   store_elem<BF16>(pack, t, v);
 }
 
+// Kernel matrix of the fused backward-data pass: the backward-data map of a stride-1 convolution
+// is itself a convolution of dy with the kernels flipped in both axes and the channel roles
+// swapped: pack[q][k = (oo, i', j')][m = ci] = w[q*Og + oo, ci, K-1-i', K-1-j'], zero padded.
+__global__ __launch_bounds__(TPB) void pack_flipped_kernel(const float* __restrict__ w,
+                                                           float* __restrict__ pack, int G, int Og,
+                                                           int Cg, int K, int Mpad, int Kpad) {
+  const long long per_group = (long long)Mpad * Kpad;
+  const long long t = (long long)blockIdx.x * TPB + threadIdx.x;
+  if (t >= per_group * G) return;
+  const int q = (int)(t / per_group);
+  const long long e = t - q * per_group;
+  const int k = (int)(e / Mpad), ci = (int)(e % Mpad);
+  float v = 0.0f;
+  if (k < Og * K * K && ci < Cg) {
+    const int j = k % K, i = (k / K) % K, oo = k / (K * K);
+    v = w[((((long long)q * Og + oo) * Cg + ci) * K + (K - 1 - i)) * K + (K - 1 - j)];
+  }
+  pack[t] = v;
+}
+
 // dw = sum over split-K partials, mapped back to O x Cg x K x K.  A workgroup owns 64 outputs;
 // its 4 thread groups each add up a quarter of the splits (in split order), and the four
 // quarter sums are combined in a fixed order: the result is bit-reproducible run to run.
@@ -123,6 +143,18 @@ int launch_pack_kernel_matrix(const float* w, void* pack, const PackDesc& d, hip
     hipLaunchKernelGGL(pack_kernel<true>, dim3((unsigned)blocks), dim3(TPB), 0, st, w, pack, d);
   else
     hipLaunchKernelGGL(pack_kernel<false>, dim3((unsigned)blocks), dim3(TPB), 0, st, w, pack, d);
+  CCT_CHECK_LAUNCH();
+  return CCT_OK;
+}
+
+int launch_pack_flipped(const float* w, float* pack, int G, int Og, int Cg, int K, int Mpad,
+                        int Kpad, hipStream_t st) {
+  const long long total = (long long)Mpad * Kpad * G;
+  const long long blocks = (total + TPB - 1) / TPB;
+  if (!grid_ok(blocks)) return CCT_EUNSUPPORTED;
+  ProfScope ps("pack_flipped_kernel", 0.0, 4.0 * G * Og * Cg * K * K + 4.0 * total, st);
+  hipLaunchKernelGGL(pack_flipped_kernel, dim3((unsigned)blocks), dim3(TPB), 0, st, w, pack, G, Og,
+                     Cg, K, Mpad, Kpad);
   CCT_CHECK_LAUNCH();
   return CCT_OK;
 }

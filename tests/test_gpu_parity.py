@@ -123,9 +123,15 @@ def test_forward_is_deterministic(B):
 
 # ------------------------------------------------------------------ backward
 @pytest.mark.parametrize("L", SMALL, ids=IDS)
-@pytest.mark.parametrize("lowering", [1, 2, 3])
+@pytest.mark.parametrize("lowering", [1, 2, 3, 4])
 def test_backward_data_matches_oracle(B, L, lowering):
     _, w, _, dy = inputs(L)
+    if lowering == 4 and (L.stride != 1 or L.pad > L.K - 1):
+        # the fused backward-data pass is a stride-1 convolution of dy with the flipped kernels
+        with pytest.raises(B.CctError) as e:
+            gpu_backward_data(B, L, w, dy, lowering)
+        assert e.value.code == B.EUNSUPPORTED
+        return
     want = oracle.conv_backward_data(odims(oracle, L), w, dy)
     got = gpu_backward_data(B, L, w, dy, lowering)
     assert np.isfinite(got).all()
@@ -208,12 +214,11 @@ def test_unsupported_and_workspace_errors(B):
     assert e.value.code == B.EWORKSPACE
     with pytest.raises(ValueError):
         B.cct_conv_forward(d, dev(x)[:2], dev(w), dev(b), y, B.alloc_workspace(d, 0))
-    # the fused layout exists for the forward pass only
+    # there is no fused backward-weights pass
     df = desc_of(B, L, B.LOWER_FUSED)
-    for p in (B.PASS_BACKWARD_DATA, B.PASS_BACKWARD_WEIGHTS):
-        with pytest.raises(B.CctError) as e:
-            B.cct_conv_workspace_bytes(df, p)
-        assert e.value.code == B.EUNSUPPORTED
+    with pytest.raises(B.CctError) as e:
+        B.cct_conv_workspace_bytes(df, B.PASS_BACKWARD_WEIGHTS)
+    assert e.value.code == B.EUNSUPPORTED
     with pytest.raises(B.CctError) as e:
         B.cct_lowered_shape(df, B.LOWER_FUSED)
     assert e.value.code == B.EINVAL
