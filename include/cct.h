@@ -55,9 +55,11 @@ typedef enum {
   CCT_LOWER_FUSED = 4  /* the fusion of Sec. 2.1 ("Fusion"): lowering, multiply and lifting in
                           one kernel, D^ (Type-1 layout) is never materialised: the GEMM gathers
                           its operand tiles from x (through LDS when they fit).  fp32 only;
-                          forward pass, and backward-data pass of stride-1 layers (computed as
-                          the convolution of dy with the flipped kernels); other passes, strides
-                          and precisions return CCT_EUNSUPPORTED when it is requested explicitly. */
+                          forward pass; backward-data pass of stride-1 layers with pad <= K-1
+                          (computed as the convolution of dy with the flipped kernels);
+                          backward-weights pass when K >= 2 and the input rows that 32 positions
+                          touch fit in LDS.  Anything else returns CCT_EUNSUPPORTED when FUSED is
+                          requested explicitly (AUTO never picks an unsupported layout). */
 } cct_lowering_t;
 
 typedef enum {

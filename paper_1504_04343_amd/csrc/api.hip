@@ -136,8 +136,10 @@ bool make_layout(const cct_conv_desc_t& d, int pass, int type, const Geom& g, lo
   } else {
     int BM, BN, BK;
     gemm_nt_tile(g.Mr, g.Kd, &BM, &BN, &BK);
-    take(dt_rows * L->ld * es, &L->dt_off, &L->dt_bytes);
-    if (type != CCT_LOWER_TYPE1 || es == 2) take(rt_rows * L->ld * es, &L->rt_off, &L->rt_bytes);
+    if (type != CCT_LOWER_FUSED) {  // the fused layout has neither D^T nor dR^T
+      take(dt_rows * L->ld * es, &L->dt_off, &L->dt_bytes);
+      if (type != CCT_LOWER_TYPE1 || es == 2) take(rt_rows * L->ld * es, &L->rt_off, &L->rt_bytes);
+    }
     // split the reduction so that about 1024 workgroups exist, partials capped at 256 MiB
     const long long tiles = (long long)((g.Mr + BM - 1) / BM) * ((g.Kd + BN - 1) / BN) * d.groups;
     long long S = std::max(1LL, 1024 / std::max(1LL, tiles));
@@ -160,7 +162,12 @@ bool type_supported(const cct_conv_desc_t& d, int pass, int type) {
   if (type < CCT_LOWER_TYPE1 || type > CCT_LOWER_FUSED) return false;
   if (type == CCT_LOWER_FUSED) {
     if (d.precision != CCT_PREC_F32) return false;
-    if (pass == CCT_PASS_BACKWARD_WEIGHTS) return false;
+    // backward-weights: the staged regions of 32 positions must fit in LDS
+    if (pass == CCT_PASS_BACKWARD_WEIGHTS &&
+        !conv_bwdw_fused_fits(d.C, d.H, d.W, d.K, d.stride, d.pad, (d.H + 2 * d.pad - d.K) / d.stride + 1,
+                              (d.W + 2 * d.pad - d.K) / d.stride + 1, d.C / d.groups,
+                              d.O / d.groups, d.O))
+      return false;
     // backward-data is fused as a convolution of dy with the flipped kernels: stride 1 only
     if (pass == CCT_PASS_BACKWARD_DATA && (d.stride != 1 || d.pad > d.K - 1)) return false;
     if ((long long)d.C * d.H * d.W >= kIntMax) return false;  // 32-bit offsets inside one image
@@ -246,6 +253,11 @@ double model_cost(const cct_conv_desc_t& d, int pass, int type) {
       launches += 1.0;
     }
     rate *= eff(g.Kd) * fill(g.Kd, cols) * short_k(g.Mr);
+  } else if (type == CCT_LOWER_FUSED) {
+    // split partial products straight from x and dy; the tiles of one split re-read both through L2
+    gemm_bytes = x_bytes + y_bytes;
+    launches += 1.0;
+    rate *= kFusedGemmFactor * eff(g.Mr) * eff(g.Kd);
   } else {
     index_bytes += x_bytes + dt_elems * es;      // lowering
     gemm_bytes += dt_elems * es;
@@ -646,6 +658,20 @@ int cct_conv_backward_weights(const cct_conv_desc_t* desc, const float* x, const
     const long long ncols = (long long)ni * g.Pc;
     const float* xc = x + n0 * d.C * d.H * d.W;
     const float* dyc = dy + n0 * d.O * P;
+    if (type == CCT_LOWER_FUSED) {
+      ConvBwdW f;
+      std::memset(&f, 0, sizeof(f));
+      f.x = xc; f.dy = dyc;
+      f.Cpart = reinterpret_cast<float*>(ws + L.part_off);
+      f.C = d.C; f.H = d.H; f.W = d.W; f.O = d.O; f.Hout = g.Hout; f.Wout = g.Wout;
+      f.s = d.stride; f.p = d.pad; f.Cg = g.Cg; f.Og = g.Og; f.K = d.K;
+      f.nimg = ni; f.G = d.groups; f.S = L.S; f.split_len = L.split_len;
+      rc = launch_conv_bwdw_fused(f, st);
+      if (rc) return rc;
+      rc = launch_reduce_dw(f.Cpart, dw, L.S, pd, chunk > 0, st);
+      if (rc) return rc;
+      continue;
+    }
     rc = launch_lower(xc, ws + L.dt_off, L.ld, ni, d.C, g.lower, bf16, st);
     if (rc) return rc;
     GemmNT p;

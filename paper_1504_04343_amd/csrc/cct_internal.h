@@ -88,6 +88,20 @@ int launch_gemm_nt(const GemmNT& p, hipStream_t st);
 // Fused forward with LDS-staged lowering (p.gather must be set).  CCT_EUNSUPPORTED = the shape
 // does not fit its staging area and nothing was launched: use launch_gemm_tn instead.
 int launch_conv_fused(const GemmTN& p, hipStream_t st);
+// Fused backward-weights pass: split partial products of dy (NCHW, read in place) with the
+// Type-1 lowering of x built in LDS.  Cpart[s][q][oo][(ci,i,j)], compact, S splits of split_len
+// positions (a multiple of 32) over the nimg*Hout*Wout positions.
+struct ConvBwdW {
+  const float* x;
+  const float* dy;
+  float* Cpart;
+  int C, H, W, O, Hout, Wout, s, p, Cg, Og, K;
+  int nimg, G, S, split_len;
+};
+// false = the geometry does not fit the kernel's LDS staging (use a materialised layout)
+bool conv_bwdw_fused_fits(int C, int H, int W, int K, int s, int pad, int Hout, int Wout, int Cg,
+                          int Og, int O);
+int launch_conv_bwdw_fused(const ConvBwdW& p, hipStream_t st);
 // Tile sizes the launchers will use for a problem (so that the planner can pad the packs).
 void gemm_tn_tile(int M, int Ncols, int* BM, int* BN, int* BK);
 void gemm_nt_tile(int M, int N, int* BM, int* BN, int* BK);

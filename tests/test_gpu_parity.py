@@ -138,10 +138,26 @@ def test_backward_data_matches_oracle(B, L, lowering):
     assert rel_err(got, want) <= TOL_F32
 
 
-@pytest.mark.parametrize("L", SMALL, ids=IDS)
-@pytest.mark.parametrize("lowering", [1, 2, 3])
+# shapes whose backward-weights pass has no fused form: 1x1 kernels, and windows whose staged
+# input rows (the rows 32 consecutive positions can reach) exceed what the kernel stages in LDS
+FUSED_BWDW_UNSUPPORTED = {"k1", "tiny", "conv1_like", "stride3_g3", "single_pixel_out"}
+BWDW_EXTRA = [
+    layer("many_images", 37, 20, 9, 7, 40, 3, 1, 1, 2),          # 2331 positions: several splits
+    layer("tiny_planes", 50, 4, 4, 4, 5, 2, 1, 0, 1),            # 9 positions per image: a chunk spans 4 or 5 images
+    layer("stride2_pad", 9, 6, 15, 15, 10, 3, 2, 1, 2),
+    layer("k7_s3", 5, 3, 30, 26, 12, 7, 3, 2, 1),
+]
+
+
+@pytest.mark.parametrize("L", SMALL + BWDW_EXTRA, ids=IDS + [L.name for L in BWDW_EXTRA])
+@pytest.mark.parametrize("lowering", [1, 2, 3, 4])
 def test_backward_weights_matches_oracle(B, L, lowering):
     x, _, _, dy = inputs(L)
+    if lowering == 4 and L.name in FUSED_BWDW_UNSUPPORTED:
+        with pytest.raises(B.CctError) as e:
+            gpu_backward_weights(B, L, x, dy, lowering)
+        assert e.value.code == B.EUNSUPPORTED
+        return
     dw_want, db_want = oracle.conv_backward_weights(odims(oracle, L), x, dy)
     dw, db = gpu_backward_weights(B, L, x, dy, lowering)
     assert np.isfinite(dw).all() and np.isfinite(db).all()
@@ -156,8 +172,9 @@ def test_backward_chunked_batch(B, chunk):
     od = odims(oracle, L)
     assert rel_err(gpu_backward_data(B, L, w, dy, 1, chunk=chunk), oracle.conv_backward_data(od, w, dy)) <= TOL_F32
     dw_want, db_want = oracle.conv_backward_weights(od, x, dy)
-    dw, db = gpu_backward_weights(B, L, x, dy, 1, chunk=chunk)
-    assert rel_err(dw, dw_want) <= TOL_F32 and rel_err(db, db_want) <= TOL_F32
+    for lowering in (1, 4):
+        dw, db = gpu_backward_weights(B, L, x, dy, lowering, chunk=chunk)
+        assert rel_err(dw, dw_want) <= TOL_F32 and rel_err(db, db_want) <= TOL_F32, lowering
 
 
 def test_backward_weights_without_dbias_and_deterministic(B):
@@ -214,11 +231,15 @@ def test_unsupported_and_workspace_errors(B):
     assert e.value.code == B.EWORKSPACE
     with pytest.raises(ValueError):
         B.cct_conv_forward(d, dev(x)[:2], dev(w), dev(b), y, B.alloc_workspace(d, 0))
-    # there is no fused backward-weights pass
-    df = desc_of(B, L, B.LOWER_FUSED)
+    # there is no fused bf16 path, and no fused backward-weights pass for 1x1 kernels
+    df = desc_of(B, L, B.LOWER_FUSED, B.PREC_BF16_IN_F32_ACC)
     with pytest.raises(B.CctError) as e:
-        B.cct_conv_workspace_bytes(df, B.PASS_BACKWARD_WEIGHTS)
+        B.cct_conv_workspace_bytes(df, B.PASS_FORWARD)
     assert e.value.code == B.EUNSUPPORTED
+    with pytest.raises(B.CctError) as e:
+        B.cct_conv_workspace_bytes(desc_of(B, SMALL[7], B.LOWER_FUSED), B.PASS_BACKWARD_WEIGHTS)
+    assert e.value.code == B.EUNSUPPORTED
+    df = desc_of(B, L, B.LOWER_FUSED)
     with pytest.raises(B.CctError) as e:
         B.cct_lowered_shape(df, B.LOWER_FUSED)
     assert e.value.code == B.EINVAL
