@@ -127,7 +127,7 @@ def main():
     prof = B.cct_profile_read(64)
     total_kernel_ms = sum(e["total_ms"] for e in prof)
     def is_mfma(e):   # the GEMMs and the fused conv kernel (matrix-core bound); the rest stream
-        return e["name"].startswith(("gemm_", "conv_fused"))
+        return e["name"].startswith(("gemm_", "conv_fused", "conv_bwdw_fused"))
     gemms = [e for e in prof if is_mfma(e)]
     dom = max(gemms, key=lambda e: e["total_ms"])
     avg_ms = dom["total_ms"] / dom["launches"]

@@ -52,7 +52,7 @@ __device__ __forceinline__ float buf_load(__amdgpu_buffer_rsrc_t r, unsigned vof
 }
 
 template <int BM, int WM, int WN, int V, int XR>
-__global__ __launch_bounds__(NT, 2) void conv_bwdw_fused_f32(ConvBwdW p, BwdwGeom fg, int tiles_m,
+__global__ __launch_bounds__(NT, 3) void conv_bwdw_fused_f32(ConvBwdW p, BwdwGeom fg, int tiles_m,
                                                              int tiles_n) {
   constexpr int WAVES_N = BN / (32 * WN);
   constexpr int WAVES_M = BM / (32 * WM);
@@ -65,7 +65,7 @@ __global__ __launch_bounds__(NT, 2) void conv_bwdw_fused_f32(ConvBwdW p, BwdwGeo
   extern __shared__ __attribute__((aligned(16))) float smem[];
   float* As = smem;                                   // [2][BM*LDK]
   float* Xs = smem + 2 * BM * LDK;                    // [2][XS]
-  int* tabs = reinterpret_cast<int*>(Xs + 2 * XS);    // [2][BK]
+  int* tabs = reinterpret_cast<int*>(Xs + 2 * XS);    // [3][BK]: chunk t uses slot t % 3
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -219,35 +219,35 @@ __global__ __launch_bounds__(NT, 2) void conv_bwdw_fused_f32(ConvBwdW p, BwdwGeo
   if (ktiles > 1) CCT_BW_LOAD(col_begin + BK, 1);
   __syncthreads();
 
-  int po[QS][4], pon[4];
+  // Position offsets run two steps ahead of the MFMAs: pa holds those of the step whose operands
+  // are read next, pb those of the step after it (being fetched from the table).
+  int pa[4], pb[4];
   f32x4 a[2][WM];
   float b[2][WN][4];
 #pragma unroll
-  for (int q = 0; q < QS; ++q)
-#pragma unroll
-    for (int e = 0; e < 4; ++e) po[q][e] = 0;
-#pragma unroll
-  for (int e = 0; e < 4; ++e) pon[e] = 0;
+  for (int e = 0; e < 4; ++e) pa[e] = pb[e] = 0;
   if (ktiles > 0) {
+    const i32x4 v0 = *reinterpret_cast<const i32x4*>(tabs + lane_hi * 4);
+    const i32x4 v1 = *reinterpret_cast<const i32x4*>(tabs + 8 + lane_hi * 4);
 #pragma unroll
-    for (int q = 0; q < QS; ++q) {
-      const i32x4 v = *reinterpret_cast<const i32x4*>(tabs + q * 8 + lane_hi * 4);
-#pragma unroll
-      for (int e = 0; e < 4; ++e) po[q][e] = v[e];
+    for (int e = 0; e < 4; ++e) {
+      pa[e] = v1[e];
+      pb[e] = v0[e];   // only used for the first reads below
     }
 #pragma unroll
     for (int i = 0; i < WM; ++i) a[0][i] = *reinterpret_cast<const f32x4*>(&As[a_lds + i * 32 * LDK]);
 #pragma unroll
     for (int j = 0; j < WN; ++j)
 #pragma unroll
-      for (int e = 0; e < 4; ++e) b[0][j][e] = Xs[po[0][e] + laneoff[j]];
+      for (int e = 0; e < 4; ++e) b[0][j][e] = Xs[pb[e] + laneoff[j]];
   }
-  __syncthreads();  // table slot 0 is rewritten (for chunk 2) in the middle of chunk 0
 
   // Main loop: the pipeline of the plain backward-weights GEMM.  Operand reads run one step (8
-  // positions) ahead; in the middle of chunk t the values loaded for chunk t+1 go to LDS and the
-  // loads of chunk t+2 are issued; the barrier sits before the last step.  The position table of
-  // chunk t+2 is written during chunk t and read during chunk t+1.
+  // positions) ahead and their position offsets one step further; in the middle of chunk t the
+  // values loaded for chunk t+1 go to LDS and the loads of chunk t+2 are issued; the barrier sits
+  // before the last step.  The position table of chunk t+2 is written during chunk t into the
+  // third slot, which no wave reads any more: the tables of chunks t and t+1 are still in use.
+  int ts0 = 0, ts1 = 1, ts2 = 2;  // table slots of chunks t, t+1, t+2
   for (int t = 0; t < ktiles; ++t) {
     const int buf = t & 1;
     const bool more = t + 1 < ktiles;
@@ -257,6 +257,7 @@ __global__ __launch_bounds__(NT, 2) void conv_bwdw_fused_f32(ConvBwdW p, BwdwGeo
 #pragma unroll
     for (int q = 0; q < QS; ++q) {
       const int cur = q & 1, nxt = cur ^ 1;
+      // on entry pa = offsets of step q+1 (of the next chunk when q = 3)
       if (q + 1 < QS) {
 #pragma unroll
         for (int i = 0; i < WM; ++i)
@@ -264,7 +265,7 @@ __global__ __launch_bounds__(NT, 2) void conv_bwdw_fused_f32(ConvBwdW p, BwdwGeo
 #pragma unroll
         for (int j = 0; j < WN; ++j)
 #pragma unroll
-          for (int e = 0; e < 4; ++e) b[nxt][j][e] = xs[po[q + 1][e] + laneoff[j]];
+          for (int e = 0; e < 4; ++e) b[nxt][j][e] = xs[pa[e] + laneoff[j]];
       } else {
         __syncthreads();
         if (more) {
@@ -274,21 +275,16 @@ __global__ __launch_bounds__(NT, 2) void conv_bwdw_fused_f32(ConvBwdW p, BwdwGeo
 #pragma unroll
           for (int j = 0; j < WN; ++j)
 #pragma unroll
-            for (int e = 0; e < 4; ++e) b[nxt][j][e] = xs_n[pon[e] + laneoff[j]];
-          // positions of the next chunk's steps 1.. (step 0's were fetched one step ago)
-#pragma unroll
-          for (int qq = 1; qq < QS; ++qq) {
-            const i32x4 v =
-                *reinterpret_cast<const i32x4*>(tabs + (buf ^ 1) * BK + qq * 8 + lane_hi * 4);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) po[qq][e] = v[e];
-          }
+            for (int e = 0; e < 4; ++e) b[nxt][j][e] = xs_n[pa[e] + laneoff[j]];
         }
       }
-      if (q == QS - 2 && more) {
-        const i32x4 v = *reinterpret_cast<const i32x4*>(tabs + (buf ^ 1) * BK + lane_hi * 4);
+      // fetch the offsets of step q+2: same chunk for q < 2, else steps 0 / 1 of the next chunk
+      if (q + 2 < QS || more) {
+        const int slot = q + 2 < QS ? ts0 : ts1;
+        const i32x4 v =
+            *reinterpret_cast<const i32x4*>(tabs + slot * BK + ((q + 2) % QS) * 8 + lane_hi * 4);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) pon[e] = v[e];
+        for (int e = 0; e < 4; ++e) pb[e] = v[e];
       }
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -300,14 +296,18 @@ __global__ __launch_bounds__(NT, 2) void conv_bwdw_fused_f32(ConvBwdW p, BwdwGeo
             acc[i][j] =
                 __builtin_amdgcn_mfma_f32_32x32x2f32(a[cur][i][e], b[cur][j][e], acc[i][j], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) pa[e] = pb[e];
       if (q == QS / 2 - 1 && more) {
         CCT_BW_STORE(buf ^ 1);
-        if (t + 2 < ktiles) CCT_BW_LOAD(col_begin + (t + 2) * BK, buf);
+        if (t + 2 < ktiles) CCT_BW_LOAD(col_begin + (t + 2) * BK, ts2);
         __builtin_amdgcn_sched_barrier(0);
       }
     }
-#pragma unroll
-    for (int e = 0; e < 4; ++e) po[0][e] = pon[e];
+    const int ts = ts0;
+    ts0 = ts1;
+    ts1 = ts2;
+    ts2 = ts;
   }
 #undef CCT_BW_LOAD
 #undef CCT_BW_STORE
@@ -369,7 +369,7 @@ bool make_geom(int C, int H, int W, int K, int s, int pad, int Hout, int Wout, i
   make_fastdiv_parts((int)Wp, &fg->mWp, &fg->sWp);
   make_fastdiv_parts((int)KK, &fg->mKK, &fg->sKK);
   make_fastdiv_parts(K, &fg->mK, &fg->sK);
-  *lds = 4ull * (2ull * BM * LDK + 2ull * XR * (V * NT + 8) + 2ull * BK);
+  *lds = 4ull * (2ull * BM * LDK + 2ull * XR * (V * NT + 8) + 3ull * BK);
   return *lds <= (size_t)kMaxLds;
 }
 
