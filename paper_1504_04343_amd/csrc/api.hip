@@ -698,8 +698,10 @@ int cct_conv_backward_weights(const cct_conv_desc_t* desc, const float* x, const
     if (rc) return rc;
   }
   if (dbias) {
+    // about 2048 workgroups: each sums the planes of every nblk-th image of one kernel
+    const int nblk = std::max(1, std::min({d.N, kDbiasBlocks, (2048 + d.O - 1) / d.O}));
     rc = launch_dbias(dy, dbias, reinterpret_cast<float*>(ws + L.scratch_off), d.N, d.O, (int)P,
-                      kDbiasBlocks, st);
+                      nblk, st);
     if (rc) return rc;
   }
   return CCT_OK;

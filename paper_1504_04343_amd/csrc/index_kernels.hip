@@ -103,23 +103,42 @@ __global__ __launch_bounds__(TPB) void reduce_dw_kernel(const float* __restrict_
 }
 
 // dbias, stage 1: block (o, blk) sums the planes dy[n, o, :, :] of the images n = blk, blk+nblk, ...
+// Its threads walk the (image, pixel) pairs of those planes as one flat range, four independent
+// partial sums per thread (loads of four iterations in flight), then combine: lanes by shuffles,
+// the four waves through LDS, always in the same order.
 __global__ __launch_bounds__(TPB) void dbias_stage1(const float* __restrict__ dy,
                                                     float* __restrict__ scratch, int N, int O, int P,
-                                                    int nblk) {
-  __shared__ float red[TPB];
+                                                    int nblk, FastDiv divP) {
+  __shared__ float red[TPB / 64];
   const int o = blockIdx.x / nblk, blk = blockIdx.x % nblk;
-  float acc = 0.0f;
-  for (int n = blk; n < N; n += nblk) {
-    const float* src = dy + ((long long)n * O + o) * P;
-    for (int t = threadIdx.x; t < P; t += TPB) acc += src[t];
+  const int nimg = (N - blk + nblk - 1) / nblk;          // images of this block
+  const long long total = (long long)nimg * P;
+  const long long img_stride = (long long)nblk * O * P;
+  const float* base = dy + ((long long)blk * O + o) * P;
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  long long t = threadIdx.x;
+  for (; t + 3 * TPB < total; t += 4 * TPB) {
+    float v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int e = (int)(t + u * TPB);
+      const int i = fdiv(e, divP);
+      v[u] = base[i * img_stride + (e - i * P)];
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) acc[u] += v[u];
   }
-  red[threadIdx.x] = acc;
+  for (; t < total; t += TPB) {
+    const int e = (int)t;
+    const int i = fdiv(e, divP);
+    acc[0] += base[i * img_stride + (e - i * P)];
+  }
+  float sum = (acc[0] + acc[1]) + (acc[2] + acc[3]);
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) sum += __shfl_down(sum, off, 64);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = sum;
   __syncthreads();
-  for (int s = TPB / 2; s > 0; s >>= 1) {
-    if ((int)threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
-    __syncthreads();
-  }
-  if (threadIdx.x == 0) scratch[blockIdx.x] = red[0];
+  if (threadIdx.x == 0) scratch[blockIdx.x] = ((red[0] + red[1]) + red[2]) + red[3];
 }
 
 __global__ void dbias_stage2(const float* __restrict__ scratch, float* __restrict__ dbias, int O,
@@ -176,7 +195,7 @@ int launch_dbias(const float* dy, float* dbias, float* scratch, int N, int O, in
   if (!grid_ok((long long)O * nblk)) return CCT_EUNSUPPORTED;
   ProfScope ps("dbias_stage1+2", 0.0, 4.0 * N * O * P, st);
   hipLaunchKernelGGL(dbias_stage1, dim3((unsigned)(O * nblk)), dim3(TPB), 0, st, dy, scratch, N, O,
-                     P, nblk);
+                     P, nblk, make_fastdiv(P));
   CCT_CHECK_LAUNCH();
   hipLaunchKernelGGL(dbias_stage2, dim3((unsigned)((O + 63) / 64)), dim3(64), 0, st, scratch, dbias,
                      O, nblk);
