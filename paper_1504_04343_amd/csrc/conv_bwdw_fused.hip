@@ -394,7 +394,7 @@ int launch_variant(const ConvBwdW& p, BwdwGeom fg, size_t lds, hipStream_t st) {
   if (p.split_len % BK) return CCT_EINVAL;
   dim3 grid((unsigned)(tiles * p.S), (unsigned)p.G);
   char name[96];
-  snprintf(name, sizeof(name), "conv_bwdw_fused_f32<%d, %d, %d>", BM, WM, WN);
+  snprintf(name, sizeof(name), "conv_bwdw_fused_f32<%d, %d, %d, %d, %d>", BM, WM, WN, fg.V, fg.XR);
   ProfScope ps(name, 2.0 * fg.M * fg.N * (double)fg.ncols * p.G,
                4.0 * ((double)p.nimg * p.C * p.H * p.W + (double)p.nimg * p.O * fg.P +
                       (double)fg.M * fg.N * p.S * p.G),

@@ -115,30 +115,46 @@ __global__ __launch_bounds__(NT) void conv_fused_f32(GemmTN p, FusedGeom fg, int
   }
 
   // ---- staging ---------------------------------------------------------------------------------
-  long long stg_src[RING ? QU : 1];
+  // Ring mode: a thread owns region cells q = tid + u*256 of every channel.  The cell's byte
+  // offset inside the tensor (relative to the first image and the group's first channel) is fixed,
+  // dead cells (zero padding, cells past the rows this workgroup needs) get an offset that fails
+  // the buffer range check and load as zero, and the channel enters through the scalar offset of
+  // the buffer load: staging 16 channels costs no vector-ALU work besides the LDS addresses.
+  unsigned stg_voff[RING ? QU : 1];
   float stg[RING ? CGRP * QU : 1];
+  const float* Xb = p.B ? reinterpret_cast<const float*>(p.B) +
+                              ((long long)n_f * p.gC + (long long)g * p.gCg) * chan_stride
+                        : nullptr;
   if (RING) {
+    const long long rel0 = ((long long)n_f * p.gC + (long long)g * p.gCg) * chan_stride;
 #pragma unroll
-    for (int u = 0; u < QU; ++u) stg_src[u] = src_of(tid + u * NT);
+    for (int u = 0; u < QU; ++u) {
+      const long long src = src_of(tid + u * NT);
+      stg_voff[u] = src >= 0 ? (unsigned)(src - rel0) * 4u : 0x80000000u;
+    }
   }
 #define CCT_STAGE_LOAD(GIDX)                                                                \
   {                                                                                         \
-    _Pragma("unroll") for (int cc = 0; cc < CGRP; ++cc) {                                   \
-      const bool chan_ok = (GIDX) * CGRP + cc < p.gCg;                                      \
-      _Pragma("unroll") for (int u = 0; u < QU; ++u) {                                      \
-        float v = 0.f;                                                                      \
-        if (chan_ok && stg_src[u] >= 0)                                                     \
-          v = X[stg_src[u] + ((long long)(GIDX) * CGRP + cc) * chan_stride];                \
-        stg[cc * QU + u] = v;                                                               \
+    _Pragma("unroll") for (int u = 0; u < QU; ++u) {                                        \
+      if (tid + u * NT < fg.R) { /* whole waves: R is a multiple of 64 */                   \
+        _Pragma("unroll") for (int cc = 0; cc < CGRP; ++cc) {                               \
+          const int ch = (GIDX) * CGRP + cc;                                                \
+          const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(              \
+              const_cast<float*>(Xb), 0, ch < p.gCg ? 0x7fffffff : 0, 0x00020000);          \
+          stg[cc * QU + u] = __builtin_bit_cast(                                            \
+              float, __builtin_amdgcn_raw_buffer_load_b32(                                  \
+                         rs, (int)stg_voff[u], (int)((unsigned)ch * (unsigned)chan_stride * 4u), 0)); \
+        }                                                                                   \
       }                                                                                     \
     }                                                                                       \
   }
 #define CCT_STAGE_STORE(SLOT)                                                               \
   {                                                                                         \
-    _Pragma("unroll") for (int cc = 0; cc < CGRP; ++cc) {                                   \
-      _Pragma("unroll") for (int u = 0; u < QU; ++u) {                                      \
-        const int q = tid + u * NT;                                                         \
-        if (q < fg.R) Xs[(SLOT) * slot_floats + cc * fg.R + q] = stg[cc * QU + u];          \
+    _Pragma("unroll") for (int u = 0; u < QU; ++u) {                                        \
+      const int q = tid + u * NT;                                                           \
+      if (q < fg.R) {                                                                       \
+        _Pragma("unroll") for (int cc = 0; cc < CGRP; ++cc)                                 \
+          Xs[(SLOT) * slot_floats + cc * fg.R + q] = stg[cc * QU + u];                      \
       }                                                                                     \
     }                                                                                       \
   }
@@ -396,7 +412,10 @@ int launch_conv_fused(const GemmTN& p, hipStream_t st) {
     fg.tab_tiles = p.Kpad / BK;
   } else {
     ring = true;
-    if (R > QU * NT || fg.KK < 4) return CCT_EUNSUPPORTED;
+    fg.R = (int)((R + 63) / 64 * 64);  // whole waves own the cells of a region
+    // staged cells are addressed with 32-bit byte offsets from the workgroup's first image
+    if ((T + 1) * p.gC * p.gH * p.gW >= (1LL << 29)) return CCT_EUNSUPPORTED;
+    if (fg.R > QU * NT || fg.KK < 4) return CCT_EUNSUPPORTED;
     fg.ngroups = (p.gCg + CGRP - 1) / CGRP;
     fg.cg = CGRP;
     fg.tab_tiles = fg.KK;
