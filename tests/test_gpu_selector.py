@@ -19,42 +19,54 @@ def B():
     return binding
 
 
-def time_forward(B, L, lowering, reps=5):
+def time_pass(B, L, lowering, pass_, reps=5):
     import torch
     d = desc_of(B, L, lowering)
     x, w, b = dev(synth.make_x(L)), dev(synth.make_w(L)), dev(synth.make_bias(L))
-    y = torch.empty((L.N, L.O, L.Hout, L.Wout), device="cuda")
-    ws = B.alloc_workspace(d, B.PASS_FORWARD)
-    B.cct_conv_forward(d, x, w, b, y, ws)
+    dy = dev(synth.make_dy(L))
+    y, dx, dw, db = torch.empty_like(dy), torch.empty_like(x), torch.empty_like(w), torch.empty_like(b)
+    ws = B.alloc_workspace(d, pass_)
+
+    def run():
+        if pass_ == B.PASS_FORWARD:
+            B.cct_conv_forward(d, x, w, b, y, ws)
+        elif pass_ == B.PASS_BACKWARD_DATA:
+            B.cct_conv_backward_data(d, w, dy, dx, ws)
+        else:
+            B.cct_conv_backward_weights(d, x, dy, dw, db, ws)
+
+    run()
     torch.cuda.synchronize()
     best = float("inf")
     for _ in range(reps):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
-        B.cct_conv_forward(d, x, w, b, y, ws)
+        run()
         e1.record()
         torch.cuda.synchronize()
         best = min(best, e0.elapsed_time(e1))
     return best
 
 
-def measured(B, L):
+def measured(B, L, pass_=0):
     d = desc_of(B, L)
     costs = {}
     for t in (1, 2, 3, 4):
         try:
-            costs[t] = B.cct_lowering_cost(d, B.PASS_FORWARD, t)
+            costs[t] = B.cct_lowering_cost(d, pass_, t)
+            B.cct_conv_workspace_bytes(desc_of(B, L, t), pass_)     # raises when unsupported
         except B.CctError:
-            pass
+            costs.pop(t, None)
     cheapest = min(costs.values())
     # layouts the model prices at more than 5x the cheapest are not worth running (conv1 Type 3)
-    return {t: time_forward(B, L, t) for t, c in costs.items() if c <= 5 * cheapest}
+    return {t: time_pass(B, L, t, pass_) for t, c in costs.items() if c <= 5 * cheapest}
 
 
+@pytest.mark.parametrize("pass_", [0, 1, 2], ids=["forward", "backward_data", "backward_weights"])
 @pytest.mark.parametrize("L", synth.caffenet(64), ids=lambda L: L.name)
-def test_regret_on_caffenet_layers(B, L):
-    times = measured(B, L)
-    pick = B.cct_pick_lowering(desc_of(B, L), B.PASS_FORWARD)
+def test_regret_on_caffenet_layers(B, L, pass_):
+    times = measured(B, L, pass_)
+    pick = B.cct_pick_lowering(desc_of(B, L), pass_)
     assert pick in times
     assert times[pick] <= (1 + REGRET) * min(times.values()), (pick, times)
 
