@@ -149,7 +149,8 @@ def main():
     stream_ms = sum(e["total_ms"] for e in streams)
     phases = {
         "all_gemm_tflops": round(all_gemm_flops / (all_gemm_ms * 1e-3) / 1e12, 2),
-        "all_gemm_frac_of_fp32_mfma_peak": round(all_gemm_flops / (all_gemm_ms * 1e-3) / 1e12 / peak, 4),
+        "all_gemm_frac_of_%s_mfma_peak" % ("fp32" if args.precision == "f32" else "bf16"):
+            round(all_gemm_flops / (all_gemm_ms * 1e-3) / 1e12 / peak, 4),
         "gemm_share_of_kernel_time": round(all_gemm_ms / total_kernel_ms, 3),
         "lower_lift_GBps": round(stream_bytes / (stream_ms * 1e-3) / 1e9, 1),
         "lower_lift_frac_of_hbm_peak": round(stream_bytes / (stream_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
@@ -199,7 +200,9 @@ def main():
                    "batch": args.batch, "gflop_per_step": round(flops_per_step / 1e9, 2),
                    "lowering_picked": {t["L"].name: [t["picked"][p] for p in passes] for t in state},
                    "workspace_MiB": ws_bytes >> 20,
-                   "frac_of_fp32_mfma_peak": round(gflops / 1e3 / PEAK_FP32_MFMA_TFLOPS, 4)},
+                   "frac_of_%s_mfma_peak" % ("fp32" if args.precision == "f32" else "bf16"):
+                       round(gflops / 1e3 / (PEAK_FP32_MFMA_TFLOPS if args.precision == "f32"
+                                             else PEAK_BF16_MFMA_TFLOPS), 4)},
         "roofline": roofline,
         "phases": phases,
         "cpu_baseline": cpu,
