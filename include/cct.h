@@ -57,9 +57,11 @@ typedef enum {
                           its operand tiles from x (through LDS when they fit).  fp32 only;
                           forward pass; backward-data pass of stride-1 layers with pad <= K-1
                           (computed as the convolution of dy with the flipped kernels);
-                          backward-weights pass when K >= 2 and the input rows that 32 positions
-                          touch fit in LDS.  Anything else returns CCT_EUNSUPPORTED when FUSED is
-                          requested explicitly (AUTO never picks an unsupported layout). */
+                          backward-weights pass when the input rows that 32 positions touch fit
+                          in LDS (K >= 2), or when the layer is unpadded (the split-K GEMM then
+                          gathers the lowered rows from x).  Anything else returns
+                          CCT_EUNSUPPORTED when FUSED is requested explicitly (AUTO never picks
+                          an unsupported layout). */
 } cct_lowering_t;
 
 typedef enum {

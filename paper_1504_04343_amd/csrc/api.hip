@@ -162,12 +162,15 @@ bool type_supported(const cct_conv_desc_t& d, int pass, int type) {
   if (type < CCT_LOWER_TYPE1 || type > CCT_LOWER_FUSED) return false;
   if (type == CCT_LOWER_FUSED) {
     if (d.precision != CCT_PREC_F32) return false;
-    // backward-weights: the staged regions of 32 positions must fit in LDS
-    if (pass == CCT_PASS_BACKWARD_WEIGHTS &&
-        !conv_bwdw_fused_fits(d.C, d.H, d.W, d.K, d.stride, d.pad, (d.H + 2 * d.pad - d.K) / d.stride + 1,
-                              (d.W + 2 * d.pad - d.K) / d.stride + 1, d.C / d.groups,
-                              d.O / d.groups, d.O))
-      return false;
+    // backward-weights: the input rows of 32 positions must fit in LDS; an unpadded layer can
+    // also gather its lowered rows inside the split-K GEMM
+    if (pass == CCT_PASS_BACKWARD_WEIGHTS) {
+      const int Ho = (d.H + 2 * d.pad - d.K) / d.stride + 1, Wo = (d.W + 2 * d.pad - d.K) / d.stride + 1;
+      if (!conv_bwdw_fused_fits(d.C, d.H, d.W, d.K, d.stride, d.pad, Ho, Wo, d.C / d.groups,
+                                d.O / d.groups, d.O) &&
+          !(d.pad == 0 && gemm_nt_gather_fits(d.C, d.H, d.W, d.O, Ho, Wo)))
+        return false;
+    }
     // backward-data is fused as a convolution of dy with the flipped kernels: stride 1 only
     if (pass == CCT_PASS_BACKWARD_DATA && (d.stride != 1 || d.pad > d.K - 1)) return false;
     if ((long long)d.C * d.H * d.W >= kIntMax) return false;  // 32-bit offsets inside one image
@@ -667,6 +670,20 @@ int cct_conv_backward_weights(const cct_conv_desc_t* desc, const float* x, const
       f.s = d.stride; f.p = d.pad; f.Cg = g.Cg; f.Og = g.Og; f.K = d.K;
       f.nimg = ni; f.G = d.groups; f.S = L.S; f.split_len = L.split_len;
       rc = launch_conv_bwdw_fused(f, st);
+      if (rc == CCT_EUNSUPPORTED && d.pad == 0) {
+        // the rows do not fit in LDS: split-K GEMM that gathers the lowered rows from x
+        GemmNT q;
+        std::memset(&q, 0, sizeof(q));
+        q.A = dyc; q.a_ms = P; q.a_gs = (long long)g.Og * P;
+        q.amap = ColMap{(int)P, (long long)d.O * P};
+        q.B = xc; q.b_gs = (long long)g.Cg * d.H * d.W;
+        q.Cpart = f.Cpart;
+        q.M = g.Mr; q.N = g.Kd; q.Ncols = (int)ncols;
+        q.G = d.groups; q.S = L.S; q.split_len = L.split_len;
+        q.gather = 1; q.gC = d.C; q.gH = d.H; q.gW = d.W; q.gHout = g.Hout; q.gWout = g.Wout;
+        q.gs = d.stride; q.gCg = g.Cg; q.gK = d.K;
+        rc = launch_gemm_nt(q, st);
+      }
       if (rc) return rc;
       rc = launch_reduce_dw(f.Cpart, dw, L.S, pd, chunk > 0, st);
       if (rc) return rc;

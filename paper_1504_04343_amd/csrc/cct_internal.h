@@ -81,10 +81,17 @@ struct GemmNT {
   int M, N, Ncols;
   int G, S, split_len; // split_len is a multiple of the kernel's BK
   int bf16;
+  // Fused lowering of an unpadded layer (gather != 0; fp32, A read in place): B is the NCHW
+  // tensor x of the chunk and row n = (ci, i, j) of the Type-1 lowered matrix is gathered on
+  // the fly, B(n, col) = x[img, q*Cg + ci, r*s + i, c*s + j] with (img, r, c) decoded from col.
+  int gather;
+  int gC, gH, gW, gHout, gWout, gs, gCg, gK;
 };
 
 int launch_gemm_tn(const GemmTN& p, hipStream_t st);
 int launch_gemm_nt(const GemmNT& p, hipStream_t st);
+// gather mode of the NT GEMM (GemmNT::gather): do its 32-bit offsets cover this geometry?
+bool gemm_nt_gather_fits(int C, int H, int W, int O, int Hout, int Wout);
 // Fused forward with LDS-staged lowering (p.gather must be set).  CCT_EUNSUPPORTED = the shape
 // does not fit its staging area and nothing was launched: use launch_gemm_tn instead.
 int launch_conv_fused(const GemmTN& p, hipStream_t st);

@@ -56,10 +56,21 @@ __device__ __forceinline__ void mma_stage_kcontig(const float* __restrict__ as,
   }
 }
 
+// Fast division constants of the gather mode (see make_fastdiv_parts).
+struct NtGather {
+  unsigned mP, mWout, mKK, mK;
+  int sP, sWout, sKK, sK;
+};
+
 // AVEC: A rows are plain 16-byte aligned matrix rows (inverse-lifted dy of Types 2/3);
 // otherwise A is dy read in place through the NCHW column map (Type 1), 4-byte loads.
-template <int BM, int BN, int BK, int WM, int WN, bool AVEC>
-__global__ __launch_bounds__(NT) void gemm_nt_f32(GemmNT p, int tiles_m, int tiles_n) {
+// BG (with !AVEC): B is not a lowered matrix but the tensor x of an unpadded layer, and row
+// n = (ci, i, j) of the Type-1 lowering is gathered while the tile is loaded.  Both operands then
+// go through buffer loads: a thread's rows give fixed byte offsets, the column of the tile adds
+// one offset per tile, columns past the end of the split fail the range check and load as zero.
+template <int BM, int BN, int BK, int WM, int WN, bool AVEC, bool BG>
+__global__ __launch_bounds__(NT) void gemm_nt_f32(GemmNT p, NtGather ng, int tiles_m, int tiles_n) {
+  static_assert(!(AVEC && BG), "the gather mode reads dy in place");
   constexpr int WAVES_N = BN / (32 * WN);
   constexpr int WAVES_M = BM / (32 * WM);
   static_assert(WAVES_M * WAVES_N == 4, "4 waves per workgroup");
@@ -70,6 +81,7 @@ __global__ __launch_bounds__(NT) void gemm_nt_f32(GemmNT p, int tiles_m, int til
   constexpr int BV_IT = BN * KQ / NT;
   constexpr int AS_IT = BM * BK / NT;    // scalar loads per thread (A, scalar path)
   constexpr int AS_ROWS = NT / BK;       // tile rows covered per scalar pass
+  constexpr int BS_IT = BN * BK / NT;    // scalar loads per thread (B, gather mode)
   static_assert((BM * KQ) % NT == 0 && (BN * KQ) % NT == 0, "tile/thread split");
 
   __shared__ __attribute__((aligned(16))) float As[2][BM * LDK];
@@ -105,18 +117,36 @@ __global__ __launch_bounds__(NT) void gemm_nt_f32(GemmNT p, int tiles_m, int til
   // Rows beyond M / N are clamped to the last valid row: their products land in rows/columns of
   // the tile that are never stored.  Columns beyond Ncols inside a plain lowered matrix are zero
   // padding written by the lowering kernels, so plain rows need no column guard.
-  gptr_f32 b_src[BV_IT];
-  int b_dst[BV_IT];
+  gptr_f32 b_src[BG ? 1 : BV_IT];
+  int b_dst[BG ? 1 : BV_IT];
+  if (!BG) {
 #pragma unroll
-  for (int it = 0; it < BV_IT; ++it) {
-    const int v = tid + it * NT;
-    const int row = v / KQ, kq = v % KQ;
-    b_src[it] = B + (long long)min(n0 + row, p.N - 1) * p.b_ns + col_begin + kq * 4;
-    b_dst[it] = row * LDK + kq * 4;
+    for (int it = 0; it < BV_IT; ++it) {
+      const int v = tid + it * NT;
+      const int row = v / KQ, kq = v % KQ;
+      b_src[it] = B + (long long)min(n0 + row, p.N - 1) * p.b_ns + col_begin + kq * 4;
+      b_dst[it] = row * LDK + kq * 4;
+    }
   }
   gptr_f32 av_src[AVEC ? AV_IT : 1];
   int av_dst[AVEC ? AV_IT : 1];
   const int as_k = tid % BK, as_r0 = tid / BK;
+  // gather mode: fixed byte offsets of this thread's dy rows and of its taps (ci, i, j) in x
+  unsigned g_arow[BG ? AS_IT : 1], g_btap[BG ? BS_IT : 1];
+  const int gP = p.gHout * p.gWout, gHW = p.gH * p.gW;
+  const long long gCHW = (long long)p.gC * gHW;
+  if (BG) {
+#pragma unroll
+    for (int it = 0; it < AS_IT; ++it)
+      g_arow[it] = (unsigned)(min(m0 + as_r0 + it * AS_ROWS, p.M - 1) * (int)p.a_ms) * 4u;
+#pragma unroll
+    for (int it = 0; it < BS_IT; ++it) {
+      const int n = min(n0 + as_r0 + it * AS_ROWS, p.N - 1);
+      const int ci = fdiv_u(n, ng.mKK, ng.sKK), t = n - ci * p.gK * p.gK;
+      const int ti = fdiv_u(t, ng.mK, ng.sK), tj = t - ti * p.gK;
+      g_btap[it] = (unsigned)(ci * gHW + ti * p.gW + tj) * 4u;
+    }
+  }
   if (AVEC) {
 #pragma unroll
     for (int it = 0; it < AV_IT; ++it) {
@@ -127,12 +157,42 @@ __global__ __launch_bounds__(NT) void gemm_nt_f32(GemmNT p, int tiles_m, int til
     }
   }
 
-  f32x4 rb[BV_IT];
+  f32x4 rb[BG ? 1 : BV_IT];
   f32x4 rav[AVEC ? AV_IT : 1];
   float ras[AVEC ? 1 : AS_IT];
+  float rbs[BG ? BS_IT : 1];
 
 #define CCT_NT_LOAD(C0)                                                                   \
   {                                                                                       \
+  if (BG) {                                                                               \
+    const int c0_ = (C0);                                                                 \
+    const int n_f = fdiv_u(c0_, ng.mP, ng.sP);   /* first image of the tile (uniform) */  \
+    const int col = c0_ + as_k;                                                           \
+    const bool ok = col < col_end;                                                        \
+    const int cc = ok ? col : c0_;                                                        \
+    const int n = fdiv_u(cc, ng.mP, ng.sP), pix = cc - n * gP;                            \
+    const int r = fdiv_u(pix, ng.mWout, ng.sWout), c = pix - r * p.gWout;                 \
+    const unsigned aoff =                                                                 \
+        ok ? ((unsigned)(n - n_f) * (unsigned)p.amap.img_stride + (unsigned)pix) * 4u     \
+           : 0x80000000u;                                                                 \
+    const unsigned boff =                                                                 \
+        ok ? ((unsigned)(n - n_f) * (unsigned)gCHW + (unsigned)((r * p.gW + c) * p.gs)) * 4u \
+           : 0x80000000u;                                                                 \
+    const __amdgpu_buffer_rsrc_t rsa = __builtin_amdgcn_make_buffer_rsrc(                 \
+        const_cast<float*>(reinterpret_cast<const float*>(p.A) + (long long)g * p.a_gs +  \
+                           (long long)n_f * p.amap.img_stride),                           \
+        0, 0x7fffffff, 0x00020000);                                                       \
+    const __amdgpu_buffer_rsrc_t rsb = __builtin_amdgcn_make_buffer_rsrc(                 \
+        const_cast<float*>(reinterpret_cast<const float*>(p.B) + (long long)g * p.b_gs +  \
+                           (long long)n_f * gCHW),                                        \
+        0, 0x7fffffff, 0x00020000);                                                       \
+    _Pragma("unroll") for (int it = 0; it < AS_IT; ++it)                                  \
+      ras[it] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(           \
+                                              rsa, (int)(g_arow[it] + aoff), 0, 0));      \
+    _Pragma("unroll") for (int it = 0; it < BS_IT; ++it)                                  \
+      rbs[it] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(           \
+                                              rsb, (int)(g_btap[it] + boff), 0, 0));      \
+  } else {                                                                                \
     _Pragma("unroll") for (int it = 0; it < BV_IT; ++it) {                                \
       rb[it] = *(gptr_f32x4)(b_src[it]);                                                  \
       b_src[it] += BK;                                                                    \
@@ -152,11 +212,17 @@ __global__ __launch_bounds__(NT) void gemm_nt_f32(GemmNT p, int tiles_m, int til
         ras[it] = ok ? val : 0.f;                                                         \
       }                                                                                   \
     }                                                                                     \
+  }                                                                                       \
   }
 #define CCT_NT_STORE(BUF)                                                                 \
   {                                                                                       \
-    _Pragma("unroll") for (int it = 0; it < BV_IT; ++it)                                  \
-      *reinterpret_cast<f32x4*>(&Bs[BUF][b_dst[it]]) = rb[it];                            \
+    if (BG) {                                                                             \
+      _Pragma("unroll") for (int it = 0; it < BS_IT; ++it)                                \
+        Bs[BUF][(as_r0 + it * AS_ROWS) * LDK + as_k] = rbs[it];                           \
+    } else {                                                                              \
+      _Pragma("unroll") for (int it = 0; it < BV_IT; ++it)                                \
+        *reinterpret_cast<f32x4*>(&Bs[BUF][b_dst[it]]) = rb[it];                          \
+    }                                                                                     \
     if (AVEC) {                                                                           \
       _Pragma("unroll") for (int it = 0; it < AV_IT; ++it)                                \
         *reinterpret_cast<f32x4*>(&As[BUF][av_dst[it]]) = rav[it];                        \
@@ -415,23 +481,46 @@ int launch_f32(const GemmNT& p, hipStream_t st) {
   const long long tiles = (long long)tiles_m * tiles_n;
   if (tiles <= 0 || p.S < 1 || tiles * p.S >= 2147483647LL || p.G > 65535) return CCT_EUNSUPPORTED;
   if (p.split_len % BK) return CCT_EINVAL;
+  dim3 grid((unsigned)(tiles * p.S), (unsigned)p.G);
+  char name[96];
+  NtGather ng;
+  memset(&ng, 0, sizeof(ng));
+  if (p.gather) {
+    // fused lowering: dy in place, x gathered; 32-bit byte offsets from the tile's first image
+    const long long P = (long long)p.gHout * p.gWout;
+    const long long T = (BK - 1) / P + 2;   // images a tile of BK positions can span
+    if (p.amap.P != P || p.a_ms != P || p.gK < 1 ||
+        (T + 1) * p.amap.img_stride >= (1LL << 29) ||
+        (T + 1) * (long long)p.gC * p.gH * p.gW >= (1LL << 29))
+      return CCT_EUNSUPPORTED;
+    make_fastdiv_parts((int)P, &ng.mP, &ng.sP);
+    make_fastdiv_parts(p.gWout, &ng.mWout, &ng.sWout);
+    make_fastdiv_parts(p.gK * p.gK, &ng.mKK, &ng.sKK);
+    make_fastdiv_parts(p.gK, &ng.mK, &ng.sK);
+    snprintf(name, sizeof(name), "gemm_nt_f32<%d, %d, %d, %d, %d, gather>", BM, BN, BK, WM, WN);
+    const double x_bytes = 4.0 * ((double)p.Ncols / P) * p.gC * p.gH * p.gW;
+    ProfScope ps(name, 2.0 * p.M * p.N * p.Ncols * p.G,
+                 x_bytes + 4.0 * ((double)p.M * p.Ncols + (double)p.M * p.N * p.S) * p.G, st);
+    hipLaunchKernelGGL((gemm_nt_f32<BM, BN, BK, WM, WN, false, true>), grid, dim3(NT), 0, st, p, ng,
+                       tiles_m, tiles_n);
+    CCT_CHECK_LAUNCH();
+    return CCT_OK;
+  }
   // B must be a plain lowered matrix with 16-byte aligned rows (the lowering kernels write it so)
   if (p.b_ns % 4 || p.b_gs % 4 || reinterpret_cast<uintptr_t>(p.B) % 16) return CCT_EINVAL;
   const bool avec = p.amap.P == 2147483647 && p.a_ms % 4 == 0 && p.a_gs % 4 == 0 &&
                     reinterpret_cast<uintptr_t>(p.A) % 16 == 0;
-  dim3 grid((unsigned)(tiles * p.S), (unsigned)p.G);
-  char name[96];
   snprintf(name, sizeof(name), "gemm_nt_f32<%d, %d, %d, %d, %d, %s>", BM, BN, BK, WM, WN,
            avec ? "true" : "false");
   ProfScope ps(name, 2.0 * p.M * p.N * p.Ncols * p.G,
                4.0 * ((double)p.M * p.Ncols + (double)p.N * p.Ncols + (double)p.M * p.N * p.S) * p.G,
                st);
   if (avec)
-    hipLaunchKernelGGL((gemm_nt_f32<BM, BN, BK, WM, WN, true>), grid, dim3(NT), 0, st, p, tiles_m,
-                       tiles_n);
+    hipLaunchKernelGGL((gemm_nt_f32<BM, BN, BK, WM, WN, true, false>), grid, dim3(NT), 0, st, p, ng,
+                       tiles_m, tiles_n);
   else
-    hipLaunchKernelGGL((gemm_nt_f32<BM, BN, BK, WM, WN, false>), grid, dim3(NT), 0, st, p, tiles_m,
-                       tiles_n);
+    hipLaunchKernelGGL((gemm_nt_f32<BM, BN, BK, WM, WN, false, false>), grid, dim3(NT), 0, st, p,
+                       ng, tiles_m, tiles_n);
   CCT_CHECK_LAUNCH();
   return CCT_OK;
 }
@@ -449,9 +538,18 @@ void gemm_nt_tile(int M, int /*N*/, int* BM, int* BN, int* BK) {
     *BM = 128;
 }
 
+bool gemm_nt_gather_fits(int C, int H, int W, int O, int Hout, int Wout) {
+  int BM, BN, BK;
+  gemm_nt_tile(1, 1, &BM, &BN, &BK);
+  const long long P = (long long)Hout * Wout;
+  const long long T = (BK - 1) / P + 2;
+  return (T + 1) * O * P < (1LL << 29) && (T + 1) * (long long)C * H * W < (1LL << 29);
+}
+
 int launch_gemm_nt(const GemmNT& p, hipStream_t st) {
   int BM, BN, BK;
   gemm_nt_tile(p.M, p.N, &BM, &BN, &BK);
+  if (p.gather && p.bf16) return CCT_EUNSUPPORTED;
   if (p.bf16) {
     if (BM == 64) return launch_bf16<64, 128, 32, 1, 2>(p, st);
     if (BM == 96) return launch_bf16<96, 128, 32, 3, 1>(p, st);

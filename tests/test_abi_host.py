@@ -151,7 +151,8 @@ def test_selector_degenerate_and_strided_cases(B):
     assert B.cct_pick_lowering(d, B.PASS_FORWARD) == 1          # k = 1: all layouts coincide
     conv1 = B.make_desc(256, 3, 227, 227, 96, 11, 4, 0, 1)
     assert B.cct_pick_lowering(conv1, B.PASS_FORWARD) in (1, 4)  # stride 4: Types 2/3 waste s, s^2 work
-    assert B.cct_pick_lowering(conv1, B.PASS_BACKWARD_WEIGHTS) == 1
+    assert B.cct_pick_lowering(conv1, B.PASS_BACKWARD_WEIGHTS) in (1, 4)
+    assert B.cct_pick_lowering(conv1, B.PASS_BACKWARD_DATA) == 1   # no fused form at stride 4
     for p in (B.PASS_FORWARD, B.PASS_BACKWARD_DATA, B.PASS_BACKWARD_WEIGHTS):
         for L in __import__("paper_1504_04343_amd.synth", fromlist=["x"]).caffenet(256):
             dd = B.make_desc(L.N, L.C, L.H, L.W, L.O, L.K, L.stride, L.pad, L.groups)

@@ -138,9 +138,10 @@ def test_backward_data_matches_oracle(B, L, lowering):
     assert rel_err(got, want) <= TOL_F32
 
 
-# shapes whose backward-weights pass has no fused form: 1x1 kernels, and windows whose staged
-# input rows (the rows 32 consecutive positions can reach) exceed what the kernel stages in LDS
-FUSED_BWDW_UNSUPPORTED = {"k1", "tiny", "conv1_like", "stride3_g3", "single_pixel_out"}
+# The fused backward-weights pass stages the input rows of 32 positions in LDS; shapes where they
+# do not fit (and 1x1 kernels) gather the lowered rows inside the split-K GEMM instead, which needs
+# an unpadded layer.  A padded layer whose rows do not fit has no fused form.
+FUSED_BWDW_UNSUPPORTED = {"stride3_g3"}
 BWDW_EXTRA = [
     layer("many_images", 37, 20, 9, 7, 40, 3, 1, 1, 2),          # 2331 positions: several splits
     layer("tiny_planes", 50, 4, 4, 4, 5, 2, 1, 0, 1),            # 9 positions per image: a chunk spans 4 or 5 images
@@ -231,13 +232,14 @@ def test_unsupported_and_workspace_errors(B):
     assert e.value.code == B.EWORKSPACE
     with pytest.raises(ValueError):
         B.cct_conv_forward(d, dev(x)[:2], dev(w), dev(b), y, B.alloc_workspace(d, 0))
-    # there is no fused bf16 path, and no fused backward-weights pass for 1x1 kernels
+    # there is no fused bf16 path, and no fused backward-weights pass for a padded layer whose
+    # input rows do not fit in LDS
     df = desc_of(B, L, B.LOWER_FUSED, B.PREC_BF16_IN_F32_ACC)
     with pytest.raises(B.CctError) as e:
         B.cct_conv_workspace_bytes(df, B.PASS_FORWARD)
     assert e.value.code == B.EUNSUPPORTED
     with pytest.raises(B.CctError) as e:
-        B.cct_conv_workspace_bytes(desc_of(B, SMALL[7], B.LOWER_FUSED), B.PASS_BACKWARD_WEIGHTS)
+        B.cct_conv_workspace_bytes(desc_of(B, SMALL[9], B.LOWER_FUSED), B.PASS_BACKWARD_WEIGHTS)
     assert e.value.code == B.EUNSUPPORTED
     df = desc_of(B, L, B.LOWER_FUSED)
     with pytest.raises(B.CctError) as e:
