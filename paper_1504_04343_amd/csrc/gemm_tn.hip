@@ -29,7 +29,8 @@ constexpr int NT = 256;
 //          (ci, i, j) -> offset table of all K rows is built once per workgroup in LDS.
 // BMODE 3: same, but the taps are decoded arithmetically (for K too long for the LDS table).
 template <int BM, int BN, int BK, int WM, int WN, int BMODE>
-__global__ __launch_bounds__(NT) void gemm_tn_f32(GemmTN p, int tiles_m, int tiles_n) {
+__global__ __launch_bounds__(NT) void gemm_tn_f32(GemmTN p, int tiles_m, int tiles_n,
+                                                  int gather_fast) {
   constexpr bool BVEC = BMODE == 0;
   constexpr bool GATHER = BMODE >= 2;
   constexpr bool TAPS_LDS = BMODE == 2;
@@ -104,6 +105,8 @@ __global__ __launch_bounds__(NT) void gemm_tn_f32(GemmTN p, int tiles_m, int til
   bool bs_ok = false;
   int bs_k0 = 0, bs_n = 0;
   int g_hh = 0, g_ww = 0;  // gather: top-left tensor pixel of this thread's column
+  unsigned g_voff = 0;
+  const bool g_nopad = GATHER && gather_fast;
   if (!BVEC) {
     bs_n = tid % BN;
     bs_k0 = tid / BN;
@@ -117,6 +120,11 @@ __global__ __launch_bounds__(NT) void gemm_tn_f32(GemmTN p, int tiles_m, int til
       g_hh = r * p.gs - p.gp;
       g_ww = c * p.gs - p.gp;
       bs_src = (gptr_f32)(p.B) + (((long long)n * p.gC + (long long)g * p.gCg) * p.gH + g_hh) * p.gW + g_ww;
+      // unpadded layer: every tap of a valid position is inside the image, so the gather needs
+      // no bounds checks; the position then is a fixed 32-bit byte offset from the tensor's start
+      // (columns past the end get one that fails the buffer range check and load as zero)
+      g_voff = bs_ok ? (unsigned)((((long long)n * p.gC + (long long)g * p.gCg) * p.gH + g_hh) * p.gW + g_ww) * 4u
+                     : 0x80000000u;
     } else {
       bs_src = Bg + (bs_ok ? col_offset(p.bmap, col) : 0) + (long long)bs_k0 * p.b_ks;
     }
@@ -150,6 +158,14 @@ __global__ __launch_bounds__(NT) void gemm_tn_f32(GemmTN p, int tiles_m, int til
         if ((K0) + b_k[it] < p.Kdim) val = *(gptr_f32x4)(b_src[it]);                        \
         rbv[it] = val;                                                                      \
         b_src[it] += b_step;                                                                \
+      }                                                                                     \
+    } else if (TAPS_LDS && g_nopad) {                                                       \
+      const __amdgpu_buffer_rsrc_t rsx = __builtin_amdgcn_make_buffer_rsrc(                 \
+          const_cast<void*>(p.B), 0, 0x7fffffff, 0x00020000);                               \
+      _Pragma("unroll") for (int it = 0; it < B_SC_IT; ++it) {                              \
+        const int2 tp = tap_tab[(K0) + bs_k0 + it * B_KSTEP];                               \
+        rbs[it] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(           \
+                                                rsx, (int)(g_voff + (unsigned)tp.x * 4u), 0, 0)); \
       }                                                                                     \
     } else if (TAPS_LDS) {                                                                  \
       _Pragma("unroll") for (int it = 0; it < B_SC_IT; ++it) {                              \
@@ -449,6 +465,10 @@ int launch_f32(const GemmTN& p, hipStream_t st) {
   const size_t tab_bytes = (size_t)p.Kpad * sizeof(int2);
   const bool tab_ok = tab_bytes <= 24576 && p.gK < 32768;
   const int bmode = p.gather ? (tab_ok ? 2 : 3) : (vec ? 0 : 1);
+  // unpadded gather through buffer loads: the whole tensor within 2 GiB
+  const int gather_fast =
+      p.gather && p.gp == 0 &&
+      ((double)p.Ncols / (p.gHout * p.gWout)) * p.gC * p.gH * p.gW * 4.0 < 2147483648.0;
   snprintf(name, sizeof(name), "gemm_tn_f32<%d, %d, %d, %d, %d, %d>", BM, BN, BK, WM, WN, bmode);
   // algorithmic bytes: operands once + result once (fused lowering: the tensor x, not D^)
   const double b_bytes = p.gather ? 4.0 * ((double)p.Ncols / (p.gHout * p.gWout)) * p.gC * p.gH * p.gW
@@ -457,16 +477,16 @@ int launch_f32(const GemmTN& p, hipStream_t st) {
                b_bytes + 4.0 * ((double)p.M * p.Ncols + (double)p.M * p.Kdim) * p.G, st);
   if (bmode == 2)
     hipLaunchKernelGGL((gemm_tn_f32<BM, BN, BK, WM, WN, 2>), grid, dim3(NT), tab_bytes, st, p,
-                       tiles_m, tiles_n);
+                       tiles_m, tiles_n, gather_fast);
   else if (bmode == 3)
     hipLaunchKernelGGL((gemm_tn_f32<BM, BN, BK, WM, WN, 3>), grid, dim3(NT), 0, st, p, tiles_m,
-                       tiles_n);
+                       tiles_n, gather_fast);
   else if (bmode == 0)
     hipLaunchKernelGGL((gemm_tn_f32<BM, BN, BK, WM, WN, 0>), grid, dim3(NT), 0, st, p, tiles_m,
-                       tiles_n);
+                       tiles_n, gather_fast);
   else
     hipLaunchKernelGGL((gemm_tn_f32<BM, BN, BK, WM, WN, 1>), grid, dim3(NT), 0, st, p, tiles_m,
-                       tiles_n);
+                       tiles_n, gather_fast);
   CCT_CHECK_LAUNCH();
   return CCT_OK;
 }
