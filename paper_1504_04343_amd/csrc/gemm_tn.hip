@@ -29,8 +29,7 @@ constexpr int NT = 256;
 //          (ci, i, j) -> offset table of all K rows is built once per workgroup in LDS.
 // BMODE 3: same, but the taps are decoded arithmetically (for K too long for the LDS table).
 template <int BM, int BN, int BK, int WM, int WN, int BMODE>
-__global__ __launch_bounds__(NT) void gemm_tn_f32(GemmTN p, int tiles_m, int tiles_n,
-                                                  int gather_fast) {
+__global__ __launch_bounds__(NT) void gemm_tn_f32(GemmTN p, int tiles_m, int tiles_n, int fast) {
   constexpr bool BVEC = BMODE == 0;
   constexpr bool GATHER = BMODE >= 2;
   constexpr bool TAPS_LDS = BMODE == 2;
@@ -105,8 +104,9 @@ __global__ __launch_bounds__(NT) void gemm_tn_f32(GemmTN p, int tiles_m, int til
   bool bs_ok = false;
   int bs_k0 = 0, bs_n = 0;
   int g_hh = 0, g_ww = 0;  // gather: top-left tensor pixel of this thread's column
-  unsigned g_voff = 0;
-  const bool g_nopad = GATHER && gather_fast;
+  unsigned g_voff = 0, b_voff = 0;
+  const bool g_nopad = GATHER && (fast & 1);
+  const bool b_fast = BMODE == 1 && (fast & 2);
   if (!BVEC) {
     bs_n = tid % BN;
     bs_k0 = tid / BN;
@@ -127,6 +127,8 @@ __global__ __launch_bounds__(NT) void gemm_tn_f32(GemmTN p, int tiles_m, int til
                      : 0x80000000u;
     } else {
       bs_src = Bg + (bs_ok ? col_offset(p.bmap, col) : 0) + (long long)bs_k0 * p.b_ks;
+      b_voff = bs_ok ? (unsigned)(col_offset(p.bmap, col) + (long long)bs_k0 * p.b_ks) * 4u
+                     : 0x80000000u;
     }
   }
 
@@ -189,6 +191,18 @@ __global__ __launch_bounds__(NT) void gemm_tn_f32(GemmTN p, int tiles_m, int til
             (unsigned)(g_ww + tj) < (unsigned)p.gW)                                         \
           val = bs_src[(ci * p.gH + ti) * p.gW + tj];                                       \
         rbs[it] = val;                                                                      \
+      }                                                                                     \
+    } else if (b_fast) {                                                                    \
+      /* column map within 2 GiB: fixed byte offset per thread, the K row in the scalar     \
+         offset (rows of the zero-padded K tail re-read the last rows: A is zero there) */  \
+      const __amdgpu_buffer_rsrc_t rsb = __builtin_amdgcn_make_buffer_rsrc(                 \
+          const_cast<float*>(reinterpret_cast<const float*>(p.B) + (long long)g * p.b_gs),  \
+          0, 0x7fffffff, 0x00020000);                                                       \
+      _Pragma("unroll") for (int it = 0; it < B_SC_IT; ++it) {                              \
+        const int kk = min((K0) + it * B_KSTEP, p.Kdim - B_KSTEP);                          \
+        rbs[it] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(           \
+                                                rsb, (int)b_voff,                           \
+                                                (int)((unsigned)kk * (unsigned)p.b_ks * 4u), 0)); \
       }                                                                                     \
     } else {                                                                                \
       _Pragma("unroll") for (int it = 0; it < B_SC_IT; ++it) {                              \
@@ -291,20 +305,26 @@ __global__ __launch_bounds__(NT) void gemm_tn_f32(GemmTN p, int tiles_m, int til
   // column l%32 and rows 8*(r/4) + 4*(l/32) + r%4 for r = 0..15.
   float* __restrict__ C = p.C + (long long)g * p.c_gs;
   const float* bias = p.bias ? p.bias + (long long)g * p.bias_gs : nullptr;
+  // A lane's column and its lane half's 4 rows give one 64-bit base per column block; the row
+  // of each accumulator register is a uniform multiple of the row stride on top of it.  Tiles that
+  // lie completely inside M (all but the last row of tiles) need no per-lane row check.
+  const int mw = m0 + wave_m * WM * 32;
+  const bool full_m = m0 + BM <= p.M;
 #pragma unroll
   for (int j = 0; j < WN; ++j) {
     const int col = n0 + bn + j * 32;
     if (col >= p.Ncols) continue;
-    const long long coff = col_offset(p.cmap, col);
+    float* __restrict__ cl = C + col_offset(p.cmap, col) + (long long)(mw + lane_hi * 4) * p.c_ms;
+    const float* bl = bias ? bias + mw + lane_hi * 4 : nullptr;
 #pragma unroll
     for (int i = 0; i < WM; ++i) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int m = m0 + wave_m * WM * 32 + i * 32 + (r >> 2) * 8 + lane_hi * 4 + (r & 3);
-        if (m < p.M) {
+        const int row = i * 32 + (r >> 2) * 8 + (r & 3);   // relative to mw + 4*lane_hi
+        if (full_m || mw + row + lane_hi * 4 < p.M) {
           float v = acc[i][j][r];
-          if (bias) v += bias[m];
-          C[(long long)m * p.c_ms + coff] = v;
+          if (bl) v += bl[row];
+          cl[(long long)row * p.c_ms] = v;
         }
       }
     }
@@ -428,20 +448,26 @@ __global__ __launch_bounds__(NT) void gemm_tn_bf16(GemmTN p, int tiles_m, int ti
 
   float* __restrict__ C = p.C + (long long)g * p.c_gs;
   const float* bias = p.bias ? p.bias + (long long)g * p.bias_gs : nullptr;
+  // A lane's column and its lane half's 4 rows give one 64-bit base per column block; the row
+  // of each accumulator register is a uniform multiple of the row stride on top of it.  Tiles that
+  // lie completely inside M (all but the last row of tiles) need no per-lane row check.
+  const int mw = m0 + wave_m * WM * 32;
+  const bool full_m = m0 + BM <= p.M;
 #pragma unroll
   for (int j = 0; j < WN; ++j) {
     const int col = n0 + bn + j * 32;
     if (col >= p.Ncols) continue;
-    const long long coff = col_offset(p.cmap, col);
+    float* __restrict__ cl = C + col_offset(p.cmap, col) + (long long)(mw + lane_hi * 4) * p.c_ms;
+    const float* bl = bias ? bias + mw + lane_hi * 4 : nullptr;
 #pragma unroll
     for (int i = 0; i < WM; ++i) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int m = m0 + wave_m * WM * 32 + i * 32 + (r >> 2) * 8 + lane_hi * 4 + (r & 3);
-        if (m < p.M) {
+        const int row = i * 32 + (r >> 2) * 8 + (r & 3);   // relative to mw + 4*lane_hi
+        if (full_m || mw + row + lane_hi * 4 < p.M) {
           float v = acc[i][j][r];
-          if (bias) v += bias[m];
-          C[(long long)m * p.c_ms + coff] = v;
+          if (bl) v += bl[row];
+          cl[(long long)row * p.c_ms] = v;
         }
       }
     }
@@ -466,9 +492,16 @@ int launch_f32(const GemmTN& p, hipStream_t st) {
   const bool tab_ok = tab_bytes <= 24576 && p.gK < 32768;
   const int bmode = p.gather ? (tab_ok ? 2 : 3) : (vec ? 0 : 1);
   // unpadded gather through buffer loads: the whole tensor within 2 GiB
-  const int gather_fast =
+  int gather_fast =
       p.gather && p.gp == 0 &&
       ((double)p.Ncols / (p.gHout * p.gWout)) * p.gC * p.gH * p.gW * 4.0 < 2147483648.0;
+  // column-mapped B (a tensor read in place) through buffer loads: one group's operand within
+  // 2 GiB and an even number of K rows (two rows are loaded per instruction)
+  if (bmode == 1 && p.Kdim % 2 == 0 && p.Kdim >= 2) {
+    const long long max_col = (long long)((p.Ncols - 1) / p.bmap.P) * p.bmap.img_stride +
+                              (p.Ncols - 1) % p.bmap.P;
+    if ((max_col + (long long)(p.Kdim + 1) * p.b_ks) * 4 < (1LL << 31)) gather_fast |= 2;
+  }
   snprintf(name, sizeof(name), "gemm_tn_f32<%d, %d, %d, %d, %d, %d>", BM, BN, BK, WM, WN, bmode);
   // algorithmic bytes: operands once + result once (fused lowering: the tensor x, not D^)
   const double b_bytes = p.gather ? 4.0 * ((double)p.Ncols / (p.gHout * p.gWout)) * p.gC * p.gH * p.gW
