@@ -29,13 +29,24 @@ struct WinMap {
   int Ht, Wt;          // tensor plane size
 };
 
+// n / d == (n * M) >> sh for 0 <= n < 2^31
+inline void make_fastdiv_parts(int d, unsigned* M, int* sh) {
+  int s = 0;
+  while ((1LL << s) < d) ++s;
+  *sh = 31 + s;
+  *M = (unsigned)(((1ULL << *sh) + (unsigned long long)d - 1) / (unsigned long long)d);
+}
+
 // Column -> memory offset map used by the GEMM kernels so that they can read and write
 // NCHW tensors in place: off(col) = (col / P) * img_stride + (col % P).
 // A plain matrix row uses P = INT32_MAX, img_stride = 0.
 struct ColMap {
   int P;
   long long img_stride;
+  unsigned divM;  // col / P == (col * divM) >> divsh; filled by the GEMM launchers (colmap_prepare)
+  int divsh;
 };
+inline void colmap_prepare(ColMap* c) { make_fastdiv_parts(c->P, &c->divM, &c->divsh); }
 
 // C[m][col] = sum_k Apack[k][m] * B(k, col) (+ bias[m]); one launch covers all groups.
 struct GemmTN {
@@ -62,14 +73,6 @@ struct GemmTN {
   unsigned g_divKK_M, g_divK_M;  // fast division by K*K and by K
   int g_divKK_sh, g_divK_sh;
 };
-// n / d == (n * M) >> sh for 0 <= n < 2^31
-inline void make_fastdiv_parts(int d, unsigned* M, int* sh) {
-  int s = 0;
-  while ((1LL << s) < d) ++s;
-  *sh = 31 + s;
-  *M = (unsigned)(((1ULL << *sh) + (unsigned long long)d - 1) / (unsigned long long)d);
-}
-
 // Cpart[s][g][m][n] = sum_{col in split s} A(m, col) * B(n, col); both operands col-contiguous.
 struct GemmNT {
   const void* A;       // rows m: a_ms apart, groups a_gs apart, columns through amap

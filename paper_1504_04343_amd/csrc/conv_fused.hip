@@ -386,7 +386,10 @@ int launch_variant(const GemmTN& p, const FusedGeom& fg, bool ring, size_t lds, 
 
 // Returns CCT_EUNSUPPORTED (nothing launched) when the shape does not fit this kernel's LDS
 // staging; the caller then uses the gather-fed GEMM.
-int launch_conv_fused(const GemmTN& p, hipStream_t st) {
+int launch_conv_fused(const GemmTN& p0, hipStream_t st) {
+  GemmTN p = p0;
+  colmap_prepare(&p.bmap);
+  colmap_prepare(&p.cmap);
   if (!p.gather || p.bf16 || p.gK < 2) return CCT_EUNSUPPORTED;
   int BM, BNt, BKt;
   gemm_tn_tile(p.M, p.Ncols, &BM, &BNt, &BKt);

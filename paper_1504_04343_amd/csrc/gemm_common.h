@@ -19,7 +19,7 @@ __device__ __forceinline__ int fdiv_u(int n, unsigned M, int sh) {
 }
 
 __device__ __forceinline__ long long col_offset(const ColMap& cm, int col) {
-  const int n = col / cm.P;
+  const int n = fdiv_u(col, cm.divM, cm.divsh);
   return (long long)n * cm.img_stride + (col - n * cm.P);
 }
 

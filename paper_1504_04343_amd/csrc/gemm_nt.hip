@@ -546,7 +546,9 @@ bool gemm_nt_gather_fits(int C, int H, int W, int O, int Hout, int Wout) {
   return (T + 1) * O * P < (1LL << 29) && (T + 1) * (long long)C * H * W < (1LL << 29);
 }
 
-int launch_gemm_nt(const GemmNT& p, hipStream_t st) {
+int launch_gemm_nt(const GemmNT& p0, hipStream_t st) {
+  GemmNT p = p0;
+  colmap_prepare(&p.amap);
   int BM, BN, BK;
   gemm_nt_tile(p.M, p.N, &BM, &BN, &BK);
   if (p.gather && p.bf16) return CCT_EUNSUPPORTED;

@@ -560,7 +560,10 @@ void gemm_tn_tile(int M, int /*Ncols*/, int* BM, int* BN, int* BK) {
     *BM = 128;
 }
 
-int launch_gemm_tn(const GemmTN& p, hipStream_t st) {
+int launch_gemm_tn(const GemmTN& p0, hipStream_t st) {
+  GemmTN p = p0;
+  colmap_prepare(&p.bmap);
+  colmap_prepare(&p.cmap);
   int BM, BN, BK;
   gemm_tn_tile(p.M, p.Ncols, &BM, &BN, &BK);
   if (p.Mpad % BM || p.Kpad % BK || p.Mpad < p.M || p.Kpad < p.Kdim) return CCT_EINVAL;
