@@ -87,6 +87,7 @@ struct Layout {
   long long ld = 0;
   int Mpad = 0, Kpad = 0;  // pack padding (TN GEMM)
   int S = 1, split_len = 0;  // NT GEMM
+  int t2_opad = 0;  // Type-2 backward-data with the inverse lifting gathered by the GEMM: padded Og
 };
 
 constexpr int kDbiasBlocks = 64;
@@ -130,8 +131,16 @@ bool make_layout(const cct_conv_desc_t& d, int pass, int type, const Geom& g, lo
     gemm_tn_tile(g.Kd, (int)ncols, &BM, &BN, &BK);
     L->Mpad = (int)align_up(g.Kd, BM);
     L->Kpad = (int)align_up(g.Mr, BK);
+    // Type 2 at stride 1 in fp32: dR^T is never built, the GEMM gathers it from dy (K vertical
+    // taps per kernel) when dy can be addressed with 32-bit byte offsets
+    if (type == CCT_LOWER_TYPE2 && es == 4 && d.stride == 1 && d.K <= 64 &&
+        nc * d.O * g.Hout * g.Wout < (1LL << 29)) {
+      L->t2_opad = (int)align_up(g.Og, BK);
+      L->Kpad = d.K * L->t2_opad;
+    }
     take((long long)d.groups * L->Mpad * L->Kpad * es, &L->pack_off, &L->pack_bytes);
-    if (type != CCT_LOWER_TYPE1 || es == 2) take(rt_rows * L->ld * es, &L->rt_off, &L->rt_bytes);
+    if ((type != CCT_LOWER_TYPE1 || es == 2) && !L->t2_opad)
+      take(rt_rows * L->ld * es, &L->rt_off, &L->rt_bytes);
     if (type != CCT_LOWER_TYPE3) take(dt_rows * L->ld * 4, &L->dt_off, &L->dt_bytes);
   } else {
     int BM, BN, BK;
@@ -193,7 +202,7 @@ constexpr double kStreamBytesPerSec = 4.0e12;   // index-map kernels (lower, lif
 constexpr double kGemmBytesPerSec = 5.0e12;     // operand / result streaming inside a GEMM
 constexpr double kGemmFlopsPerSec = 110.0e12;
 constexpr double kLaunchSec = 4.0e-6;
-constexpr double kFusedGemmFactor = 0.9;  // fused kernels vs the GEMM on a materialised matrix
+constexpr double kFusedGemmFactor = 0.95; // fused kernels vs the GEMM on a materialised matrix
 
 // time = sum over index-map kernels of bytes / stream rate
 //      + max(GEMM flops / MFMA rate, GEMM bytes / GEMM stream rate)     (loads overlap the MFMAs)
@@ -241,8 +250,8 @@ double model_cost(const cct_conv_desc_t& d, int pass, int type) {
     const double util = g.Cg / (std::ceil(g.Cg / mt) * mt);  // tiles of 64 / 96 / 128 rows
     rate *= kFusedGemmFactor * util * fill(g.Cg, pos);
   } else if (pass == CCT_PASS_BACKWARD_DATA) {
-    if (type == CCT_LOWER_TYPE1) {
-      gemm_bytes += y_bytes;                     // GEMM reads dy in place
+    if (type == CCT_LOWER_TYPE1 || (type == CCT_LOWER_TYPE2 && d.stride == 1 && es == 4.0)) {
+      gemm_bytes += y_bytes;                     // GEMM reads (Type 2: gathers) dy in place
     } else {
       index_bytes += y_bytes + rt_elems * es;    // inverse lifting writes dR^T
       gemm_bytes += rt_elems * es;               // GEMM reads it
@@ -586,7 +595,11 @@ int cct_conv_backward_data(const cct_conv_desc_t* desc, const float* w, const fl
     if (rc == CCT_EUNSUPPORTED) rc = launch_gemm_tn(p, st);
     return rc;
   }
-  rc = launch_pack_kernel_matrix(w, ws + L.pack_off, make_pack(d, g, L, 1), st);
+  if (L.t2_opad)
+    rc = launch_pack_type2_bwd(w, reinterpret_cast<float*>(ws + L.pack_off), d.groups, g.Og, g.Cg,
+                               d.K, L.t2_opad, L.Mpad, st);
+  else
+    rc = launch_pack_kernel_matrix(w, ws + L.pack_off, make_pack(d, g, L, 1), st);
   if (rc) return rc;
   for (long long n0 = 0; n0 < d.N; n0 += nc) {
     const int ni = (int)std::min<long long>(nc, d.N - n0);
@@ -599,7 +612,20 @@ int cct_conv_backward_data(const cct_conv_desc_t* desc, const float* w, const fl
     p.a_gs = (long long)L.Mpad * L.Kpad;
     p.Mpad = L.Mpad; p.Kpad = L.Kpad;
     p.M = g.Kd; p.Ncols = (int)ncols; p.Kdim = g.Mr; p.G = d.groups; p.bf16 = bf16;
-    if (L.rt_bytes) {
+    if (L.t2_opad) {
+      // Type 2, stride 1: dR^T[(o,i)][(n,a,b)] = dy[n,o,a+p-i,b] gathered by the GEMM, rows
+      // ordered (K-1-i, o): a convolution-like gather with K vertical taps, pad K-1-p
+      p.B = dyc;
+      p.bmap = ColMap{1, 0};
+      p.gather = 1; p.tapmajor = 1;
+      p.gC = d.O; p.gCg = g.Og; p.gH = g.Hout; p.gW = g.Wout;
+      p.gHout = d.H; p.gWout = g.Wout;   // the grid of D^ columns: every input row, output columns
+      p.gs = 1; p.gK = d.K; p.gKK = d.K * d.K;
+      p.tKi = d.K; p.tKj = 1; p.tph = d.K - 1 - d.pad; p.tpw = 0;
+      p.gCpad = L.t2_opad;
+      make_fastdiv_parts(p.gCpad, &p.g_divKK_M, &p.g_divKK_sh);
+      p.Kdim = L.Kpad;
+    } else if (L.rt_bytes) {
       // inverse lifting: spread dy over the rows of dR^T (a copy for Type 1 in bf16 mode)
       rc = launch_inv_lift(dyc, ws + L.rt_off, L.ld, ni, d.O, g.lift, bf16, st);
       if (rc) return rc;

@@ -70,6 +70,10 @@ struct GemmTN {
   // (ci, i, j) decoded from k = (ci*K + i)*K + j and (n, r, c) from col.
   int gather;
   int gC, gH, gW, gHout, gWout, gs, gp, gCg, gK, gKK;
+  // tapmajor != 0 (with gather): rows are ordered k = tap*gCpad + channel, gCpad a multiple of the
+  // K tile, taps on a tKi x tKj grid with pads tph / tpw and stride 1; g_divKK_* divide by gCpad;
+  // the gathered tensor must lie within 2 GiB.
+  int tapmajor, gCpad, tKi, tKj, tph, tpw;
   unsigned g_divKK_M, g_divK_M;  // fast division by K*K and by K
   int g_divKK_sh, g_divK_sh;
 };
@@ -147,6 +151,10 @@ int launch_pack_kernel_matrix(const float* w, void* pack, const PackDesc& d, hip
 // pack[q][(oo,i',j')][ci] = w[q*Og+oo, ci, K-1-i', K-1-j'] (fp32), zero padded to Kpad x Mpad.
 int launch_pack_flipped(const float* w, float* pack, int G, int Og, int Cg, int K, int Mpad,
                         int Kpad, hipStream_t st);
+// Kernel matrix of the Type-2 backward-data pass with the inverse lifting done as a gather:
+// pack[q][k = i'*Opad + oo][m = (ci, j)] = w[q*Og + oo, ci, K-1-i', j], zero padded.
+int launch_pack_type2_bwd(const float* w, float* pack, int G, int Og, int Cg, int K, int Opad,
+                          int Mpad, hipStream_t st);
 // dw[o,ci,i,j] = (accumulate ? dw : 0) + sum_s part[s][q][rho][delta]
 int launch_reduce_dw(const float* part, float* dw, int S, const PackDesc& d, int accumulate,
                      hipStream_t st);

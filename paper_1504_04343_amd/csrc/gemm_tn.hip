@@ -28,11 +28,20 @@ constexpr int NT = 256;
 // BMODE 2: fused lowering, B tiles are gathered from x (see GemmTN::gather), 4-byte loads; the
 //          (ci, i, j) -> offset table of all K rows is built once per workgroup in LDS.
 // BMODE 3: same, but the taps are decoded arithmetically (for K too long for the LDS table).
+// BMODE 4: gather with the K dimension ordered tap-major, k = tap*Cpad + channel with Cpad a
+// multiple of BK and taps on a tKi x tKj grid (pads tph, tpw, stride 1): all rows of a K tile share
+// one tap, so a thread (which owns one position) needs one byte offset per tap - position + tap,
+// or an offset the buffer range check rejects when the tap falls into the padding - kept in an
+// LDS table [tap][position of the tile]; the channel of each row enters through the scalar offset
+// of the buffer load.  A tile's gather then costs no vector-ALU work at all.  Used for the
+// inverse lifting of the Type-2 backward-data pass: dR^[(o,i)][(n,a,b)] = dy[n,o,a+p-i,b] is a
+// gather from dy with K vertical taps.
 template <int BM, int BN, int BK, int WM, int WN, int BMODE>
 __global__ __launch_bounds__(NT) void gemm_tn_f32(GemmTN p, int tiles_m, int tiles_n, int fast) {
   constexpr bool BVEC = BMODE == 0;
   constexpr bool GATHER = BMODE >= 2;
   constexpr bool TAPS_LDS = BMODE == 2;
+  constexpr bool TAPMAJOR = BMODE == 4;
   extern __shared__ int2 tap_tab[];  // BMODE 2: {(ci*H + i)*W + j, (i << 16) | j} per row k
   constexpr int WAVES_N = BN / (32 * WN);
   constexpr int WAVES_M = BM / (32 * WM);
@@ -117,8 +126,8 @@ __global__ __launch_bounds__(NT) void gemm_tn_f32(GemmTN p, int tiles_m, int til
       const int cc = bs_ok ? col : 0;
       const int n = cc / P, pix = cc - n * P;
       const int r = pix / p.gWout, c = pix - r * p.gWout;
-      g_hh = r * p.gs - p.gp;
-      g_ww = c * p.gs - p.gp;
+      g_hh = r * p.gs - (TAPMAJOR ? p.tph : p.gp);
+      g_ww = c * p.gs - (TAPMAJOR ? p.tpw : p.gp);
       bs_src = (gptr_f32)(p.B) + (((long long)n * p.gC + (long long)g * p.gCg) * p.gH + g_hh) * p.gW + g_ww;
       // unpadded layer: every tap of a valid position is inside the image, so the gather needs
       // no bounds checks; the position then is a fixed 32-bit byte offset from the tensor's start
@@ -132,6 +141,22 @@ __global__ __launch_bounds__(NT) void gemm_tn_f32(GemmTN p, int tiles_m, int til
     }
   }
 
+  unsigned* tap_voff = reinterpret_cast<unsigned*>(tap_tab);  // BMODE 4: [tap][BN positions]
+  if (TAPMAJOR) {
+    // the two threads that share a position (bs_k0 = 0, 1) fill alternate taps
+    const long long chan0 = (long long)g * p.gCg * p.gH * p.gW;  // the group's first channel
+    const int P = p.gHout * p.gWout;
+    const int cc = bs_ok ? n0 + bs_n : 0;
+    const long long img = (long long)(cc / P) * p.gC * p.gH * p.gW;
+    for (int t = bs_k0; t < p.tKi * p.tKj; t += NT / BN) {
+      const int ti = t / p.tKj, tj = t - ti * p.tKj;
+      const int h = g_hh + ti, w = g_ww + tj;
+      const bool ok = bs_ok && (unsigned)h < (unsigned)p.gH && (unsigned)w < (unsigned)p.gW;
+      tap_voff[t * BN + bs_n] =
+          ok ? (unsigned)(img + chan0 + (long long)h * p.gW + w) * 4u : 0x80000000u;
+    }
+    __syncthreads();
+  }
   if (TAPS_LDS) {
     for (int k = tid; k < p.Kpad; k += NT) {
       const int ci = k / p.gKK, rem = k - ci * p.gKK;
@@ -160,6 +185,19 @@ __global__ __launch_bounds__(NT) void gemm_tn_f32(GemmTN p, int tiles_m, int til
         if ((K0) + b_k[it] < p.Kdim) val = *(gptr_f32x4)(b_src[it]);                        \
         rbv[it] = val;                                                                      \
         b_src[it] += b_step;                                                                \
+      }                                                                                     \
+    } else if (TAPMAJOR) {                                                                  \
+      const int k0_ = (K0);                                                                 \
+      const int t_ = fdiv_u(k0_, p.g_divKK_M, p.g_divKK_sh);  /* divides by gCpad here */    \
+      const int c0_ = k0_ - t_ * p.gCpad + __builtin_amdgcn_readfirstlane(bs_k0);           \
+      const unsigned vo = tap_voff[t_ * BN + bs_n];                                         \
+      const __amdgpu_buffer_rsrc_t rsx = __builtin_amdgcn_make_buffer_rsrc(                 \
+          const_cast<void*>(p.B), 0, 0x7fffffff, 0x00020000);                               \
+      _Pragma("unroll") for (int it = 0; it < B_SC_IT; ++it) {                              \
+        const int ci = min(c0_ + it * B_KSTEP, p.gCg - 1);  /* padded rows: A is zero */     \
+        rbs[it] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(           \
+                                                rsx, (int)vo,                               \
+                                                (int)((unsigned)ci * (unsigned)(p.gH * p.gW) * 4u), 0)); \
       }                                                                                     \
     } else if (TAPS_LDS && g_nopad) {                                                       \
       const __amdgpu_buffer_rsrc_t rsx = __builtin_amdgcn_make_buffer_rsrc(                 \
@@ -490,7 +528,7 @@ int launch_f32(const GemmTN& p, hipStream_t st) {
   // fused lowering: tap table in LDS when it fits 24 KiB (and the kernel size fits 15 bits)
   const size_t tab_bytes = (size_t)p.Kpad * sizeof(int2);
   const bool tab_ok = tab_bytes <= 24576 && p.gK < 32768;
-  const int bmode = p.gather ? (tab_ok ? 2 : 3) : (vec ? 0 : 1);
+  const int bmode = p.gather ? (p.tapmajor ? 4 : (tab_ok ? 2 : 3)) : (vec ? 0 : 1);
   // unpadded gather through buffer loads: the whole tensor within 2 GiB
   int gather_fast =
       p.gather && p.gp == 0 &&
@@ -508,7 +546,14 @@ int launch_f32(const GemmTN& p, hipStream_t st) {
                                   : 4.0 * (double)p.Kdim * p.Ncols * p.G;
   ProfScope ps(name, 2.0 * p.M * p.Ncols * p.Kdim * p.G,
                b_bytes + 4.0 * ((double)p.M * p.Ncols + (double)p.M * p.Kdim) * p.G, st);
-  if (bmode == 2)
+  if (bmode == 4) {
+    const long long taps = (long long)p.tKi * p.tKj;
+    if (p.gCpad % BK || p.Kpad != taps * p.gCpad || taps * BN * 4 > 32768 || p.gs != 1 ||
+        ((double)p.Ncols / (p.gHout * p.gWout)) * p.gC * p.gH * p.gW * 4.0 >= 2147483648.0)
+      return CCT_EINVAL;
+    hipLaunchKernelGGL((gemm_tn_f32<BM, BN, BK, WM, WN, 4>), grid, dim3(NT),
+                       (size_t)taps * BN * sizeof(unsigned), st, p, tiles_m, tiles_n, gather_fast);
+  } else if (bmode == 2)
     hipLaunchKernelGGL((gemm_tn_f32<BM, BN, BK, WM, WN, 2>), grid, dim3(NT), tab_bytes, st, p,
                        tiles_m, tiles_n, gather_fast);
   else if (bmode == 3)

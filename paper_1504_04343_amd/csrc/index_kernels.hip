@@ -63,6 +63,26 @@ __global__ __launch_bounds__(TPB) void pack_flipped_kernel(const float* __restri
   pack[t] = v;
 }
 
+// Kernel matrix of the Type-2 backward-data pass when the GEMM gathers dR^ from dy itself:
+// rows k = i'*Opad + oo (vertical tap i' = K-1-i first, so that a K tile has one tap), columns
+// m = ci*K + j.
+__global__ __launch_bounds__(TPB) void pack_type2_bwd_kernel(const float* __restrict__ w,
+                                                             float* __restrict__ pack, int G, int Og,
+                                                             int Cg, int K, int Opad, int Mpad) {
+  const long long per_group = (long long)Mpad * K * Opad;
+  const long long t = (long long)blockIdx.x * TPB + threadIdx.x;
+  if (t >= per_group * G) return;
+  const int q = (int)(t / per_group);
+  const long long e = t - q * per_group;
+  const int k = (int)(e / Mpad), m = (int)(e % Mpad);
+  const int ip = k / Opad, oo = k - ip * Opad;
+  const int ci = m / K, j = m - ci * K;
+  float v = 0.0f;
+  if (oo < Og && ci < Cg)
+    v = w[((((long long)q * Og + oo) * Cg + ci) * K + (K - 1 - ip)) * K + j];
+  pack[t] = v;
+}
+
 // dw = sum over split-K partials, mapped back to O x Cg x K x K.  A workgroup owns 64 outputs;
 // its 4 thread groups each add up a quarter of the splits (in split order), and the four
 // quarter sums are combined in a fixed order: the result is bit-reproducible run to run.
@@ -174,6 +194,18 @@ int launch_pack_flipped(const float* w, float* pack, int G, int Og, int Cg, int 
   ProfScope ps("pack_flipped_kernel", 0.0, 4.0 * G * Og * Cg * K * K + 4.0 * total, st);
   hipLaunchKernelGGL(pack_flipped_kernel, dim3((unsigned)blocks), dim3(TPB), 0, st, w, pack, G, Og,
                      Cg, K, Mpad, Kpad);
+  CCT_CHECK_LAUNCH();
+  return CCT_OK;
+}
+
+int launch_pack_type2_bwd(const float* w, float* pack, int G, int Og, int Cg, int K, int Opad,
+                          int Mpad, hipStream_t st) {
+  const long long total = (long long)Mpad * K * Opad * G;
+  const long long blocks = (total + TPB - 1) / TPB;
+  if (!grid_ok(blocks)) return CCT_EUNSUPPORTED;
+  ProfScope ps("pack_type2_bwd_kernel", 0.0, 4.0 * G * Og * Cg * K * K + 4.0 * total, st);
+  hipLaunchKernelGGL(pack_type2_bwd_kernel, dim3((unsigned)blocks), dim3(TPB), 0, st, w, pack, G, Og,
+                     Cg, K, Opad, Mpad);
   CCT_CHECK_LAUNCH();
   return CCT_OK;
 }
