@@ -178,6 +178,17 @@ def test_backward_chunked_batch(B, chunk):
         assert rel_err(dw, dw_want) <= TOL_F32 and rel_err(db, db_want) <= TOL_F32, lowering
 
 
+@pytest.mark.parametrize("chunk", [1, 3])
+def test_backward_data_type2_gather_chunked(B, chunk):
+    """Type 2 at stride 1 gathers dR^ from dy inside the GEMM; chunks must not change the bits."""
+    L = layer("chunked_s1", 7, 6, 15, 15, 10, 3, 1, 1, 2)
+    _, w, _, dy = inputs(L, 5)
+    want = oracle.conv_backward_data(odims(oracle, L), w, dy)
+    got = gpu_backward_data(B, L, w, dy, 2, chunk=chunk)
+    assert rel_err(got, want) <= TOL_F32
+    assert np.array_equal(got, gpu_backward_data(B, L, w, dy, 2))
+
+
 def test_backward_weights_without_dbias_and_deterministic(B):
     L = SMALL[4]
     x, _, _, dy = inputs(L)
