@@ -133,7 +133,7 @@ bool make_layout(const cct_conv_desc_t& d, int pass, int type, const Geom& g, lo
     L->Kpad = (int)align_up(g.Mr, BK);
     // Type 2 at stride 1 in fp32: dR^T is never built, the GEMM gathers it from dy (K vertical
     // taps per kernel) when dy can be addressed with 32-bit byte offsets
-    if (type == CCT_LOWER_TYPE2 && es == 4 && d.stride == 1 && d.K <= 64 &&
+    if (type == CCT_LOWER_TYPE2 && es == 4 && d.stride == 1 && d.K > 1 && d.K <= 64 &&
         nc * d.O * g.Hout * g.Wout < (1LL << 29)) {
       L->t2_opad = (int)align_up(g.Og, BK);
       L->Kpad = d.K * L->t2_opad;
@@ -515,19 +515,30 @@ int cct_conv_forward(const cct_conv_desc_t* desc, const float* x, const float* w
       if (rc) return rc;
       continue;
     }
-    rc = launch_lower(xc, ws + L.dt_off, L.ld, ni, d.C, g.lower, bf16, st);
-    if (rc) return rc;
+    // 1x1 kernel, stride 1, no padding: all three lowerings are the identity (D^ = x, R^ = y as
+    // matrices), so the GEMM reads x and writes y in place through column maps
+    const bool ident = d.K == 1 && d.stride == 1 && d.pad == 0 && !bf16;
     GemmTN p;
     std::memset(&p, 0, sizeof(p));
     p.A = ws + L.pack_off;
     p.a_gs = (long long)L.Mpad * L.Kpad;
     p.Mpad = L.Mpad; p.Kpad = L.Kpad;
-    p.B = ws + L.dt_off;
-    p.b_ks = L.ld; p.b_gs = (long long)g.Kd * L.ld;
-    p.bmap = kPlain;
-    p.b_ld_guard = (int)L.ld;
+    if (ident) {
+      const long long HW = (long long)d.H * d.W;
+      p.B = xc;
+      p.b_ks = HW; p.b_gs = (long long)g.Cg * HW;
+      p.bmap = ColMap{(int)HW, (long long)d.C * HW};
+      p.b_ld_guard = 0;
+    } else {
+      rc = launch_lower(xc, ws + L.dt_off, L.ld, ni, d.C, g.lower, bf16, st);
+      if (rc) return rc;
+      p.B = ws + L.dt_off;
+      p.b_ks = L.ld; p.b_gs = (long long)g.Kd * L.ld;
+      p.bmap = kPlain;
+      p.b_ld_guard = (int)L.ld;
+    }
     p.M = g.Mr; p.Ncols = (int)ncols; p.Kdim = g.Kd; p.G = d.groups; p.bf16 = bf16;
-    if (type == CCT_LOWER_TYPE1) {
+    if (type == CCT_LOWER_TYPE1 || ident) {
       // lifting phase of Type 1 (a reshape) + bias fused into the GEMM epilogue
       p.C = yc;
       p.c_ms = P; p.c_gs = (long long)g.Og * P;
@@ -612,7 +623,8 @@ int cct_conv_backward_data(const cct_conv_desc_t* desc, const float* w, const fl
     p.a_gs = (long long)L.Mpad * L.Kpad;
     p.Mpad = L.Mpad; p.Kpad = L.Kpad;
     p.M = g.Kd; p.Ncols = (int)ncols; p.Kdim = g.Mr; p.G = d.groups; p.bf16 = bf16;
-    if (L.t2_opad) {
+    const bool ident = d.K == 1 && d.stride == 1 && d.pad == 0 && !bf16;
+    if (L.t2_opad && !ident) {
       // Type 2, stride 1: dR^T[(o,i)][(n,a,b)] = dy[n,o,a+p-i,b] gathered by the GEMM, rows
       // ordered (K-1-i, o): a convolution-like gather with K vertical taps, pad K-1-p
       p.B = dyc;
@@ -625,7 +637,7 @@ int cct_conv_backward_data(const cct_conv_desc_t* desc, const float* w, const fl
       p.gCpad = L.t2_opad;
       make_fastdiv_parts(p.gCpad, &p.g_divKK_M, &p.g_divKK_sh);
       p.Kdim = L.Kpad;
-    } else if (L.rt_bytes) {
+    } else if (L.rt_bytes && !ident) {
       // inverse lifting: spread dy over the rows of dR^T (a copy for Type 1 in bf16 mode)
       rc = launch_inv_lift(dyc, ws + L.rt_off, L.ld, ni, d.O, g.lift, bf16, st);
       if (rc) return rc;
@@ -640,8 +652,8 @@ int cct_conv_backward_data(const cct_conv_desc_t* desc, const float* w, const fl
       p.bmap = ColMap{(int)P, (long long)d.O * P};
       p.b_ld_guard = 0;
     }
-    if (type == CCT_LOWER_TYPE3) {
-      // inverse lowering of Type 3 is a reshape: the epilogue writes dx in place
+    if (type == CCT_LOWER_TYPE3 || ident) {
+      // inverse lowering of Type 3 (and of any 1x1 layer) is a reshape: the epilogue writes dx in place
       p.C = dxc;
       p.c_ms = HW; p.c_gs = (long long)g.Cg * HW;
       p.cmap = ColMap{(int)HW, (long long)d.C * HW};
