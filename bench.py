@@ -144,7 +144,8 @@ def main():
     }
     all_gemm_flops = sum(e["flops"] for e in gemms)
     all_gemm_ms = sum(e["total_ms"] for e in gemms)
-    streams = [e for e in prof if not is_mfma(e)]
+    # the lowering / lifting kernels proper (pack, split-K reduce and dbias are small helpers)
+    streams = [e for e in prof if e["name"].startswith(("lower_", "lift_", "inv_lift_", "inv_lower_"))]
     stream_bytes = sum(e["bytes"] for e in streams)
     stream_ms = sum(e["total_ms"] for e in streams)
     phases = {
@@ -152,8 +153,10 @@ def main():
         "all_gemm_frac_of_%s_mfma_peak" % ("fp32" if args.precision == "f32" else "bf16"):
             round(all_gemm_flops / (all_gemm_ms * 1e-3) / 1e12 / peak, 4),
         "gemm_share_of_kernel_time": round(all_gemm_ms / total_kernel_ms, 3),
-        "lower_lift_GBps": round(stream_bytes / (stream_ms * 1e-3) / 1e9, 1),
-        "lower_lift_frac_of_hbm_peak": round(stream_bytes / (stream_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+        "lower_lift_GBps": round(stream_bytes / (stream_ms * 1e-3) / 1e9, 1) if stream_ms else None,
+        "lower_lift_frac_of_hbm_peak":
+            round(stream_bytes / (stream_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4) if stream_ms else None,
+        "lower_lift_share_of_kernel_time": round(stream_ms / total_kernel_ms, 3),
     }
     if args.per_kernel:
         for e in sorted(prof, key=lambda e: -e["total_ms"]):
