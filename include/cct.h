@@ -158,7 +158,10 @@ int cct_conv_forward(const cct_conv_desc_t* desc, const float* x, const float* w
  *   dx[n,q*Cg+ci,h,w] = sum_{o in group q} sum_{i,j} dy[n,o,r,c] * w[o,ci,i,j]
  *   over (i,j) with h = r*stride+i-pad, w = c*stride+j-pad for a valid output position (r,c).
  * Computed as the three phases reversed: inverse lifting of dy, multiply with K^ transposed,
- * inverse lowering (a gather, no atomics).  w, dy: device, read.  dx: device, written.
+ * inverse lowering (a gather, no atomics).  A phase that is a reshape or a plain gather is done
+ * inside the multiply kernel instead of through a matrix in the workspace (Type 1: dy is read
+ * in place; Type 2 at stride 1: dy is gathered; Type 3 and 1x1 kernels: dx is written in place).
+ * w, dy: device, read.  dx: device, written.
  */
 int cct_conv_backward_data(const cct_conv_desc_t* desc, const float* w, const float* dy,
                            float* dx, void* workspace, size_t workspace_bytes,
