@@ -159,3 +159,41 @@ def test_selector_degenerate_and_strided_cases(B):
             t = B.cct_pick_lowering(dd, p)
             dd.lowering = t
             assert B.cct_conv_workspace_bytes(dd, p) > 0
+
+
+def test_fused_support_rules(B):
+    """Which passes the fused layout accepts (host-side rules only, no device work)."""
+    def supported(desc_args, p):
+        d = B.make_desc(*desc_args, lowering=B.LOWER_FUSED)
+        try:
+            B.cct_conv_workspace_bytes(d, p)
+            return True
+        except B.CctError as e:
+            assert e.code == B.EUNSUPPORTED
+            return False
+    conv1 = (256, 3, 227, 227, 96, 11, 4, 0, 1)
+    conv3 = (256, 256, 13, 13, 384, 3, 1, 1, 1)
+    assert supported(conv1, B.PASS_FORWARD) and supported(conv3, B.PASS_FORWARD)
+    assert not supported(conv1, B.PASS_BACKWARD_DATA)      # stride 4: no convolution with flipped kernels
+    assert supported(conv3, B.PASS_BACKWARD_DATA)
+    assert supported(conv1, B.PASS_BACKWARD_WEIGHTS)       # unpadded: rows gathered inside the GEMM
+    assert supported(conv3, B.PASS_BACKWARD_WEIGHTS)       # rows staged in LDS
+    padded_wide = (2, 6, 14, 400, 9, 4, 3, 1, 3)            # padded, rows too wide for LDS staging
+    assert not supported(padded_wide, B.PASS_BACKWARD_WEIGHTS)
+    # bf16 has no fused path at all
+    d = B.make_desc(*conv3, lowering=B.LOWER_FUSED, precision=B.PREC_BF16_IN_F32_ACC)
+    with pytest.raises(B.CctError):
+        B.cct_conv_workspace_bytes(d, B.PASS_FORWARD)
+
+
+def test_type2_backward_data_needs_no_inverse_lifted_matrix(B):
+    """At stride 1 in fp32 the Type-2 backward-data GEMM gathers dy itself: its workspace holds the
+    kernel matrix and dD^ only, so it is smaller than Type 3's (which holds dR^ of K*K*O rows)."""
+    conv2 = (256, 96, 27, 27, 256, 5, 1, 2, 2)
+    t2 = B.cct_conv_workspace_bytes(B.make_desc(*conv2, lowering=2), B.PASS_BACKWARD_DATA)
+    ld = 256 * 27 * 27
+    ddhat = 96 * 5 * ld * 4                       # C*K rows of the transposed lowered gradient
+    assert ddhat <= t2 < ddhat + (64 << 20)
+    s2 = B.cct_conv_workspace_bytes(B.make_desc(256, 96, 27, 27, 256, 5, 2, 2, 2, lowering=2),
+                                    B.PASS_BACKWARD_DATA)
+    assert s2 > 0                                  # stride 2 keeps the materialised route
