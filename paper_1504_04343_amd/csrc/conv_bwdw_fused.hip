@@ -119,7 +119,7 @@ __global__ __launch_bounds__(NT, 3) void conv_bwdw_fused_f32(ConvBwdW p, BwdwGeo
     rowoff[it] = (unsigned)(min(m0 + as_r0 + it * AS_ROWS, fg.M - 1) * fg.P + as_k) * 4u;
 
   float ras[AS_IT];
-  float rx[XR * V];
+  float rx[XR * V] = {};   // rows a chunk does not need keep their previous contents
 
   // Global loads of one chunk (dy tile, input rows) and its position table.
 #define CCT_BW_LOAD(C0, TSLOT)                                                                  \
@@ -163,20 +163,26 @@ __global__ __launch_bounds__(NT, 3) void conv_bwdw_fused_f32(ConvBwdW p, BwdwGeo
       tabs[(TSLOT) * BK + as_k] = srow * ROWP + c * p.s;                                        \
     }                                                                                           \
     /* input rows: a scalar walk over the staged rows (rest of the first image, whole images,   \
-       the first rows of the last image); rows outside the image get an empty range */          \
+       the first rows of the last image).  The row pointer advances by one input row per staged \
+       row and jumps at an image boundary; rows outside the image get an empty range, rows     \
+       past the last needed one are not loaded at all (nothing reads them). */                  \
     {                                                                                           \
-      int img = n_f, h = a_f * p.s - p.p, left = rows_first;                                    \
+      int h = a_f * p.s - p.p, left = rows_first;                                               \
+      const float* rowp = Xg + (long long)n_f * CHW + (long long)h * p.W;                       \
       _Pragma("unroll") for (int u = 0; u < XR; ++u) {                                          \
-        const bool valid = u < rows_total && h >= 0 && h < p.H;                                 \
-        const float* base = Xg + (valid ? (long long)img * CHW + (long long)h * p.W : 0ll);     \
-        const __amdgpu_buffer_rsrc_t rxs = __builtin_amdgcn_make_buffer_rsrc(                   \
-            const_cast<float*>(base), 0, valid ? 0x7fffffff : 0, kRsrcFlags);                   \
-        _Pragma("unroll") for (int v = 0; v < V; ++v) rx[u * V + v] = buf_load(rxs, xvoff[v], 0u); \
-        ++h;                                                                                    \
-        if (--left == 0) {                                                                      \
-          ++img;                                                                                \
-          h = -p.p;                                                                             \
-          left = fg.rows_full;                                                                  \
+        if (u < rows_total) {                                                                   \
+          const bool valid = h >= 0 && h < p.H;                                                 \
+          const __amdgpu_buffer_rsrc_t rxs = __builtin_amdgcn_make_buffer_rsrc(                 \
+              const_cast<float*>(rowp), 0, valid ? 0x7fffffff : 0, kRsrcFlags);                 \
+          _Pragma("unroll") for (int v = 0; v < V; ++v)                                         \
+            rx[u * V + v] = buf_load(rxs, xvoff[v], 0u);                                        \
+          ++h;                                                                                  \
+          rowp += p.W;                                                                          \
+          if (--left == 0) { /* next image: its staged rows start at input row -pad */          \
+            rowp += CHW - (long long)(h + p.p) * p.W;                                           \
+            h = -p.p;                                                                           \
+            left = fg.rows_full;                                                                \
+          }                                                                                     \
         }                                                                                       \
       }                                                                                         \
     }                                                                                           \
