@@ -32,8 +32,8 @@
  *  - Return value: CCT_OK (0) or a negative CCT_E* code.  On error nothing has been
  *    enqueued for that call (except CCT_EHIP, which reports a failed launch).
  *  - The workspace must be 256-byte aligned.  Its size decides how many images are
- *    lowered and multiplied together ("batch as much as device memory permits",
- *    Sec. 2.2): the library processes the batch in chunks of the largest number of
+ *    lowered and multiplied together (Sec. 2.2 recommends the largest batch that memory
+ *    allows): the library processes the batch in chunks of the largest number of
  *    images whose buffers fit the workspace it was given.
  */
 #ifndef CCT_H_
@@ -117,9 +117,9 @@ int cct_lowered_shape(const cct_conv_desc_t* desc, cct_lowering_t lowering, int6
                       int64_t* cols, int64_t* rcols);
 
 /*
- * The automatic lowering optimizer (Sec. 1; Appendix A "the relative performance ...
- * is determined by the ratio between the number of input channels and the number of
- * output channels").  Host only, no device work.  Evaluates a cost model
+ * The automatic lowering optimizer (Sec. 1; Appendix A: which layout is fastest depends
+ * on how the number of input channels compares with the number of output channels).
+ * Host only, no device work.  Evaluates a cost model
  * (bytes moved by lowering and lifting at the measured HBM rate + GEMM flops at the
  * measured MFMA rate, both calibrated on MI355X) for each layout that the library can
  * run for `pass` on this shape and returns the cheapest.  Never returns a layout that
