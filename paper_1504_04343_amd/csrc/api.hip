@@ -169,6 +169,7 @@ bool make_layout(const cct_conv_desc_t& d, int pass, int type, const Geom& g, lo
 
 bool type_supported(const cct_conv_desc_t& d, int pass, int type) {
   if (type < CCT_LOWER_TYPE1 || type > CCT_LOWER_FUSED) return false;
+  if (d.groups > 65535) return false;  // groups are the second grid dimension of every GEMM launch
   if (type == CCT_LOWER_FUSED) {
     if (d.precision != CCT_PREC_F32) return false;
     // backward-weights: the input rows of 32 positions must fit in LDS; an unpadded layer can
@@ -287,7 +288,8 @@ double model_cost(const cct_conv_desc_t& d, int pass, int type) {
 }
 
 int pick(const cct_conv_desc_t& d, int pass) {
-  if (d.K == 1 && d.stride == 1 && d.pad == 0) return CCT_LOWER_TYPE1;
+  if (d.K == 1 && d.stride == 1 && d.pad == 0 && type_supported(d, pass, CCT_LOWER_TYPE1))
+    return CCT_LOWER_TYPE1;
   int best = 0;
   double best_cost = 0.0;
   for (int t = CCT_LOWER_TYPE1; t <= CCT_LOWER_FUSED; ++t) {
@@ -581,30 +583,35 @@ int cct_conv_backward_data(const cct_conv_desc_t* desc, const float* w, const fl
   const long long HW = (long long)d.H * d.W;
 
   if (type == CCT_LOWER_FUSED) {
-    // one kernel: dx = convolution of dy (O channels, Hout x Wout) with the flipped kernels,
-    // stride 1, pad K-1-p; lowering of dy happens in LDS (or as a gather), never in HBM
+    // one kernel per chunk: dx = convolution of dy (O channels, Hout x Wout) with the flipped
+    // kernels, stride 1, pad K-1-p; lowering of dy happens in LDS (or as a gather), never in HBM
     rc = launch_pack_flipped(w, reinterpret_cast<float*>(ws + L.pack_off), d.groups, g.Og, g.Cg, d.K,
                              L.Mpad, L.Kpad, st);
     if (rc) return rc;
-    GemmTN p;
-    std::memset(&p, 0, sizeof(p));
-    p.A = ws + L.pack_off;
-    p.a_gs = (long long)L.Mpad * L.Kpad;
-    p.Mpad = L.Mpad; p.Kpad = L.Kpad;
-    p.B = dy;
-    p.bmap = ColMap{1, 0};
-    p.gather = 1;
-    p.gC = d.O; p.gH = g.Hout; p.gW = g.Wout; p.gHout = d.H; p.gWout = d.W;
-    p.gs = 1; p.gp = d.K - 1 - d.pad; p.gCg = g.Og; p.gK = d.K; p.gKK = d.K * d.K;
-    make_fastdiv_parts(p.gKK, &p.g_divKK_M, &p.g_divKK_sh);
-    make_fastdiv_parts(p.gK, &p.g_divK_M, &p.g_divK_sh);
-    p.M = g.Cg; p.Ncols = (int)((long long)d.N * HW); p.Kdim = g.Og * d.K * d.K; p.G = d.groups;
-    p.C = dx;
-    p.c_ms = HW; p.c_gs = (long long)g.Cg * HW;
-    p.cmap = ColMap{(int)HW, (long long)d.C * HW};
-    rc = launch_conv_fused(p, st);
-    if (rc == CCT_EUNSUPPORTED) rc = launch_gemm_tn(p, st);
-    return rc;
+    for (long long n0 = 0; n0 < d.N; n0 += nc) {
+      const long long ni = std::min<long long>(nc, d.N - n0);
+      GemmTN p;
+      std::memset(&p, 0, sizeof(p));
+      p.A = ws + L.pack_off;
+      p.a_gs = (long long)L.Mpad * L.Kpad;
+      p.Mpad = L.Mpad; p.Kpad = L.Kpad;
+      p.B = dy + n0 * d.O * P;
+      p.bmap = ColMap{1, 0};
+      p.gather = 1;
+      p.gC = d.O; p.gH = g.Hout; p.gW = g.Wout; p.gHout = d.H; p.gWout = d.W;
+      p.gs = 1; p.gp = d.K - 1 - d.pad; p.gCg = g.Og; p.gK = d.K; p.gKK = d.K * d.K;
+      make_fastdiv_parts(p.gKK, &p.g_divKK_M, &p.g_divKK_sh);
+      make_fastdiv_parts(p.gK, &p.g_divK_M, &p.g_divK_sh);
+      // make_layout accepted this chunk size only if ni*H*W fits 31 bits
+      p.M = g.Cg; p.Ncols = (int)(ni * HW); p.Kdim = g.Og * d.K * d.K; p.G = d.groups;
+      p.C = dx + n0 * d.C * HW;
+      p.c_ms = HW; p.c_gs = (long long)g.Cg * HW;
+      p.cmap = ColMap{(int)HW, (long long)d.C * HW};
+      rc = launch_conv_fused(p, st);
+      if (rc == CCT_EUNSUPPORTED) rc = launch_gemm_tn(p, st);
+      if (rc) return rc;
+    }
+    return CCT_OK;
   }
   if (L.t2_opad)
     rc = launch_pack_type2_bwd(w, reinterpret_cast<float*>(ws + L.pack_off), d.groups, g.Og, g.Cg,

@@ -6,6 +6,8 @@
 #include <stdint.h>
 #include <string.h>
 
+#include <atomic>
+
 #include "cct.h"
 
 namespace cct {
@@ -177,6 +179,24 @@ class ProfScope {
   hipStream_t st_;
   long long idx_;
 };
+
+// Raises the dynamic-LDS limit of kernel `Kern` to `bytes` once per device and process instead of
+// on every launch.  CCT_EHIP if the runtime refuses.
+template <auto Kern>
+int ensure_dynamic_lds(int bytes) {
+  static std::atomic<unsigned long long> done{0};  // bit d: set for device d
+  int dev = 0;
+  const bool known = hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < 64;
+  if (known && (done.load(std::memory_order_acquire) >> dev) & 1ULL) return CCT_OK;
+  const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(Kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e != hipSuccess) {
+    set_hip_error(e);
+    return CCT_EHIP;
+  }
+  if (known) done.fetch_or(1ULL << dev, std::memory_order_release);
+  return CCT_OK;
+}
 
 #define CCT_CHECK_LAUNCH()                       \
   do {                                           \

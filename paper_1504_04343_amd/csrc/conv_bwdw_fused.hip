@@ -382,11 +382,8 @@ bool make_geom(int C, int H, int W, int K, int s, int pad, int Hout, int Wout, i
 template <int BM, int WM, int WN, int V, int XR>
 int launch_kernel(const ConvBwdW& p, const BwdwGeom& fg, size_t lds, dim3 grid, int tiles_m,
                   int tiles_n, hipStream_t st) {
-  auto kern = conv_bwdw_fused_f32<BM, WM, WN, V, XR>;
-  if (lds > 65536 && hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize,
-                                         (int)lds) != hipSuccess)
-    return CCT_EUNSUPPORTED;
+  constexpr auto kern = conv_bwdw_fused_f32<BM, WM, WN, V, XR>;
+  if (const int rc = ensure_dynamic_lds<kern>(kMaxLds)) return rc;
   hipLaunchKernelGGL(kern, grid, dim3(NT), lds, st, p, fg, tiles_m, tiles_n);
   return CCT_OK;
 }

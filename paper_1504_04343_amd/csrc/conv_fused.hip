@@ -363,19 +363,14 @@ int launch_variant(const GemmTN& p, const FusedGeom& fg, bool ring, size_t lds, 
   const double x_bytes = 4.0 * ((double)p.Ncols / (p.gHout * p.gWout)) * p.gC * p.gH * p.gW;
   ProfScope ps(name, 2.0 * p.M * p.Ncols * p.Kdim * p.G,
                x_bytes + 4.0 * ((double)p.M * p.Ncols + (double)p.M * p.Kdim) * p.G, st);
+  constexpr int kLdsCap = 80 * 1024;  // what launch_conv_fused admits
   if (ring) {
-    auto kern = conv_fused_f32<BM, WM, WN, true>;
-    if (lds > 65536 &&
-        hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-      return CCT_EUNSUPPORTED;
+    constexpr auto kern = conv_fused_f32<BM, WM, WN, true>;
+    if (const int rc = ensure_dynamic_lds<kern>(kLdsCap)) return rc;
     hipLaunchKernelGGL(kern, grid, dim3(NT), lds, st, p, fg, tiles_m, tiles_n);
   } else {
-    auto kern = conv_fused_f32<BM, WM, WN, false>;
-    if (lds > 65536 &&
-        hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-      return CCT_EUNSUPPORTED;
+    constexpr auto kern = conv_fused_f32<BM, WM, WN, false>;
+    if (const int rc = ensure_dynamic_lds<kern>(kLdsCap)) return rc;
     hipLaunchKernelGGL(kern, grid, dim3(NT), lds, st, p, fg, tiles_m, tiles_n);
   }
   CCT_CHECK_LAUNCH();

@@ -197,3 +197,28 @@ def test_type2_backward_data_needs_no_inverse_lifted_matrix(B):
     s2 = B.cct_conv_workspace_bytes(B.make_desc(256, 96, 27, 27, 256, 5, 2, 2, 2, lowering=2),
                                     B.PASS_BACKWARD_DATA)
     assert s2 > 0                                  # stride 2 keeps the materialised route
+
+
+def test_fused_backward_data_chunks_a_batch_whose_pixel_count_exceeds_31_bits(B):
+    """N*H*W >= 2^31: the fused backward-data pass cannot cover the batch with one launch (its
+    columns are 32-bit), so the whole-batch chunk is refused and the default workspace stands for
+    a smaller chunk that the entry point then loops over."""
+    d = B.make_desc(40000, 1, 256, 256, 1, 3, 1, 1, 1, B.LOWER_FUSED)
+    assert d.N * d.H * d.W >= 2 ** 31
+    assert B.cct_conv_workspace_bytes(d, B.PASS_BACKWARD_DATA) > 0
+    assert B.cct_conv_workspace_bytes_for_chunk(d, B.PASS_BACKWARD_DATA, 1000) > 0
+    with pytest.raises(B.CctError) as e:
+        B.cct_conv_workspace_bytes_for_chunk(d, B.PASS_BACKWARD_DATA, d.N)
+    assert e.value.code == B.EUNSUPPORTED
+
+
+def test_group_count_beyond_the_grid_limit_is_unsupported_not_a_late_failure(B):
+    d = B.make_desc(1, 70000, 4, 4, 70000, 3, 1, 1, 70000)
+    for pass_ in (0, 1, 2):
+        with pytest.raises(B.CctError) as e:
+            B.cct_pick_lowering(d, pass_)
+        assert e.value.code == B.EUNSUPPORTED
+    d1 = B.make_desc(1, 70000, 4, 4, 70000, 1, 1, 0, 70000)       # 1x1: the shortcut must check too
+    with pytest.raises(B.CctError) as e:
+        B.cct_pick_lowering(d1, B.PASS_FORWARD)
+    assert e.value.code == B.EUNSUPPORTED

@@ -1,13 +1,22 @@
-"""GPU parity at the benchmark's full sizes (CaffeNet conv1-5, batch 256, the launch
-configuration bench.py times: AUTO lowering, default workspace), on sampled outputs that the
-oracle computes one by one."""
+"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times (AUTO
+lowering, default workspace).
+
+* CaffeNet conv1-5 at batch 256, fp32: EVERY element of y, dx, dw and dbias against the oracle's
+  full direct loops.
+* The same layers at batch 1024 and with bf16 operands: all five layers, on sampled outputs that
+  the oracle computes one by one (the full loops would take minutes per layer at batch 1024).
+* conv2 at batch 1024 with the Type-1 layout forced and a workspace for the whole batch: its
+  lowered matrix is 7.2 GB, so element offsets pass 2^32 bytes.
+* The channel-ratio sweep (Appendix A) at its own batch of 128: every layout and the optimizer's
+  pick, every element.
+"""
 import numpy as np
 import pytest
 
 import oracle
 from paper_1504_04343_amd import synth
-from gpu_util import (TOL_F32, desc_of, gpu_backward_data, gpu_backward_weights, gpu_forward,
-                      odims, rel_err)
+from gpu_util import (TOL_BF16, TOL_F32, desc_of, gpu_backward_data, gpu_backward_weights,
+                      gpu_forward, odims, rel_err)
 
 pytestmark = pytest.mark.gpu
 
@@ -26,83 +35,121 @@ def scale_of(vals):
     return float(np.abs(vals).max())
 
 
+def sampled_err(got, want, idx):
+    return float(np.abs(got.ravel()[idx] - want).max() / scale_of(want))
+
+
 @pytest.mark.parametrize("L", LAYERS, ids=[L.name for L in LAYERS])
-def test_full_size_layer_forward_backward_sampled(B, L):
-    print("full-size", L.name, flush=True)
+def test_full_size_layer_every_element(B, L):
+    """The headline configuration, element by element: nothing is sampled."""
+    print("full-size, all elements", L.name, flush=True)
     x, w, dy = synth.make_x(L), synth.make_w(L), synth.make_dy(L)
     bias = (np.random.default_rng(11).standard_normal(L.O) * 0.1).astype(np.float32)
     od = odims(oracle, L)
 
     y = gpu_forward(B, L, x, w, bias, B.LOWER_AUTO)
-    idx = synth.sample_indices(y.size, 4000, 1)
-    want = oracle.conv_forward_at(od, x, w, bias, idx)
-    assert np.abs(y.ravel()[idx] - want).max() / scale_of(want) <= TOL_F32
-    assert np.isfinite(y).all()
-    del y
+    want = oracle.conv_forward(od, x, w, bias)
+    assert y.shape == want.shape
+    assert rel_err(y, want) <= TOL_F32
+    del y, want
+    print("  forward ok", flush=True)
 
     dx = gpu_backward_data(B, L, w, dy, B.LOWER_AUTO)
-    idx = synth.sample_indices(dx.size, 4000, 2)
-    want = oracle.conv_backward_data_at(od, w, dy, idx)
-    assert np.abs(dx.ravel()[idx] - want).max() / scale_of(want) <= TOL_F32
-    assert np.isfinite(dx).all()
-    del dx
+    want = oracle.conv_backward_data(od, w, dy)
+    assert dx.shape == want.shape
+    assert rel_err(dx, want) <= TOL_F32
+    del dx, want
+    print("  backward-data ok", flush=True)
 
     dw, db = gpu_backward_weights(B, L, x, dy, B.LOWER_AUTO)
-    idx = synth.sample_indices(dw.size, 96, 3)
-    want = oracle.conv_backward_weights_at(od, x, dy, idx)
-    assert np.abs(dw.ravel()[idx] - want).max() / scale_of(want) <= TOL_F32
+    dw_want, db_want = oracle.conv_backward_weights(od, x, dy)
+    assert rel_err(dw, dw_want) <= TOL_F32
+    assert rel_err(db, db_want) <= TOL_F32
+    # dbias is a plain sum: numpy's fp64 sum is its definition, independent of the oracle
+    assert rel_err(db, dy.astype(np.float64).sum(axis=(0, 2, 3))) <= TOL_F32
+    print("  backward-weights ok", flush=True)
+
+
+def _sampled_layer(B, L, lowering, precision, tol, n_y, n_dw, chunk=None):
+    x, w, dy = synth.make_x(L), synth.make_w(L), synth.make_dy(L)
+    od = odims(oracle, L)
+    y = gpu_forward(B, L, x, w, None, lowering, precision, chunk=chunk)
+    idx = synth.sample_indices(y.size, n_y, 1)
+    assert sampled_err(y, oracle.conv_forward_at(od, x, w, None, idx), idx) <= tol
+    assert np.isfinite(y).all()
+    del y
+    dx = gpu_backward_data(B, L, w, dy, lowering, precision, chunk=chunk)
+    idx = synth.sample_indices(dx.size, n_y, 2)
+    assert sampled_err(dx, oracle.conv_backward_data_at(od, w, dy, idx), idx) <= tol
+    assert np.isfinite(dx).all()
+    del dx
+    dw, db = gpu_backward_weights(B, L, x, dy, lowering, precision, chunk=chunk)
+    idx = synth.sample_indices(dw.size, n_dw, 3)
+    assert sampled_err(dw, oracle.conv_backward_weights_at(od, x, dy, idx), idx) <= tol
     assert np.isfinite(dw).all()
-    # dbias is a plain sum: fp64 numpy sum is its definition
-    want_db = dy.astype(np.float64).sum(axis=(0, 2, 3))
-    assert rel_err(db, want_db) <= TOL_F32
+    assert rel_err(db, dy.astype(np.float64).sum(axis=(0, 2, 3))) <= TOL_F32
 
 
-BIG = [L.with_batch(1024) for L in LAYERS if L.name in ("conv1", "conv3")]
+BIG = [L.with_batch(1024) for L in LAYERS]
 
 
 @pytest.mark.parametrize("L", BIG, ids=[L.name + "_b1024" for L in BIG])
 def test_batch_1024_sampled(B, L):
-    """The larger batch of the full-stack configuration.  conv1's lowered matrices (4.5 GB at this
-    batch) exceed the default workspace, so its backward passes run in several chunks."""
+    """The larger batch of the full-stack configuration, all five layers.  conv1's lowered
+    gradient (4.5 GB at this batch) exceeds the default workspace, so that pass runs in chunks."""
     print("batch-1024", L.name, flush=True)
-    x, w, dy = synth.make_x(L), synth.make_w(L), synth.make_dy(L)
-    od = odims(oracle, L)
-    y = gpu_forward(B, L, x, w, None, B.LOWER_AUTO)
-    idx = synth.sample_indices(y.size, 1500, 1)
-    want = oracle.conv_forward_at(od, x, w, None, idx)
-    assert np.abs(y.ravel()[idx] - want).max() / scale_of(want) <= TOL_F32
-    del y
-    dx = gpu_backward_data(B, L, w, dy, B.LOWER_AUTO)
-    idx = synth.sample_indices(dx.size, 1500, 2)
-    want = oracle.conv_backward_data_at(od, w, dy, idx)
-    assert np.abs(dx.ravel()[idx] - want).max() / scale_of(want) <= TOL_F32
-    del dx
-    dw, db = gpu_backward_weights(B, L, x, dy, B.LOWER_AUTO)
-    idx = synth.sample_indices(dw.size, 24, 3)
-    want = oracle.conv_backward_weights_at(od, x, dy, idx)
-    assert np.abs(dw.ravel()[idx] - want).max() / scale_of(want) <= TOL_F32
-    assert rel_err(db, dy.astype(np.float64).sum(axis=(0, 2, 3))) <= TOL_F32
+    _sampled_layer(B, L, B.LOWER_AUTO, B.PREC_F32, TOL_F32, 1500, 24)
 
 
-@pytest.mark.parametrize("L", [LAYERS[1], LAYERS[2]], ids=["conv2_bf16", "conv3_bf16"])
+def test_batch_1024_conv2_type1_matrix_beyond_4GiB(B):
+    """conv2 at batch 1024, Type 1 forced, workspace for all 1024 images at once: the lowered
+    matrix has 2400 rows of 746 496 floats = 7.2 GB, so row offsets do not fit 32 bits."""
+    L = BIG[1]
+    d = desc_of(B, L, B.LOWER_TYPE1)
+    assert B.cct_conv_workspace_bytes_for_chunk(d, B.PASS_FORWARD, L.N) > (1 << 32)
+    print("batch-1024 conv2 Type 1, one chunk", flush=True)
+    _sampled_layer(B, L, B.LOWER_TYPE1, B.PREC_F32, TOL_F32, 1500, 24, chunk=L.N)
+
+
+@pytest.mark.parametrize("L", LAYERS, ids=[L.name + "_bf16" for L in LAYERS])
 def test_full_size_bf16_variant_sampled(B, L):
-    """bf16 operands, fp32 accumulate, AUTO lowering, against the fp64 oracle on unrounded inputs."""
-    from gpu_util import TOL_BF16
+    """bf16 operands, fp32 accumulate, AUTO lowering, all five layers, against the fp64 oracle on
+    the unrounded inputs."""
     print("full-size bf16", L.name, flush=True)
+    _sampled_layer(B, L, B.LOWER_AUTO, B.PREC_BF16_IN_F32_ACC, TOL_BF16, 2000, 48)
+
+
+SWEEP = synth.tradeoff_sweep()          # batch 128, 28 x 28, k in {1, 3}
+
+
+@pytest.mark.parametrize("L", SWEEP, ids=[L.name for L in SWEEP])
+def test_tradeoff_sweep_at_batch_128_every_element(B, L):
+    """Appendix A's sweep at the batch the configuration names: Types 1-3, the fused layout and
+    the optimizer's pick all give the oracle's y, element by element."""
+    print("sweep", L.name, flush=True)
+    x, w, b = synth.make_x(L, 2), synth.make_w(L, 2), synth.make_bias(L, 2)
+    want = oracle.conv_forward(odims(oracle, L), x, w, b)
+    for lowering in (1, 2, 3, B.LOWER_FUSED, B.LOWER_AUTO):
+        got = gpu_forward(B, L, x, w, b, lowering)
+        assert rel_err(got, want) <= TOL_F32, lowering
+
+
+@pytest.mark.parametrize("pass_", ["forward", "backward_data", "backward_weights"])
+def test_auto_path_is_bit_reproducible_conv2(B, pass_):
+    """The layouts AUTO picks (fused kernels, split reductions summed in split order) give the
+    same bits run after run: no atomics, no order that depends on scheduling."""
+    L = LAYERS[1]
     x, w, dy = synth.make_x(L), synth.make_w(L), synth.make_dy(L)
-    od = odims(oracle, L)
-    P = B.PREC_BF16_IN_F32_ACC
-    y = gpu_forward(B, L, x, w, None, B.LOWER_AUTO, P)
-    idx = synth.sample_indices(y.size, 2000, 1)
-    want = oracle.conv_forward_at(od, x, w, None, idx)
-    assert np.abs(y.ravel()[idx] - want).max() / scale_of(want) <= TOL_BF16
-    del y
-    dx = gpu_backward_data(B, L, w, dy, B.LOWER_AUTO, P)
-    idx = synth.sample_indices(dx.size, 2000, 2)
-    want = oracle.conv_backward_data_at(od, w, dy, idx)
-    assert np.abs(dx.ravel()[idx] - want).max() / scale_of(want) <= TOL_BF16
-    del dx
-    dw, _ = gpu_backward_weights(B, L, x, dy, B.LOWER_AUTO, P)
-    idx = synth.sample_indices(dw.size, 48, 3)
-    want = oracle.conv_backward_weights_at(od, x, dy, idx)
-    assert np.abs(dw.ravel()[idx] - want).max() / scale_of(want) <= TOL_BF16
+    bias = synth.make_bias(L)
+
+    def run():
+        if pass_ == "forward":
+            return gpu_forward(B, L, x, w, bias, B.LOWER_AUTO).tobytes()
+        if pass_ == "backward_data":
+            return gpu_backward_data(B, L, w, dy, B.LOWER_AUTO).tobytes()
+        dw, db = gpu_backward_weights(B, L, x, dy, B.LOWER_AUTO)
+        return dw.tobytes() + db.tobytes()
+
+    first = run()
+    assert first == run()
+    assert first == run()

@@ -291,6 +291,52 @@ def test_lowering_is_a_pure_copy_with_positive_zero_padding():
     assert d1[0, 0] == 0 and d1[0, 4] == x[0, 0, 0, 0]
 
 
+def test_type2_and_type3_lowered_entries_written_out_by_hand():
+    """Sec. 2.1: a Type-2 row holds, for one input row and one output column, the K pixels of the
+    horizontal window of every channel; a Type-3 row holds the channels of one input pixel.  The
+    entries below are worked out by hand from those two sentences for a grouped, strided, padded
+    layer, with x[n,c,h,w] = 1000 n + 100 c + 10 h + w + 1 so that a value names its source."""
+    N, C, H, W, O, K, s, p, g = 2, 4, 5, 6, 2, 3, 2, 1, 2
+    d = Dims(N, C, H, W, O, K, s, p, g)
+    x = np.zeros((N, C, H, W), np.float32)
+    for n, c, h, w in itertools.product(range(N), range(C), range(H), range(W)):
+        x[n, c, h, w] = 1000 * n + 100 * c + 10 * h + w + 1
+    assert oracle.output_dims(d) == (3, 3)                       # (5+2-3)//2+1 = 3, (6+2-3)//2+1 = 3
+    Wout, Cg = 3, 2
+
+    d2 = oracle.lower_data(d, 2, x)                              # (groups, N*H*Wout, Cg*K)
+    assert d2.shape == (2, N * H * Wout, Cg * K)
+    # group 0, image 1, input row h=4, output column c=2: window columns c*s+j-p = 3,4,5
+    row = (1 * H + 4) * Wout + 2
+    assert d2[0, row].tolist() == [1044, 1045, 1046,             # channel 0: x[1,0,4,3..5]
+                                   1144, 1145, 1146]             # channel 1: x[1,1,4,3..5]
+    # group 1 (channels 2,3), image 0, row h=0, column c=0: window columns -1,0,1 -> first is padding
+    row = (0 * H + 0) * Wout + 0
+    assert d2[1, row].tolist() == [0, 201, 202, 0, 301, 302]
+    # a middle column, c=1: window columns 1,2,3; every input row appears, also odd ones (h=3)
+    row = (0 * H + 3) * Wout + 1
+    assert d2[0, row].tolist() == [32, 33, 34, 132, 133, 134]
+    # a wrong row order (c-major instead of h-major) would put x[.,.,1,*] here, not x[.,.,0,*]
+    assert d2[0, 1].tolist() == [2, 3, 4, 102, 103, 104]          # (h=0, c=1)
+    assert d2[0, Wout].tolist() == [0, 11, 12, 0, 111, 112]       # (h=1, c=0)
+
+    d3 = oracle.lower_data(d, 3, x)                              # (groups, N*H*W, Cg)
+    assert d3.shape == (2, N * H * W, Cg)
+    assert d3[0, (1 * H + 2) * W + 5].tolist() == [1026, 1126]    # pixel (n=1,h=2,w=5), channels 0,1
+    assert d3[1, (0 * H + 4) * W + 0].tolist() == [241, 341]      # pixel (n=0,h=4,w=0), channels 2,3
+    assert d3[0, 1].tolist() == [2, 102]                          # (h=0,w=1): w runs fastest
+    assert d3[0, W].tolist() == [11, 111]                         # (h=1,w=0)
+    # Type 3 is a pure transpose of x: every entry, rebuilt without the oracle
+    want3 = x.reshape(N, g, Cg, H * W).transpose(1, 0, 3, 2).reshape(g, N * H * W, Cg)
+    assert np.array_equal(d3, want3)
+    # Type 2, every entry, from the sentence above with explicit zero padding of the columns
+    xp = np.pad(x, ((0, 0), (0, 0), (0, 0), (p, p)))
+    want2 = np.zeros((g, N * H * Wout, Cg * K), np.float32)
+    for q, n, h, c, ci, j in itertools.product(range(g), range(N), range(H), range(Wout), range(Cg), range(K)):
+        want2[q, (n * H + h) * Wout + c, ci * K + j] = xp[n, q * Cg + ci, h, c * s + j]
+    assert np.array_equal(d2, want2)
+
+
 # ---------------------------------------------------------------- shape laws
 def test_shape_laws_golden():
     path = os.path.join(os.path.dirname(__file__), "golden", "caffenet_shapes.txt")
