@@ -84,7 +84,9 @@ enum {
   CCT_EWORKSPACE = -2,   /* workspace smaller than what one image needs                      */
   CCT_EUNSUPPORTED = -3, /* explicitly requested combination the library does not run, or
                             sizes beyond its 31-bit row/column limits                        */
-  CCT_EHIP = -4          /* a HIP launch failed; see cct_last_hip_error                      */
+  CCT_EHIP = -4,         /* a HIP call failed; see cct_last_hip_error                        */
+  CCT_ESCRATCH = -5      /* cct_conv_forward_static: the buffers of one image exceed
+                            CCT_STATIC_SCRATCH_BYTES                                         */
 };
 
 /* Host struct.  `lowering` holds a cct_lowering_t, `precision` a cct_precision_t. */
@@ -152,6 +154,25 @@ int cct_conv_workspace_bytes_for_chunk(const cct_conv_desc_t* desc, cct_pass_t p
 int cct_conv_forward(const cct_conv_desc_t* desc, const float* x, const float* w,
                      const float* bias, float* y, void* workspace, size_t workspace_bytes,
                      void* hip_stream);
+
+/*
+ * Forward pass for callers that cannot allocate or pass device memory of their own beyond the
+ * tensors: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same computation, same kernels and same results as cct_conv_forward, but the workspace is a
+ * fixed array of CCT_STATIC_SCRATCH_BYTES bytes inside the library's device image (every GPU
+ * the library is used on holds its own copy until the process ends).  The call allocates and
+ * frees nothing, on the host side it only looks up that array's device address the first time it
+ * runs on a device.  The batch is processed in chunks of as many images as fit the array;
+ * CCT_ESCRATCH (nothing enqueued) if the buffers of a single image do not fit, which can only
+ * happen with a materialised layout (the fused layout AUTO prefers needs the packed kernels only).
+ * All calls on one GPU share the array, which keeps the previous call's contents (every kernel
+ * writes what it later reads, nothing needs to start at zero): calls that may overlap in time on
+ * the same GPU, e.g. on two streams, race and must be serialised by the caller.
+ * The current device must be the one that owns x, w, bias, y and the stream.
+ */
+#define CCT_STATIC_SCRATCH_BYTES (32u << 20)
+int cct_conv_forward_static(const cct_conv_desc_t* desc, const float* x, const float* w,
+                            const float* bias, float* y, void* hip_stream);
 
 /*
  * Backward pass w.r.t. the data: dx = adjoint of the forward map in x applied to dy,

@@ -23,14 +23,15 @@ _lib = ctypes.CDLL(LIB_PATH)
 LOWER_AUTO, LOWER_TYPE1, LOWER_TYPE2, LOWER_TYPE3, LOWER_FUSED = 0, 1, 2, 3, 4
 PREC_F32, PREC_BF16_IN_F32_ACC = 0, 1
 PASS_FORWARD, PASS_BACKWARD_DATA, PASS_BACKWARD_WEIGHTS = 0, 1, 2
-OK, EINVAL, EWORKSPACE, EUNSUPPORTED, EHIP = 0, -1, -2, -3, -4
+OK, EINVAL, EWORKSPACE, EUNSUPPORTED, EHIP, ESCRATCH = 0, -1, -2, -3, -4, -5
+STATIC_SCRATCH_BYTES = 32 << 20
 
 EXPORTS = [
     "cct_strerror", "cct_last_hip_error", "cct_conv_output_dims", "cct_lowered_shape",
     "cct_pick_lowering", "cct_lowering_cost", "cct_conv_workspace_bytes",
     "cct_conv_workspace_bytes_for_chunk", "cct_conv_forward", "cct_conv_backward_data",
     "cct_conv_backward_weights", "cct_lowered_ld", "cct_lower", "cct_profile_enable",
-    "cct_profile_read", "cct_calibration_copy",
+    "cct_profile_read", "cct_calibration_copy", "cct_conv_forward_static",
 ]
 
 
@@ -61,6 +62,7 @@ _lib.cct_lowering_cost.argtypes = [_dp, ctypes.c_int, ctypes.c_int, ctypes.POINT
 _lib.cct_conv_workspace_bytes.argtypes = [_dp, ctypes.c_int, ctypes.POINTER(_sz)]
 _lib.cct_conv_workspace_bytes_for_chunk.argtypes = [_dp, ctypes.c_int, _i32, ctypes.POINTER(_sz)]
 _lib.cct_conv_forward.argtypes = [_dp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.cct_conv_forward_static.argtypes = [_dp, _vp, _vp, _vp, _vp, _vp]
 _lib.cct_conv_backward_data.argtypes = [_dp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.cct_conv_backward_weights.argtypes = [_dp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.cct_lower.argtypes = [_dp, ctypes.c_int, _vp, _vp, _vp]
@@ -221,6 +223,13 @@ def cct_conv_forward(desc: ConvDesc, x, w, bias, y, workspace) -> None:
     _check(_lib.cct_conv_forward(ctypes.byref(desc), _ptr(x, "x", xs), _ptr(w, "w", ws_),
                                  _ptr(bias, "bias", (desc.O,), optional=True), _ptr(y, "y", ys),
                                  wp, wn, _stream()), "cct_conv_forward")
+
+
+def cct_conv_forward_static(desc: ConvDesc, x, w, bias, y) -> None:
+    xs, ws_, ys = _shapes(desc)
+    _check(_lib.cct_conv_forward_static(ctypes.byref(desc), _ptr(x, "x", xs), _ptr(w, "w", ws_),
+                                        _ptr(bias, "bias", (desc.O,), optional=True),
+                                        _ptr(y, "y", ys), _stream()), "cct_conv_forward_static")
 
 
 def cct_conv_backward_data(desc: ConvDesc, w, dy, dx, workspace) -> None:

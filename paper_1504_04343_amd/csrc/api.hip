@@ -5,6 +5,7 @@
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 
 #include "cct_internal.h"
 
@@ -377,6 +378,7 @@ const char* cct_strerror(int code) {
     case CCT_EWORKSPACE: return "workspace too small for one image";
     case CCT_EUNSUPPORTED: return "unsupported combination or size";
     case CCT_EHIP: return "HIP launch failed";
+    case CCT_ESCRATCH: return "one image needs more than the library's static scratch array";
     default: return "unknown error code";
   }
 }
@@ -468,18 +470,62 @@ int cct_lower(const cct_conv_desc_t* desc, cct_lowering_t lowering, const float*
                       (hipStream_t)hip_stream);
 }
 
-int cct_conv_forward(const cct_conv_desc_t* desc, const float* x, const float* w, const float* bias,
-                     float* y, void* workspace, size_t workspace_bytes, void* hip_stream) {
+}  // extern "C"
+
+// Memory of cct_conv_forward_static: one array per GPU, part of the library's code object, so it
+// exists from the moment the library is loaded on a device until the process ends.  Host code
+// must not use this name as an address; scratch_address() asks the runtime where the current
+// device's copy lives.
+static __device__ __align__(256) unsigned char scratch[CCT_STATIC_SCRATCH_BYTES];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices];  // device address of `scratch` on each GPU, filled on first use
+
+// Device address of the current device's scratch array (looked up once per device).
+int scratch_address(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) {
+    set_hip_error(e);
+    return CCT_EHIP;
+  }
+  if (dev < 0 || dev >= kMaxDevices) return CCT_EUNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr) {
+      set_hip_error(e);
+      return CCT_EHIP;
+    }
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return CCT_OK;
+}
+
+// The forward pass.  static_scratch: the workspace is the library's scratch array, whose address
+// is looked up only after every argument and size check has passed.
+int forward_on_workspace(const cct_conv_desc_t* desc, const float* x, const float* w,
+                         const float* bias, float* y, void* workspace, size_t workspace_bytes,
+                         bool static_scratch, void* hip_stream) {
   int type;
   Geom g;
   int rc = resolve(desc, CCT_PASS_FORWARD, &type, &g);
   if (rc) return rc;
-  if (!x || !w || !y || !workspace) return CCT_EINVAL;
+  if (!x || !w || !y || (!static_scratch && !workspace)) return CCT_EINVAL;
   if (reinterpret_cast<uintptr_t>(workspace) % kAlign) return CCT_EINVAL;
   const cct_conv_desc_t& d = *desc;
   Layout L;
   const long long nc = chunk_for_workspace(d, CCT_PASS_FORWARD, type, g, workspace_bytes, &L);
-  if (nc < 1) return CCT_EWORKSPACE;
+  if (nc < 1) return static_scratch ? CCT_ESCRATCH : CCT_EWORKSPACE;
+  if (static_scratch) {
+    rc = scratch_address(&workspace);
+    if (rc) return rc;
+  }
   hipStream_t st = (hipStream_t)hip_stream;
   char* ws = static_cast<char*>(workspace);
   const int bf16 = d.precision == CCT_PREC_BF16_IN_F32_ACC;
@@ -562,6 +608,21 @@ int cct_conv_forward(const cct_conv_desc_t* desc, const float* x, const float* w
   }
   (void)es;
   return CCT_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int cct_conv_forward(const cct_conv_desc_t* desc, const float* x, const float* w, const float* bias,
+                     float* y, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return forward_on_workspace(desc, x, w, bias, y, workspace, workspace_bytes, false, hip_stream);
+}
+
+int cct_conv_forward_static(const cct_conv_desc_t* desc, const float* x, const float* w,
+                            const float* bias, float* y, void* hip_stream) {
+  return forward_on_workspace(desc, x, w, bias, y, nullptr, CCT_STATIC_SCRATCH_BYTES, true,
+                              hip_stream);
 }
 
 int cct_conv_backward_data(const cct_conv_desc_t* desc, const float* w, const float* dy, float* dx,

@@ -32,7 +32,7 @@ def test_library_exports_every_declared_symbol(B):
 
 def test_strerror(B):
     assert B.strerror(0) == "ok"
-    for code in (B.EINVAL, B.EWORKSPACE, B.EUNSUPPORTED, B.EHIP, -99):
+    for code in (B.EINVAL, B.EWORKSPACE, B.EUNSUPPORTED, B.EHIP, B.ESCRATCH, -99):
         assert B.strerror(code)
 
 
@@ -197,6 +197,25 @@ def test_type2_backward_data_needs_no_inverse_lifted_matrix(B):
     s2 = B.cct_conv_workspace_bytes(B.make_desc(256, 96, 27, 27, 256, 5, 2, 2, 2, lowering=2),
                                     B.PASS_BACKWARD_DATA)
     assert s2 > 0                                  # stride 2 keeps the materialised route
+
+
+def test_static_forward_validates_on_the_host_before_touching_the_gpu(B):
+    """cct_conv_forward_static checks arguments and sizes first: these calls return without a GPU."""
+    lib = ctypes.CDLL(B.LIB_PATH)
+    fn = lib.cct_conv_forward_static
+    fn.argtypes = [ctypes.c_void_p] * 6
+    fn.restype = ctypes.c_int
+    d = B.make_desc(1, 64, 128, 128, 8, 5, 1, 2, 1, B.LOWER_TYPE1)
+    assert fn(ctypes.byref(d), None, None, None, None, None) == B.EINVAL
+    # 64 channels x 25 taps x 16384 positions x 4 bytes = 105 MB for one image: more than the array
+    need = B.cct_conv_workspace_bytes_for_chunk(d, B.PASS_FORWARD, 1)
+    assert need > B.STATIC_SCRATCH_BYTES
+    fake = ctypes.c_void_p(4096)      # never dereferenced: the size check comes first
+    assert fn(ctypes.byref(d), fake, fake, None, fake, None) == B.ESCRATCH
+    bad = B.make_desc(0, 64, 128, 128, 8, 5, 1, 2, 1)
+    assert fn(ctypes.byref(bad), fake, fake, None, fake, None) == B.EINVAL
+    text = open(os.path.join(ROOT, "include", "cct.h")).read()
+    assert re.search(r"#define\s+CCT_STATIC_SCRATCH_BYTES\s+\(32u\s*<<\s*20\)", text)
 
 
 def test_fused_backward_data_chunks_a_batch_whose_pixel_count_exceeds_31_bits(B):
