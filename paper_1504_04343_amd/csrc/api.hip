@@ -87,6 +87,7 @@ struct Layout {
   long long total = 0;
   long long ld = 0;
   int Mpad = 0, Kpad = 0;  // pack padding (TN GEMM)
+  int Kpad_kc = 0;         // fused passes: K padding of the channel-contiguous pack
   int S = 1, split_len = 0;  // NT GEMM
   int t2_opad = 0;  // Type-2 backward-data with the inverse lifting gathered by the GEMM: padded Og
 };
@@ -114,7 +115,14 @@ bool make_layout(const cct_conv_desc_t& d, int pass, int type, const Geom& g, lo
     gemm_tn_tile(g.Mr, (int)ncols, &BM, &BN, &BK);
     L->Mpad = (int)align_up(g.Mr, BM);
     L->Kpad = (int)align_up(g.Kd, BK);
-    take((long long)d.groups * L->Mpad * L->Kpad * es, &L->pack_off, &L->pack_bytes);
+    long long kp = L->Kpad;
+    if (type == CCT_LOWER_FUSED) {
+      const long long kc = conv_fused_kc_kpad(g.Cg, d.K);
+      if (kc >= kIntMax) return false;
+      L->Kpad_kc = (int)kc;
+      kp = std::max(kp, kc);
+    }
+    take((long long)d.groups * L->Mpad * kp * es, &L->pack_off, &L->pack_bytes);
     if (type != CCT_LOWER_FUSED) {  // the fused layout has no D^T
       take(dt_rows * L->ld * es, &L->dt_off, &L->dt_bytes);
       if (type != CCT_LOWER_TYPE1) take(rt_rows * L->ld * 4, &L->rt_off, &L->rt_bytes);
@@ -126,7 +134,11 @@ bool make_layout(const cct_conv_desc_t& d, int pass, int type, const Geom& g, lo
     gemm_tn_tile(g.Cg, (int)(nc * d.H * d.W), &BM, &BN, &BK);
     L->Mpad = (int)align_up(g.Cg, BM);
     L->Kpad = (int)align_up((long long)g.Og * d.K * d.K, BK);
-    take((long long)d.groups * L->Mpad * L->Kpad * 4, &L->pack_off, &L->pack_bytes);
+    const long long kc = conv_fused_kc_kpad(g.Og, d.K);
+    if (kc >= kIntMax) return false;
+    L->Kpad_kc = (int)kc;
+    take((long long)d.groups * L->Mpad * std::max<long long>(L->Kpad, kc) * 4, &L->pack_off,
+         &L->pack_bytes);
   } else if (pass == CCT_PASS_BACKWARD_DATA) {
     int BM, BN, BK;
     gemm_tn_tile(g.Kd, (int)ncols, &BM, &BN, &BK);
@@ -532,7 +544,36 @@ int forward_on_workspace(const cct_conv_desc_t* desc, const float* x, const floa
   const int es = esize(d);
   const long long P = (long long)g.Hout * g.Wout;
 
-  rc = launch_pack_kernel_matrix(w, ws + L.pack_off, make_pack(d, g, L, 0), st);
+  // the fused pass: the operand description of one chunk (lowering, multiply and lifting in one
+  // kernel: the GEMM gathers its B tiles from x)
+  auto fused_chunk = [&](const float* xc, float* yc, long long ncols, bool kc) {
+    GemmTN p;
+    std::memset(&p, 0, sizeof(p));
+    p.A = ws + L.pack_off;
+    p.Mpad = L.Mpad;
+    p.Kpad = kc ? L.Kpad_kc : L.Kpad;
+    p.a_gs = (long long)p.Mpad * p.Kpad;
+    p.B = xc;
+    p.bmap = ColMap{1, 0};  // not a plain matrix
+    p.gather = 1;
+    p.gC = d.C; p.gH = d.H; p.gW = d.W; p.gHout = g.Hout; p.gWout = g.Wout;
+    p.gs = d.stride; p.gp = d.pad; p.gCg = g.Cg; p.gK = d.K; p.gKK = d.K * d.K;
+    make_fastdiv_parts(p.gKK, &p.g_divKK_M, &p.g_divKK_sh);
+    make_fastdiv_parts(p.gK, &p.g_divK_M, &p.g_divK_sh);
+    p.M = g.Mr; p.Ncols = (int)ncols; p.Kdim = g.Kd; p.G = d.groups;
+    p.C = yc;
+    p.c_ms = P; p.c_gs = (long long)g.Og * P;
+    p.cmap = ColMap{(int)P, (long long)d.O * P};
+    p.bias = bias; p.bias_gs = g.Og;
+    return p;
+  };
+  // channel-contiguous form of the fused kernel when the shape allows it (it has its own pack)
+  const bool kc = type == CCT_LOWER_FUSED && conv_fused_kc_fits(fused_chunk(x, y, nc * g.Pc, true));
+  if (kc)
+    rc = launch_pack_fused_kc(w, reinterpret_cast<float*>(ws + L.pack_off), d.groups, g.Og, g.Cg, d.K,
+                              L.Mpad, 0, st);
+  else
+    rc = launch_pack_kernel_matrix(w, ws + L.pack_off, make_pack(d, g, L, 0), st);
   if (rc) return rc;
   for (long long n0 = 0; n0 < d.N; n0 += nc) {
     const int ni = (int)std::min<long long>(nc, d.N - n0);
@@ -540,26 +581,13 @@ int forward_on_workspace(const cct_conv_desc_t* desc, const float* x, const floa
     const float* xc = x + n0 * d.C * d.H * d.W;
     float* yc = y + n0 * d.O * P;
     if (type == CCT_LOWER_FUSED) {
-      // lowering, multiply and lifting in one kernel: the GEMM gathers its B tiles from x
-      GemmTN p;
-      std::memset(&p, 0, sizeof(p));
-      p.A = ws + L.pack_off;
-      p.a_gs = (long long)L.Mpad * L.Kpad;
-      p.Mpad = L.Mpad; p.Kpad = L.Kpad;
-      p.B = xc;
-      p.bmap = ColMap{1, 0};  // not a plain matrix
-      p.gather = 1;
-      p.gC = d.C; p.gH = d.H; p.gW = d.W; p.gHout = g.Hout; p.gWout = g.Wout;
-      p.gs = d.stride; p.gp = d.pad; p.gCg = g.Cg; p.gK = d.K; p.gKK = d.K * d.K;
-      make_fastdiv_parts(p.gKK, &p.g_divKK_M, &p.g_divKK_sh);
-      make_fastdiv_parts(p.gK, &p.g_divK_M, &p.g_divK_sh);
-      p.M = g.Mr; p.Ncols = (int)ncols; p.Kdim = g.Kd; p.G = d.groups;
-      p.C = yc;
-      p.c_ms = P; p.c_gs = (long long)g.Og * P;
-      p.cmap = ColMap{(int)P, (long long)d.O * P};
-      p.bias = bias; p.bias_gs = g.Og;
-      rc = launch_conv_fused(p, st);                            // LDS-staged lowering
-      if (rc == CCT_EUNSUPPORTED) rc = launch_gemm_tn(p, st);  // else gather-fed GEMM
+      const GemmTN p = fused_chunk(xc, yc, ncols, kc);
+      if (kc) {
+        rc = launch_conv_fused_kc(p, st);
+      } else {
+        rc = launch_conv_fused(p, st);                            // LDS-staged lowering
+        if (rc == CCT_EUNSUPPORTED) rc = launch_gemm_tn(p, st);  // else gather-fed GEMM
+      }
       if (rc) return rc;
       continue;
     }
@@ -646,17 +674,14 @@ int cct_conv_backward_data(const cct_conv_desc_t* desc, const float* w, const fl
   if (type == CCT_LOWER_FUSED) {
     // one kernel per chunk: dx = convolution of dy (O channels, Hout x Wout) with the flipped
     // kernels, stride 1, pad K-1-p; lowering of dy happens in LDS (or as a gather), never in HBM
-    rc = launch_pack_flipped(w, reinterpret_cast<float*>(ws + L.pack_off), d.groups, g.Og, g.Cg, d.K,
-                             L.Mpad, L.Kpad, st);
-    if (rc) return rc;
-    for (long long n0 = 0; n0 < d.N; n0 += nc) {
-      const long long ni = std::min<long long>(nc, d.N - n0);
+    auto fused_chunk = [&](const float* dyc, float* dxc, long long ni, bool kc) {
       GemmTN p;
       std::memset(&p, 0, sizeof(p));
       p.A = ws + L.pack_off;
-      p.a_gs = (long long)L.Mpad * L.Kpad;
-      p.Mpad = L.Mpad; p.Kpad = L.Kpad;
-      p.B = dy + n0 * d.O * P;
+      p.Mpad = L.Mpad;
+      p.Kpad = kc ? L.Kpad_kc : L.Kpad;
+      p.a_gs = (long long)p.Mpad * p.Kpad;
+      p.B = dyc;
       p.bmap = ColMap{1, 0};
       p.gather = 1;
       p.gC = d.O; p.gH = g.Hout; p.gW = g.Wout; p.gHout = d.H; p.gWout = d.W;
@@ -665,11 +690,28 @@ int cct_conv_backward_data(const cct_conv_desc_t* desc, const float* w, const fl
       make_fastdiv_parts(p.gK, &p.g_divK_M, &p.g_divK_sh);
       // make_layout accepted this chunk size only if ni*H*W fits 31 bits
       p.M = g.Cg; p.Ncols = (int)(ni * HW); p.Kdim = g.Og * d.K * d.K; p.G = d.groups;
-      p.C = dx + n0 * d.C * HW;
+      p.C = dxc;
       p.c_ms = HW; p.c_gs = (long long)g.Cg * HW;
       p.cmap = ColMap{(int)HW, (long long)d.C * HW};
-      rc = launch_conv_fused(p, st);
-      if (rc == CCT_EUNSUPPORTED) rc = launch_gemm_tn(p, st);
+      return p;
+    };
+    const bool kc = conv_fused_kc_fits(fused_chunk(dy, dx, nc, true));
+    if (kc)
+      rc = launch_pack_fused_kc(w, reinterpret_cast<float*>(ws + L.pack_off), d.groups, g.Og, g.Cg,
+                                d.K, L.Mpad, 1, st);
+    else
+      rc = launch_pack_flipped(w, reinterpret_cast<float*>(ws + L.pack_off), d.groups, g.Og, g.Cg,
+                               d.K, L.Mpad, L.Kpad, st);
+    if (rc) return rc;
+    for (long long n0 = 0; n0 < d.N; n0 += nc) {
+      const long long ni = std::min<long long>(nc, d.N - n0);
+      const GemmTN p = fused_chunk(dy + n0 * d.O * P, dx + n0 * d.C * HW, ni, kc);
+      if (kc) {
+        rc = launch_conv_fused_kc(p, st);
+      } else {
+        rc = launch_conv_fused(p, st);
+        if (rc == CCT_EUNSUPPORTED) rc = launch_gemm_tn(p, st);
+      }
       if (rc) return rc;
     }
     return CCT_OK;

@@ -104,6 +104,16 @@ bool gemm_nt_gather_fits(int C, int H, int W, int O, int Hout, int Wout);
 // Fused forward with LDS-staged lowering (p.gather must be set).  CCT_EUNSUPPORTED = the shape
 // does not fit its staging area and nothing was launched: use launch_gemm_tn instead.
 int launch_conv_fused(const GemmTN& p, hipStream_t st);
+// The same pass with channel-contiguous operands in LDS (16-byte operand reads; see
+// conv_fused_kc.hip).  It needs its own kernel pack, [group of 16 channels][tap][row][16], with
+// Kpad = conv_fused_kc_kpad(channels per group, K); `flipped` selects the flipped, role-swapped
+// kernels of the fused backward-data pass.  conv_fused_kc_fits: can it run this problem
+// (p filled as for launch_conv_fused)?
+bool conv_fused_kc_fits(const GemmTN& p);
+long long conv_fused_kc_kpad(int channels_per_group, int K);
+int launch_pack_fused_kc(const float* w, float* pack, int G, int Og, int Cg, int K, int Mpad,
+                         int flipped, hipStream_t st);
+int launch_conv_fused_kc(const GemmTN& p, hipStream_t st);
 // Fused backward-weights pass: split partial products of dy (NCHW, read in place) with the
 // Type-1 lowering of x built in LDS.  Cpart[s][q][oo][(ci,i,j)], compact, S splits of split_len
 // positions (a multiple of 32) over the nimg*Hout*Wout positions.

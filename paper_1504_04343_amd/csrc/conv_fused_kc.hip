@@ -1,0 +1,476 @@
+// Fused forward / stride-1 backward-data pass (the "Fusion" of Sec. 2.1), second form: the
+// reduction index is ordered (channel group of 16, tap, channel) and both operands are kept
+// CHANNEL-CONTIGUOUS in LDS, so that a lane fetches four reduction indices of its row / position
+// with ONE 16-byte LDS read.
+//
+// Why: on gfx950 the rate of an LDS-fed v_mfma_f32_32x32x2_f32 loop depends on how many LDS
+// instructions accompany each MFMA.  With 4-byte operand reads (one LDS instruction per MFMA)
+// a 64x64 wave tile tops out near 134 TFLOP/s; with 16-byte reads that cover four K-steps
+// (0.25 LDS instructions per MFMA) the same loop reaches 150.  The first form of this kernel
+// (conv_fused.hip) reads its B operand element by element from per-channel regions; this form
+// transposes the staged input to [cell][channel] while writing it to LDS, which costs nothing:
+// a thread already holds the 16 channels of its cells in registers and writes them as four
+// 16-byte stores instead of sixteen 4-byte ones.
+//
+// Product: C[o][pos] = sum_{grp, tap, c} K^[grp][tap][o][c] * xpad[n, grp*16 + c, r*s + i, c*s + j]
+//   - a workgroup owns BM kernels x 128 consecutive positions (output pixels of the chunk);
+//   - per channel group it stages the zero-padded input rows those positions can touch as cells
+//     (row, column) of 16 channels each, 20 floats apart (the 4 spare floats spread consecutive
+//     cells over all LDS banks for 16-byte accesses), in a two-slot ring: the global loads of
+//     group g+1 are in flight while group g is multiplied;
+//   - one K tile = one tap of one channel group = 16 reduction indices.  The B operand of a lane
+//     is the 16 channels of cell  base(position) + tap offset, the A operand the 16 channels of
+//     its kernel row; reduction index q*8 + half*4 + e goes to MFMA (q, e), lane half `half`, on
+//     both sides;
+//   - the kernel matrix comes packed as [group][tap][kernel][16 channels] (pack_fused_kc_kernel),
+//     so a K tile of it is one contiguous block that is copied to LDS with 16-byte loads and
+//     stores, double buffered;
+//   - epilogue = Type-1 lifting + bias, as in the plain GEMM.
+#include <stdio.h>
+
+#include "cct_internal.h"
+#include "gemm_common.h"
+
+namespace cct {
+namespace {
+
+constexpr int NT = 256;
+constexpr int BN = 128;
+constexpr int CG = 16;        // channels per group = reduction indices per K tile
+constexpr int CS = CG + 4;    // floats between cells / kernel rows in LDS
+constexpr int QU = 2;         // cells per thread and slot (R <= QU*256)
+constexpr int kLdsCap = 80 * 1024;  // two workgroups per CU
+
+struct KcGeom {
+  int Wp;       // padded row width W + 2*pad (cells per staged row)
+  int R;        // cells reserved per slot (multiple of 64, >= any workgroup's need)
+  int ngroups;  // channel groups of 16
+  int KK;       // taps
+  int tpi;      // > 0: column tiles never cross an image, tpi tiles per image (the last one
+                // partly empty); used when the rows of a tile that spans two images would not
+                // fit the staging area.  0: tiles are cut from the positions of the whole chunk.
+};
+
+template <int BM, int WM, int WN>
+__global__ __launch_bounds__(NT) void conv_fused_kc_f32(GemmTN p, KcGeom fg, int tiles_m,
+                                                        int tiles_n) {
+  constexpr int WAVES_N = BN / (32 * WN);
+  constexpr int WAVES_M = BM / (32 * WM);
+  static_assert(WAVES_M * WAVES_N == 4, "4 waves per workgroup");
+  constexpr int A_VECS = BM * CG / 4;
+  constexpr int A_IT = (A_VECS + NT - 1) / NT;
+  constexpr int A_BUF = BM * CS;  // floats per kernel-tile buffer
+
+  extern __shared__ __attribute__((aligned(16))) float smem[];
+  float* As = smem;                          // [2][BM][CS]
+  float* Xs = smem + 2 * A_BUF;              // [2][R][CS]
+  const int slot_floats = fg.R * CS;
+  int* tab = reinterpret_cast<int*>(Xs + 2 * slot_floats);  // [KK] tap -> float offset of the cell
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int wave_m = wave / WAVES_N, wave_n = wave % WAVES_N;
+  const int lane_lo = lane & 31, lane_hi = lane >> 5;
+
+  // consecutive workgroup ids go round-robin over the 8 XCDs: give every XCD a contiguous run of
+  // column tiles with the M tiles of one column tile next to each other (they share x through L2)
+  int bid = blockIdx.x;
+  {
+    const int total = tiles_m * tiles_n;
+    const int per = total >> 3, rem = total & 7;
+    const int xcd = bid & 7, slot = bid >> 3;
+    bid = xcd * per + min(xcd, rem) + slot;
+  }
+  const int tile_n = bid / tiles_m;
+  const int tile_m = bid - tile_n * tiles_m;
+  const int g = blockIdx.y;
+  const int m0 = tile_m * BM;
+
+  // ---- which positions, images and output rows does this workgroup cover ---------------------
+  const int P = p.gHout * p.gWout;
+  int n0, ce;  // positions [n0, ce) of the chunk
+  if (fg.tpi > 0) {
+    const int img = tile_n / fg.tpi;
+    n0 = img * P + (tile_n - img * fg.tpi) * BN;
+    ce = min(n0 + BN, (img + 1) * P);
+  } else {
+    n0 = tile_n * BN;
+    ce = min(n0 + BN, p.Ncols);
+  }
+  const int n_f = n0 / P;
+  const int a_f = (n0 - n_f * P) / p.gWout;
+  const int n_l = (ce - 1) / P;
+  const int a_l = ((ce - 1) - n_l * P) / p.gWout;
+  const int rows_first = ((n_f == n_l ? a_l : p.gHout - 1) - a_f) * p.gs + p.gK;
+  const int len_first = rows_first * fg.Wp;
+  const int len_full = ((p.gHout - 1) * p.gs + p.gK) * fg.Wp;
+  const int rows_last = n_l == n_f ? rows_first : a_l * p.gs + p.gK;
+  const int r_actual = (n_l == n_f ? 0 : len_first + (n_l - n_f - 1) * len_full) + rows_last * fg.Wp;
+
+  // cell q -> offset of its pixel inside x, relative to (first image, first channel of the
+  // group), or -1 for padding / cells past the rows this workgroup needs
+  auto src_of = [&](int q) -> long long {
+    if (q >= r_actual) return -1;
+    int seg = 0, rem = q, a_lo = a_f;
+    if (q >= len_first) {
+      const int qq = q - len_first;
+      seg = 1 + qq / len_full;
+      rem = qq - (seg - 1) * len_full;
+      a_lo = 0;
+    }
+    const int row = rem / fg.Wp, wp = rem - row * fg.Wp;
+    const int h = a_lo * p.gs + row - p.gp, w = wp - p.gp;
+    if (h < 0 || h >= p.gH || w < 0 || w >= p.gW) return -1;
+    return ((long long)seg * p.gC * p.gH + h) * p.gW + w;
+  };
+  const long long chan_stride = (long long)p.gH * p.gW;
+
+  for (int e = tid; e < fg.KK; e += NT) {
+    const int ti = e / p.gK, tj = e - ti * p.gK;
+    tab[e] = (ti * fg.Wp + tj) * CS;
+  }
+
+  // ---- staging: a thread owns cells tid + u*256 of every group.  The cell's byte offset inside
+  // the tensor never changes; dead cells get an offset that fails the buffer range check and load
+  // as zero; the channel enters through the scalar offset of the buffer load, channels past the
+  // group's last one through an empty range.  So staging 16 channels costs no vector-ALU work.
+  unsigned stg_voff[QU];
+  float stg[QU * CG];
+  const float* Xb = reinterpret_cast<const float*>(p.B) +
+                    ((long long)n_f * p.gC + (long long)g * p.gCg) * chan_stride;
+#pragma unroll
+  for (int u = 0; u < QU; ++u) {
+    const long long src = src_of(tid + u * NT);
+    stg_voff[u] = src >= 0 ? (unsigned)src * 4u : 0x80000000u;
+  }
+#define CCT_STAGE_LOAD(GIDX)                                                                \
+  {                                                                                         \
+    _Pragma("unroll") for (int u = 0; u < QU; ++u) {                                        \
+      if (tid + u * NT < fg.R) { /* whole waves: R is a multiple of 64 */                   \
+        _Pragma("unroll") for (int cc = 0; cc < CG; ++cc) {                                 \
+          const int ch = (GIDX) * CG + cc;                                                  \
+          const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(              \
+              const_cast<float*>(Xb), 0, ch < p.gCg ? 0x7fffffff : 0, 0x00020000);          \
+          stg[u * CG + cc] = __builtin_bit_cast(                                            \
+              float, __builtin_amdgcn_raw_buffer_load_b32(                                  \
+                         rs, (int)stg_voff[u], (int)((unsigned)ch * (unsigned)chan_stride * 4u), 0)); \
+        }                                                                                   \
+      }                                                                                     \
+    }                                                                                       \
+  }
+#define CCT_STAGE_STORE(SLOT)                                                               \
+  {                                                                                         \
+    _Pragma("unroll") for (int u = 0; u < QU; ++u) {                                        \
+      const int q = tid + u * NT;                                                           \
+      if (q < fg.R) {                                                                       \
+        _Pragma("unroll") for (int v = 0; v < CG / 4; ++v) {                                \
+          f32x4 val;                                                                        \
+          _Pragma("unroll") for (int e = 0; e < 4; ++e) val[e] = stg[u * CG + v * 4 + e];   \
+          *reinterpret_cast<f32x4*>(&Xs[(SLOT) * slot_floats + q * CS + v * 4]) = val;      \
+        }                                                                                   \
+      }                                                                                     \
+    }                                                                                       \
+  }
+  CCT_STAGE_LOAD(0);
+  CCT_STAGE_STORE(0);
+  if (fg.ngroups > 1) CCT_STAGE_LOAD(1);
+
+  // ---- kernel-matrix tiles: a K tile is BM*16 contiguous floats [kernel][16 channels] ----------
+  const int ktiles = fg.ngroups * fg.KK;
+  gptr_f32 Ag = (gptr_f32)(p.A) + (long long)g * p.a_gs + (long long)m0 * CG;
+  gptr_f32 a_src[A_IT];
+  int a_dst[A_IT];
+#pragma unroll
+  for (int it = 0; it < A_IT; ++it) {
+    const int v = tid + it * NT;
+    a_src[it] = Ag + v * 4;
+    a_dst[it] = (v >> 2) * CS + (v & 3) * 4;
+  }
+  const long long a_step = (long long)p.Mpad * CG;
+  f32x4 ra[A_IT];
+#define CCT_LOAD_A()                                                                        \
+  {                                                                                         \
+    _Pragma("unroll") for (int it = 0; it < A_IT; ++it) {                                   \
+      if (A_VECS % NT == 0 || tid + it * NT < A_VECS) ra[it] = *(gptr_f32x4)(a_src[it]);    \
+      a_src[it] += a_step;                                                                  \
+    }                                                                                       \
+  }
+#define CCT_STORE_A(BUF)                                                                    \
+  {                                                                                         \
+    _Pragma("unroll") for (int it = 0; it < A_IT; ++it) {                                   \
+      if (A_VECS % NT == 0 || tid + it * NT < A_VECS)                                       \
+        *reinterpret_cast<f32x4*>(&As[(BUF) * A_BUF + a_dst[it]]) = ra[it];                 \
+    }                                                                                       \
+  }
+
+  floatx16 acc[WM][WN];
+#pragma unroll
+  for (int i = 0; i < WM; ++i)
+#pragma unroll
+    for (int j = 0; j < WN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  // per-lane operand bases (float offsets): kernel row, and the cell of each owned position
+  const int am = wave_m * WM * 32 + lane_lo;
+  const int bn = wave_n * WN * 32 + lane_lo;
+  const int a_lds = am * CS + lane_hi * 4;
+  int bbase[WN];
+#pragma unroll
+  for (int j = 0; j < WN; ++j) {
+    const int col = n0 + bn + j * 32;
+    int cb = 0;
+    if (col < ce) {
+      const int n = col / P, pix = col - n * P;
+      const int r = pix / p.gWout, c = pix - r * p.gWout;
+      const int seg = n == n_f ? 0 : len_first + (n - n_f - 1) * len_full;
+      const int a_lo = n == n_f ? a_f : 0;
+      cb = seg + (r - a_lo) * p.gs * fg.Wp + c * p.gs;
+    }
+    bbase[j] = cb * CS + lane_hi * 4;
+  }
+
+  CCT_LOAD_A();
+  CCT_STORE_A(0);
+  __syncthreads();  // tap table, slot 0 and the first kernel tile are visible
+  if (ktiles > 1) CCT_LOAD_A();
+
+  // operands: [q parity][block] of four reduction indices each
+  f32x4 a[2][WM], b[2][WN];
+  int boff[WN];     // float offset of the current tile's cells (slot + tap folded in)
+#pragma unroll
+  for (int j = 0; j < WN; ++j) boff[j] = bbase[j] + tab[0];
+#pragma unroll
+  for (int i = 0; i < WM; ++i) a[0][i] = *reinterpret_cast<const f32x4*>(&As[a_lds + i * 32 * CS]);
+#pragma unroll
+  for (int j = 0; j < WN; ++j) b[0][j] = *reinterpret_cast<const f32x4*>(&Xs[boff[j]]);
+
+  int tt = 0;    // tap inside the current channel group
+  int grp = 0;   // current channel group
+  int slot = 0;  // ring slot of the current group
+  for (int t = 0; t < ktiles; ++t) {
+    const int buf = t & 1;
+    const bool more = t + 1 < ktiles;
+    int tt_n = tt + 1, grp_n = grp, slot_n = slot;
+    if (tt_n == fg.KK) {
+      tt_n = 0;
+      grp_n = grp + 1;
+      slot_n = slot ^ 1;
+    }
+    // ---- first half of the tile (reduction indices 0..7): its operands are in a[0], b[0] ------
+#pragma unroll
+    for (int i = 0; i < WM; ++i)
+      a[1][i] = *reinterpret_cast<const f32x4*>(&As[buf * A_BUF + a_lds + i * 32 * CS + 8]);
+#pragma unroll
+    for (int j = 0; j < WN; ++j) b[1][j] = *reinterpret_cast<const f32x4*>(&Xs[boff[j] + 8]);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+#pragma unroll
+      for (int i = 0; i < WM; ++i)
+#pragma unroll
+        for (int j = 0; j < WN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[0][i][e], b[0][j][e], acc[i][j], 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    if (more) {
+      // the next kernel tile (loaded one tile ago) goes to the other buffer, the loads of the
+      // tile after it are issued; last tile of a group: publish the next group's cells (their
+      // loads were issued at the group's first tile); first tile: start loading the group after
+      CCT_STORE_A(buf ^ 1);
+      if (t + 2 < ktiles) CCT_LOAD_A();
+      if (tt == fg.KK - 1 && grp + 1 < fg.ngroups) CCT_STAGE_STORE(slot ^ 1);
+      if (tt == 0 && t > 0 && grp + 1 < fg.ngroups) CCT_STAGE_LOAD(grp + 1);
+      const int tapo = tab[tt_n] + slot_n * slot_floats;
+#pragma unroll
+      for (int j = 0; j < WN; ++j) boff[j] = bbase[j] + tapo;
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    // ---- second half (indices 8..15): the barrier that publishes the next tile sits before its
+    // MFMAs, which then cover the latency of the next tile's first operand reads
+    __syncthreads();
+    if (more) {
+#pragma unroll
+      for (int i = 0; i < WM; ++i)
+        a[0][i] = *reinterpret_cast<const f32x4*>(&As[(buf ^ 1) * A_BUF + a_lds + i * 32 * CS]);
+#pragma unroll
+      for (int j = 0; j < WN; ++j) b[0][j] = *reinterpret_cast<const f32x4*>(&Xs[boff[j]]);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+#pragma unroll
+      for (int i = 0; i < WM; ++i)
+#pragma unroll
+        for (int j = 0; j < WN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[1][i][e], b[1][j][e], acc[i][j], 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    tt = tt_n;
+    grp = grp_n;
+    slot = slot_n;
+  }
+#undef CCT_LOAD_A
+#undef CCT_STORE_A
+#undef CCT_STAGE_LOAD
+#undef CCT_STAGE_STORE
+
+  // ---- epilogue: Type-1 lifting + bias (same accumulator layout as the plain GEMM) -------------
+  float* __restrict__ C = p.C + (long long)g * p.c_gs;
+  const float* bias = p.bias ? p.bias + (long long)g * p.bias_gs : nullptr;
+  const int mw = m0 + wave_m * WM * 32;
+  const bool full_m = m0 + BM <= p.M;
+#pragma unroll
+  for (int j = 0; j < WN; ++j) {
+    const int col = n0 + bn + j * 32;
+    if (col >= ce) continue;
+    float* __restrict__ cl = C + col_offset(p.cmap, col) + (long long)(mw + lane_hi * 4) * p.c_ms;
+    const float* bl = bias ? bias + mw + lane_hi * 4 : nullptr;
+#pragma unroll
+    for (int i = 0; i < WM; ++i) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = i * 32 + (r >> 2) * 8 + (r & 3);  // relative to mw + 4*lane_hi
+        if (full_m || mw + row + lane_hi * 4 < p.M) {
+          float v = acc[i][j][r];
+          if (bl) v += bl[row];
+          cl[(long long)row * p.c_ms] = v;
+        }
+      }
+    }
+  }
+}
+
+// Geometry and LDS need; false = this form cannot run the shape.
+bool make_kc_geom(const GemmTN& p, int BM, KcGeom* fg, size_t* lds) {
+  if (!p.gather || p.bf16 || p.tapmajor || p.gK < 2 || p.gCg < 1) return false;
+  fg->KK = p.gK * p.gK;
+  fg->Wp = p.gW + 2 * p.gp;
+  fg->ngroups = (p.gCg + CG - 1) / CG;
+  // channels are padded to whole groups of 16: not worth it when that wastes over an eighth
+  if ((long long)fg->ngroups * CG * 8 > (long long)p.gCg * 9) return false;
+  const long long P = (long long)p.gHout * p.gWout;
+  // rows of padded input that 128 consecutive positions can touch: at most A output rows spread
+  // over at most T images; t images need (A - t)*stride + t*K rows, largest at t = 1 or t = T
+  const long long A = (BN - 1) / p.gWout + 2, T = (BN - 1) / P + 2;
+  const long long r1 = (A - 1) * p.gs + p.gK;
+  const long long rT = (A > T ? A - T : 0) * p.gs + T * p.gK;
+  auto cells = [&](long long rows) { return (rows * fg->Wp + 63) / 64 * 64; };
+  auto lds_of = [&](long long R) { return 4LL * (2LL * BM * CS + 2LL * R * CS + fg->KK); };
+  long long R = cells(r1 > rT ? r1 : rT);
+  fg->tpi = 0;
+  if (R > QU * NT || lds_of(R) > kLdsCap) {
+    // tiles cut per image need the rows of one image only; worth it while the partly empty last
+    // tile of an image wastes less than a tenth of the launch
+    const long long tpi = (P + BN - 1) / BN;
+    const long long rows1 = (A < p.gHout ? A - 1 : p.gHout - 1) * p.gs + p.gK;
+    R = cells(rows1);
+    if (tpi * BN * 10 > P * 11 || tpi * ((double)p.Ncols / P) >= 2147483647.0) return false;
+    fg->tpi = (int)tpi;
+  }
+  if (R > QU * NT) return false;
+  fg->R = (int)R;
+  // staged cells are addressed with 32-bit byte offsets from the workgroup's first image
+  if ((T + 1) * p.gC * p.gH * p.gW >= (1LL << 29)) return false;
+  const long long need = lds_of(R);
+  if (need > kLdsCap) return false;
+  *lds = (size_t)need;
+  return true;
+}
+
+template <int BM, int WM, int WN>
+int launch_variant(const GemmTN& p, const KcGeom& fg, size_t lds, hipStream_t st) {
+  const int tiles_m = p.Mpad / BM;
+  const long long tn = fg.tpi > 0 ? (long long)fg.tpi * (p.Ncols / (p.gHout * p.gWout))
+                                  : ((long long)p.Ncols + BN - 1) / BN;
+  const long long blocks = (long long)tiles_m * tn;
+  if (blocks <= 0 || blocks >= 2147483647LL || p.G > 65535) return CCT_EUNSUPPORTED;
+  const int tiles_n = (int)tn;
+  dim3 grid((unsigned)blocks, (unsigned)p.G);
+  char name[96];
+  snprintf(name, sizeof(name), "conv_fused_kc_f32<%d, %d, %d>", BM, WM, WN);
+  const double x_bytes = 4.0 * ((double)p.Ncols / (p.gHout * p.gWout)) * p.gC * p.gH * p.gW;
+  ProfScope ps(name, 2.0 * p.M * p.Ncols * p.Kdim * p.G,
+               x_bytes + 4.0 * ((double)p.M * p.Ncols + (double)p.M * p.Kdim) * p.G, st);
+  constexpr auto kern = conv_fused_kc_f32<BM, WM, WN>;
+  if (const int rc = ensure_dynamic_lds<kern>(kLdsCap)) return rc;
+  hipLaunchKernelGGL(kern, grid, dim3(NT), lds, st, p, fg, tiles_m, tiles_n);
+  CCT_CHECK_LAUNCH();
+  return CCT_OK;
+}
+
+// pack[q][grp][tap][m][c] (c < 16), zero padded in m (to Mpad) and c (to whole groups).
+//   forward (flipped == 0): m = kernel oo < Og,  channel = input channel ci < Cg,
+//                           value w[q*Og + m, grp*16 + c, i, j],            tap = i*K + j
+//   backward-data (flipped): m = input channel ci < Cg, channel = kernel oo < Og,
+//                           value w[q*Og + grp*16 + c, m, K-1-i, K-1-j],    tap = i*K + j
+__global__ __launch_bounds__(256) void pack_fused_kc_kernel(const float* __restrict__ w,
+                                                            float* __restrict__ pack, int G, int Og,
+                                                            int Cg, int K, int Mpad, int ngroups,
+                                                            int flipped) {
+  const int KK = K * K;
+  const long long per_group = (long long)ngroups * KK * Mpad * CG;
+  const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (t >= per_group * G) return;
+  const int q = (int)(t / per_group);
+  long long e = t - q * per_group;
+  const int c = (int)(e % CG);
+  e /= CG;
+  const int m = (int)(e % Mpad);
+  e /= Mpad;
+  const int tap = (int)(e % KK), grp = (int)(e / KK);
+  const int i = tap / K, j = tap - i * K;
+  const int ch = grp * CG + c;
+  float v = 0.0f;
+  if (!flipped) {
+    if (m < Og && ch < Cg) v = w[((((long long)q * Og + m) * Cg + ch) * K + i) * K + j];
+  } else {
+    if (m < Cg && ch < Og)
+      v = w[((((long long)q * Og + ch) * Cg + m) * K + (K - 1 - i)) * K + (K - 1 - j)];
+  }
+  pack[t] = v;
+}
+
+}  // namespace
+
+bool conv_fused_kc_fits(const GemmTN& p) {
+  int BM, BNt, BKt;
+  gemm_tn_tile(p.M, p.Ncols, &BM, &BNt, &BKt);
+  KcGeom fg;
+  size_t lds;
+  return BNt == BN && make_kc_geom(p, BM, &fg, &lds);
+}
+
+long long conv_fused_kc_kpad(int channels_per_group, int K) {
+  return (long long)((channels_per_group + CG - 1) / CG) * CG * K * K;
+}
+
+int launch_pack_fused_kc(const float* w, float* pack, int G, int Og, int Cg, int K, int Mpad,
+                         int flipped, hipStream_t st) {
+  const int ngroups = ((flipped ? Og : Cg) + CG - 1) / CG;
+  const long long total = (long long)G * ngroups * K * K * Mpad * CG;
+  const long long blocks = (total + 255) / 256;
+  if (blocks <= 0 || blocks >= 2147483647LL) return CCT_EUNSUPPORTED;
+  ProfScope ps("pack_fused_kc_kernel", 0.0, 4.0 * G * Og * Cg * K * K + 4.0 * total, st);
+  hipLaunchKernelGGL(pack_fused_kc_kernel, dim3((unsigned)blocks), dim3(256), 0, st, w, pack, G, Og,
+                     Cg, K, Mpad, ngroups, flipped);
+  CCT_CHECK_LAUNCH();
+  return CCT_OK;
+}
+
+// p.A must have been written by launch_pack_fused_kc; p.Kpad = conv_fused_kc_kpad(...).
+int launch_conv_fused_kc(const GemmTN& p0, hipStream_t st) {
+  GemmTN p = p0;
+  colmap_prepare(&p.bmap);
+  colmap_prepare(&p.cmap);
+  int BM, BNt, BKt;
+  gemm_tn_tile(p.M, p.Ncols, &BM, &BNt, &BKt);
+  KcGeom fg;
+  size_t lds;
+  if (BNt != BN || p.Mpad % BM || !make_kc_geom(p, BM, &fg, &lds)) return CCT_EUNSUPPORTED;
+  if (p.Kpad != (long long)fg.ngroups * CG * fg.KK) return CCT_EINVAL;
+  if (BM == 64) return launch_variant<64, 1, 2>(p, fg, lds, st);
+  if (BM == 96) return launch_variant<96, 3, 1>(p, fg, lds, st);
+  return launch_variant<128, 2, 2>(p, fg, lds, st);
+}
+
+}  // namespace cct
