@@ -264,28 +264,36 @@ __global__ __launch_bounds__(NT) void conv_fused_kc_f32(GemmTN p, KcGeom fg, int
       a[1][i] = *reinterpret_cast<const f32x4*>(&As[buf * A_BUF + a_lds + i * 32 * CS + 8]);
 #pragma unroll
     for (int j = 0; j < WN; ++j) b[1][j] = *reinterpret_cast<const f32x4*>(&Xs[boff[j] + 8]);
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int e = 0; e < 4; ++e)
-#pragma unroll
-      for (int i = 0; i < WM; ++i)
-#pragma unroll
-        for (int j = 0; j < WN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[0][i][e], b[0][j][e], acc[i][j], 0, 0, 0);
-    __builtin_amdgcn_sched_barrier(0);
+    // The workgroup's other per-tile duties are issued BETWEEN the four MFMA groups of this half,
+    // not after them: a wave issues in order, so whatever follows the last MFMA of a group goes
+    // out while that MFMA still occupies the matrix pipe, whereas work placed after all sixteen
+    // would run with the wave's MFMA queue empty.
+#define CCT_MFMA_GROUP(SET, E)                                                              \
+  {                                                                                         \
+    __builtin_amdgcn_sched_barrier(0);                                                      \
+    _Pragma("unroll") for (int i = 0; i < WM; ++i)                                          \
+      _Pragma("unroll") for (int j = 0; j < WN; ++j)                                        \
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[SET][i][E], b[SET][j][E],        \
+                                                         acc[i][j], 0, 0, 0);               \
+    __builtin_amdgcn_sched_barrier(0);                                                      \
+  }
+    CCT_MFMA_GROUP(0, 0);
+    // the next kernel tile (loaded one tile ago) goes to the other buffer
+    if (more) CCT_STORE_A(buf ^ 1);
+    CCT_MFMA_GROUP(0, 1);
+    // the loads of the tile after it
+    if (t + 2 < ktiles) CCT_LOAD_A();
+    CCT_MFMA_GROUP(0, 2);
     if (more) {
-      // the next kernel tile (loaded one tile ago) goes to the other buffer, the loads of the
-      // tile after it are issued; last tile of a group: publish the next group's cells (their
-      // loads were issued at the group's first tile); first tile: start loading the group after
-      CCT_STORE_A(buf ^ 1);
-      if (t + 2 < ktiles) CCT_LOAD_A();
+      // last tile of a group: publish the next group's cells (their loads were issued at the
+      // group's first tile); first tile of a group: start loading the group after it
       if (tt == fg.KK - 1 && grp + 1 < fg.ngroups) CCT_STAGE_STORE(slot ^ 1);
       if (tt == 0 && t > 0 && grp + 1 < fg.ngroups) CCT_STAGE_LOAD(grp + 1);
       const int tapo = tab[tt_n] + slot_n * slot_floats;
 #pragma unroll
       for (int j = 0; j < WN; ++j) boff[j] = bbase[j] + tapo;
     }
-    __builtin_amdgcn_sched_barrier(0);
+    CCT_MFMA_GROUP(0, 3);
     // ---- second half (indices 8..15): the barrier that publishes the next tile sits before its
     // MFMAs, which then cover the latency of the next tile's first operand reads
     __syncthreads();
@@ -296,19 +304,15 @@ __global__ __launch_bounds__(NT) void conv_fused_kc_f32(GemmTN p, KcGeom fg, int
 #pragma unroll
       for (int j = 0; j < WN; ++j) b[0][j] = *reinterpret_cast<const f32x4*>(&Xs[boff[j]]);
     }
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int e = 0; e < 4; ++e)
-#pragma unroll
-      for (int i = 0; i < WM; ++i)
-#pragma unroll
-        for (int j = 0; j < WN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[1][i][e], b[1][j][e], acc[i][j], 0, 0, 0);
-    __builtin_amdgcn_sched_barrier(0);
+    CCT_MFMA_GROUP(1, 0);
+    CCT_MFMA_GROUP(1, 1);
+    CCT_MFMA_GROUP(1, 2);
+    CCT_MFMA_GROUP(1, 3);
     tt = tt_n;
     grp = grp_n;
     slot = slot_n;
   }
+#undef CCT_MFMA_GROUP
 #undef CCT_LOAD_A
 #undef CCT_STORE_A
 #undef CCT_STAGE_LOAD
