@@ -292,23 +292,27 @@ __global__ __launch_bounds__(NT, 3) void conv_bwdw_fused_f32(ConvBwdW p, BwdwGeo
 #pragma unroll
         for (int e = 0; e < 4; ++e) pb[e] = v[e];
       }
-      __builtin_amdgcn_sched_barrier(0);
+      // In the step that also moves the next chunk, the LDS stores and the global loads are
+      // issued between the MFMA groups (a wave issues in order: what follows an MFMA goes out
+      // while that MFMA occupies the matrix pipe), not after all sixteen.
 #pragma unroll
-      for (int e = 0; e < 4; ++e)
+      for (int e = 0; e < 4; ++e) {
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < WM; ++i)
 #pragma unroll
           for (int j = 0; j < WN; ++j)
             acc[i][j] =
                 __builtin_amdgcn_mfma_f32_32x32x2f32(a[cur][i][e], b[cur][j][e], acc[i][j], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (q == QS / 2 - 1 && more) {
+          if (e == 0) CCT_BW_STORE(buf ^ 1);
+          if (e == 1 && t + 2 < ktiles) CCT_BW_LOAD(col_begin + (t + 2) * BK, ts2);
+        }
+      }
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int e = 0; e < 4; ++e) pa[e] = pb[e];
-      if (q == QS / 2 - 1 && more) {
-        CCT_BW_STORE(buf ^ 1);
-        if (t + 2 < ktiles) CCT_BW_LOAD(col_begin + (t + 2) * BK, ts2);
-        __builtin_amdgcn_sched_barrier(0);
-      }
     }
     const int ts = ts0;
     ts0 = ts1;
