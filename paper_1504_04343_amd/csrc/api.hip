@@ -231,8 +231,16 @@ double model_cost(const cct_conv_desc_t& d, int pass, int type) {
   const double dt_elems = (double)d.C * g.DKi * g.DKj * cols;
   const double rt_elems = (double)d.O * g.RKi * g.RKj * cols;
   double gemm_flops = 2.0 * cols * (double)g.Mr * (double)g.Kd * d.groups;
-  // small M or K dimensions run the matrix cores below their sustained rate
-  auto eff = [](double dim) { return std::min(1.0, dim / 128.0); };
+  // Row-tile efficiency of the GEMM family: the launchers cut the rows into tiles of 64 (up to
+  // 64 rows), 96 (multiples of 96 that are not multiples of 128) or 128; rows beyond the true
+  // count are wasted work, and the narrower tiles run their MFMAs below the 128-row tile's rate
+  // (measured: about 0.8 for 64 rows, 0.95 for 96).
+  auto eff = [](double dim) {
+    const long long m = (long long)dim;
+    const double tile = m <= 64 ? 64.0 : ((m % 128 != 0 && m % 96 == 0) ? 96.0 : 128.0);
+    const double speed = tile == 64.0 ? 0.8 : (tile == 96.0 ? 0.95 : 1.0);
+    return dim / (std::ceil(dim / tile) * tile) * speed;
+  };
   auto short_k = [](double k) { return std::min(1.0, std::max(0.25, k / 64.0)); };
   // a GEMM with fewer than ~2 workgroups (128 x 128 tiles) per CU cannot fill the chip
   auto fill = [&](double rows, double ncols) {
@@ -260,9 +268,7 @@ double model_cost(const cct_conv_desc_t& d, int pass, int type) {
     const double pos = N * d.H * d.W;
     gemm_bytes = x_bytes + y_bytes;
     gemm_flops = 2.0 * pos * (double)g.Cg * (double)g.Og * d.K * d.K * d.groups;
-    const double mt = g.Cg <= 64 ? 64.0 : ((g.Cg % 128 != 0 && g.Cg % 96 == 0) ? 96.0 : 128.0);
-    const double util = g.Cg / (std::ceil(g.Cg / mt) * mt);  // tiles of 64 / 96 / 128 rows
-    rate *= kFusedGemmFactor * util * fill(g.Cg, pos);
+    rate *= kFusedGemmFactor * eff(g.Cg) * fill(g.Cg, pos);
   } else if (pass == CCT_PASS_BACKWARD_DATA) {
     if (type == CCT_LOWER_TYPE1 || (type == CCT_LOWER_TYPE2 && d.stride == 1 && es == 4.0)) {
       gemm_bytes += y_bytes;                     // GEMM reads (Type 2: gathers) dy in place

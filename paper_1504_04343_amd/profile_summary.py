@@ -17,11 +17,25 @@ FETCH_SIZE / WRITE_SIZE in MiB (the counters count KiB).
 """
 import collections
 import csv
+import hashlib
+import os
 import re
 import sys
 
 SIMDS = 1024      # MI355X: 256 CUs x 4 SIMDs
 XCDS = 8          # GRBM_GUI_ACTIVE is reported summed over the 8 XCDs
+
+
+def kernel_sources_digest():
+    """Short hash of the kernel sources (csrc/*.hip, *.h): a counter profile is only quoted for
+    the code it was taken from."""
+    h = hashlib.sha256()
+    d = os.path.join(os.path.dirname(os.path.abspath(__file__)), "csrc")
+    for name in sorted(os.listdir(d)):
+        if name.endswith((".hip", ".h")):
+            h.update(name.encode())
+            h.update(open(os.path.join(d, name), "rb").read())
+    return h.hexdigest()[:12]
 
 
 def short(name):
@@ -82,6 +96,7 @@ def traffic(fetch_csv, write_csv):
         sys.exit("no %s dispatch in the runs: use bench.py --copy-calibration" % cal)
     gib_kib = float(1 << 20)
     fs, ws = gib_kib / fetch[cal], gib_kib / write[cal]
+    print("# kernel sources digest: %s" % kernel_sources_digest())
     print("# HBM traffic per dispatch = FETCH_SIZE*%.4f + WRITE_SIZE*%.4f KiB (scales from the 1 GiB "
           "%s: FETCH_SIZE read %.0f KiB, WRITE_SIZE read %.0f KiB)" % (fs, ws, cal, fetch[cal], write[cal]))
     print("# kernel<TAB>bytes_per_dispatch<TAB>dispatches<TAB>fetch_MiB_scaled<TAB>write_MiB_scaled")

@@ -8,7 +8,7 @@ from paper_1504_04343_amd import synth
 from gpu_util import desc_of, dev
 
 pytestmark = pytest.mark.gpu
-REGRET = 0.30      # picked layout may be at most 30 % slower than the best measured one
+REGRET = 0.10      # picked layout may be at most 10 % slower than the best measured one
 
 
 @pytest.fixture(scope="module")
@@ -19,7 +19,7 @@ def B():
     return binding
 
 
-def time_pass(B, L, lowering, pass_, reps=5):
+def time_pass(B, L, lowering, pass_, reps=7):
     import torch
     d = desc_of(B, L, lowering)
     x, w, b = dev(synth.make_x(L)), dev(synth.make_w(L)), dev(synth.make_bias(L))
@@ -36,16 +36,17 @@ def time_pass(B, L, lowering, pass_, reps=5):
             B.cct_conv_backward_weights(d, x, dy, dw, db, ws)
 
     run()
+    run()
     torch.cuda.synchronize()
-    best = float("inf")
+    times = []
     for _ in range(reps):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
         run()
         e1.record()
         torch.cuda.synchronize()
-        best = min(best, e0.elapsed_time(e1))
-    return best
+        times.append(e0.elapsed_time(e1))
+    return sorted(times)[len(times) // 2]          # median
 
 
 def measured(B, L, pass_=0):
@@ -63,7 +64,7 @@ def measured(B, L, pass_=0):
 
 
 @pytest.mark.parametrize("pass_", [0, 1, 2], ids=["forward", "backward_data", "backward_weights"])
-@pytest.mark.parametrize("L", synth.caffenet(64), ids=lambda L: L.name)
+@pytest.mark.parametrize("L", synth.caffenet(256), ids=lambda L: L.name)
 def test_regret_on_caffenet_layers(B, L, pass_):
     times = measured(B, L, pass_)
     pick = B.cct_pick_lowering(desc_of(B, L), pass_)
@@ -72,7 +73,7 @@ def test_regret_on_caffenet_layers(B, L, pass_):
 
 
 def test_measured_winner_follows_channel_ratio(B):
-    sweep = [L.with_batch(32) for L in synth.tradeoff_sweep() if L.K == 3]
+    sweep = [L for L in synth.tradeoff_sweep() if L.K == 3]           # batch 128, as the study names it
     winners = {}
     for L in sweep:
         times = measured(B, L)
