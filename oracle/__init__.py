@@ -5,6 +5,9 @@ Thin ctypes binding over ``conv_oracle.c`` (plain C, fp64 accumulation).  Only
 ``bench.py`` may import this package; the product path never does, and this
 package imports nothing from the HIP path.
 
+``layers_oracle.c`` holds the rectified linear unit and max pooling (Caffe's definitions), the
+two layers between CaffeNet's convolutions.
+
 Part A is the direct definition (eq. (1) of the paper plus Caffe-style stride /
 pad / groups / bias) and its two adjoints; Part B is the paper's three lowerings
 (Sec. 2.1) executed as lower -> multiply -> lift.  See the header of
@@ -20,15 +23,16 @@ from dataclasses import dataclass
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRC = os.path.join(_HERE, "conv_oracle.c")
+_SRCS = [os.path.join(_HERE, "conv_oracle.c"), os.path.join(_HERE, "layers_oracle.c")]
 _LIB = os.path.join(_HERE, "liboracle.so")
 
 
 def build(force: bool = False) -> str:
-    """Compile conv_oracle.c with gcc (-O2 -fopenmp) into liboracle.so."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+    """Compile conv_oracle.c and layers_oracle.c with gcc (-O2 -fopenmp) into liboracle.so."""
+    if force or not os.path.exists(_LIB) or \
+            os.path.getmtime(_LIB) < max(os.path.getmtime(s) for s in _SRCS):
         cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c99", "-Wall", "-Wextra",
-               "-o", _LIB, _SRC]
+               "-o", _LIB] + _SRCS
         subprocess.run(cmd, check=True)
     return _LIB
 
@@ -251,3 +255,73 @@ def conv_forward_lowered(d: Dims, lowering: int, x, w, bias=None) -> np.ndarray:
     """The paper's route: lower, multiply, lift."""
     return lift(d, lowering, multiply(d, lowering, lower_data(d, lowering, x),
                                       lower_kernel(d, lowering, w)), bias)
+
+
+# ---- the layers between the convolutions: ReLU and max pooling (layers_oracle.c) ----------
+
+class _Pool(ctypes.Structure):
+    _fields_ = [(k, ctypes.c_int) for k in ("N", "C", "H", "W", "K", "stride", "pad")]
+
+
+@dataclass(frozen=True)
+class PoolDims:
+    """Max pooling over K x K windows of an N x C x H x W tensor (Caffe's output-size rule)."""
+    N: int
+    C: int
+    H: int
+    W: int
+    K: int
+    stride: int
+    pad: int = 0
+
+    def _c(self) -> _Pool:
+        return _Pool(self.N, self.C, self.H, self.W, self.K, self.stride, self.pad)
+
+
+def pool_output_dims(d: PoolDims):
+    ho, wo = ctypes.c_int(), ctypes.c_int()
+    _check(_load().oracle_pool_output_dims(ctypes.byref(d._c()), ctypes.byref(ho), ctypes.byref(wo)),
+           "pool_output_dims")
+    return ho.value, wo.value
+
+
+def relu_forward(x) -> np.ndarray:
+    x = _f32(x)
+    y = np.empty_like(x)
+    _check(_load().oracle_relu_forward(_p(x, ctypes.c_float), _p(y, ctypes.c_float),
+                                       ctypes.c_int64(x.size)), "relu_forward")
+    return y
+
+
+def relu_backward(x, dy) -> np.ndarray:
+    x, dy = _f32(x), _f32(dy)
+    _expect(dy, x.shape, "dy")
+    dx = np.empty_like(x)
+    _check(_load().oracle_relu_backward(_p(x, ctypes.c_float), _p(dy, ctypes.c_float),
+                                        _p(dx, ctypes.c_float), ctypes.c_int64(x.size)), "relu_backward")
+    return dx
+
+
+def maxpool_forward(d: PoolDims, x):
+    """(y, argmax): fp32 values and int32 plane indices h*W + w of the chosen pixels."""
+    x = _f32(x)
+    _expect(x, (d.N, d.C, d.H, d.W), "x")
+    ho, wo = pool_output_dims(d)
+    y = np.empty((d.N, d.C, ho, wo), np.float32)
+    am = np.empty((d.N, d.C, ho, wo), np.int32)
+    _check(_load().oracle_maxpool_forward(ctypes.byref(d._c()), _p(x, ctypes.c_float),
+                                          _p(y, ctypes.c_float), _p(am, ctypes.c_int32)), "maxpool_forward")
+    return y, am
+
+
+def maxpool_backward(d: PoolDims, dy, argmax) -> np.ndarray:
+    dy = _f32(dy)
+    argmax = np.ascontiguousarray(argmax, np.int32)
+    ho, wo = pool_output_dims(d)
+    _expect(dy, (d.N, d.C, ho, wo), "dy")
+    _expect(argmax, (d.N, d.C, ho, wo), "argmax")
+    dx = np.empty((d.N, d.C, d.H, d.W), np.float32)
+    _check(_load().oracle_maxpool_backward(ctypes.byref(d._c()), _p(dy, ctypes.c_float),
+                                           _p(argmax, ctypes.c_int32), _p(dx, ctypes.c_float)),
+           "maxpool_backward")
+    return dx

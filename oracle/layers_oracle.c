@@ -1,0 +1,119 @@
+/*
+ * CPU oracle for the two layers that sit between CaffeNet's convolutional layers: the rectified
+ * linear unit and max pooling.  TEST INFRASTRUCTURE ONLY: nothing in the product path may call
+ * this file, and it shares no code with the GPU path.
+ *
+ * The paper names these layers only collectively (Sec. 1: all layers are optimised with the
+ * same techniques, and every layer's output matches Caffe's); their definitions are Caffe's:
+ *
+ *   ReLU      y = max(x, 0);   dx = dy where x > 0, else 0  (the test on x and on y agree).
+ *   max pool  y[n,c,r,q] = max over the K x K window whose top-left corner is
+ *             (r*s - p, q*s - p), clipped to the image; output size
+ *             ceil((H + 2p - K)/s) + 1, minus one if the last window would start beyond the
+ *             image (only possible with padding).  The position of the maximum is the FIRST one
+ *             in row-major scan order of the window (strict > when scanning); the backward pass
+ *             routes dy[n,c,r,q] to that position and sums where windows overlap.
+ *
+ * Plain loops, one output at a time, exact (comparisons and copies of fp32 values; the backward
+ * sum of the few overlapping windows is done in fp64).
+ *
+ * Pins (tests/test_oracle_pins.py): values worked out by hand, the output-size law at CaffeNet's
+ * 55 -> 27 and 27 -> 13, torch's CPU max_pool2d (ceil mode) and its autograd on tie-free data,
+ * the tie rule on a constant image.
+ */
+#include <stdint.h>
+#include <stddef.h>
+#include <stdlib.h>
+
+typedef struct {
+  int N, C, H, W, K, stride, pad;
+} oracle_pool_t;
+
+static int pool_ok(const oracle_pool_t* d) {
+  return d && d->N > 0 && d->C > 0 && d->H > 0 && d->W > 0 && d->K > 0 && d->stride > 0 &&
+         d->pad >= 0 && d->pad < d->K;
+}
+
+static int pool_out(int in, int K, int s, int p) {
+  int t = in + 2 * p - K;
+  int o;
+  if (t < 0) t = 0;
+  o = (t + s - 1) / s + 1;
+  if (p > 0 && (o - 1) * s >= in + p) --o;
+  return o;
+}
+
+int oracle_pool_output_dims(const oracle_pool_t* d, int* Hout, int* Wout) {
+  if (!pool_ok(d) || !Hout || !Wout) return -1;
+  *Hout = pool_out(d->H, d->K, d->stride, d->pad);
+  *Wout = pool_out(d->W, d->K, d->stride, d->pad);
+  return 0;
+}
+
+int oracle_relu_forward(const float* x, float* y, int64_t n) {
+  if (!x || !y || n < 0) return -1;
+  for (int64_t i = 0; i < n; ++i) y[i] = x[i] > 0.0f ? x[i] : 0.0f;
+  return 0;
+}
+
+int oracle_relu_backward(const float* x, const float* dy, float* dx, int64_t n) {
+  if (!x || !dy || !dx || n < 0) return -1;
+  for (int64_t i = 0; i < n; ++i) dx[i] = x[i] > 0.0f ? dy[i] : 0.0f;
+  return 0;
+}
+
+/* y: N*C*Hout*Wout floats; argmax (nullable): index h*W + w of the chosen pixel in its plane. */
+int oracle_maxpool_forward(const oracle_pool_t* d, const float* x, float* y, int32_t* argmax) {
+  int Ho, Wo;
+  if (oracle_pool_output_dims(d, &Ho, &Wo) || !x || !y) return -1;
+  for (int64_t pl = 0; pl < (int64_t)d->N * d->C; ++pl) {
+    const float* xp = x + pl * d->H * d->W;
+    for (int r = 0; r < Ho; ++r)
+      for (int q = 0; q < Wo; ++q) {
+        int h0 = r * d->stride - d->pad, w0 = q * d->stride - d->pad;
+        int h1 = h0 + d->K, w1 = w0 + d->K;
+        int best = -1;
+        float bv = 0.0f;
+        if (h0 < 0) h0 = 0;
+        if (w0 < 0) w0 = 0;
+        if (h1 > d->H) h1 = d->H;
+        if (w1 > d->W) w1 = d->W;
+        for (int h = h0; h < h1; ++h)
+          for (int w = w0; w < w1; ++w) {
+            const float v = xp[h * d->W + w];
+            if (best < 0 || v > bv) {
+              bv = v;
+              best = h * d->W + w;
+            }
+          }
+        y[(pl * Ho + r) * Wo + q] = bv;
+        if (argmax) argmax[(pl * Ho + r) * Wo + q] = best;
+      }
+  }
+  return 0;
+}
+
+/* dx[n,c,h,w] = sum of dy over the windows whose argmax is (h,w): every window adds its dy to
+ * the pixel it chose (fp64 accumulator per pixel, windows visited in row-major order). */
+int oracle_maxpool_backward(const oracle_pool_t* d, const float* dy, const int32_t* argmax, float* dx) {
+  int Ho, Wo;
+  double* acc;
+  if (oracle_pool_output_dims(d, &Ho, &Wo) || !dy || !argmax || !dx) return -1;
+  acc = (double*)malloc(sizeof(double) * (size_t)d->H * d->W);
+  if (!acc) return -1;
+  for (int64_t pl = 0; pl < (int64_t)d->N * d->C; ++pl) {
+    for (int t = 0; t < d->H * d->W; ++t) acc[t] = 0.0;
+    for (int r = 0; r < Ho; ++r)
+      for (int q = 0; q < Wo; ++q) {
+        const int32_t a = argmax[(pl * Ho + r) * Wo + q];
+        if (a < 0 || a >= d->H * d->W) {
+          free(acc);
+          return -1;
+        }
+        acc[a] += (double)dy[(pl * Ho + r) * Wo + q];
+      }
+    for (int t = 0; t < d->H * d->W; ++t) dx[pl * d->H * d->W + t] = (float)acc[t];
+  }
+  free(acc);
+  return 0;
+}

@@ -47,14 +47,17 @@ __device__ __forceinline__ void inv_lift_rows(const WinMap& m, const FastDiv& di
   *t_hi = min(m.Ht - 1, fdiv(a_hi + m.ph, divSh));
 }
 
-// Column assignment inside a workgroup: consecutive lanes own consecutive columns (CPT = 1 for
-// fp32 output, 2 for bf16 so that every lane still stores 4 bytes), which makes the LDS reads of
-// a tap bank-conflict free and the global stores of a wave one contiguous run.
-template <bool BF16>
+// Column assignment inside a workgroup: a lane owns CPT consecutive columns and consecutive lanes
+// own consecutive groups, so the global stores of a wave are one contiguous run (4, or with the
+// four-column fp32 form of lower_kernel 16, bytes per lane).  The LDS reads of that form hit the
+// banks four at a time, which does not matter for a kernel bound by its HBM write stream.
+template <bool BF16, int CPT>
 __device__ __forceinline__ void store_run(void* base, long long idx, const float* v) {
   if (BF16) {
     reinterpret_cast<unsigned*>(reinterpret_cast<unsigned short*>(base) + idx)[0] =
         (unsigned)f32_to_bf16_rne(v[0]) | ((unsigned)f32_to_bf16_rne(v[1]) << 16);
+  } else if (CPT == 4) {
+    *reinterpret_cast<float4*>(reinterpret_cast<float*>(base) + idx) = make_float4(v[0], v[1], v[2], v[3]);
   } else {
     reinterpret_cast<float*>(base)[idx] = v[0];
   }
@@ -68,7 +71,9 @@ __global__ __launch_bounds__(TPB) void lower_kernel(const float* __restrict__ x,
   extern __shared__ float tile[];
   constexpr int NTH = TPB;
   constexpr int NCB = NTH * VC;        // columns per workgroup
-  constexpr int CPT = BF16 ? 2 : 1;    // consecutive columns per lane
+  // consecutive columns per lane: 4 (one 16-byte store per tap row) when a thread has 4 columns,
+  // 2 in bf16 mode (one 4-byte store); else 1
+  constexpr int CPT = BF16 ? 2 : (VC == 4 ? 4 : 1);
   constexpr int EG = VC / CPT;         // column groups per thread
   static_assert(VC % CPT == 0, "columns per thread");
   const int tid = threadIdx.x;
@@ -177,7 +182,7 @@ __global__ __launch_bounds__(TPB) void lower_kernel(const float* __restrict__ x,
 #pragma unroll
       for (int e = 0; e < EG; ++e) {
         const int c0 = cb + (e * NTH + tid) * CPT;
-        if (c0 < ld) store_run<BF16>(dt, rbase + c0, &v[e * CPT]);
+        if (c0 < ld) store_run<BF16, CPT>(dt, rbase + c0, &v[e * CPT]);
       }
     }
   }
@@ -280,7 +285,7 @@ __global__ __launch_bounds__(TPB) void inv_lift_kernel(const float* __restrict__
 #pragma unroll
       for (int e = 0; e < EG; ++e) {
         const int c0 = cb + (e * NTH + tid) * CPT;
-        if (c0 < ld) store_run<BF16>(drt, rbase + c0, &v[e * CPT]);
+        if (c0 < ld) store_run<BF16, CPT>(drt, rbase + c0, &v[e * CPT]);
       }
     }
   }

@@ -7,6 +7,18 @@
 namespace cct {
 namespace {
 
+// Consecutive workgroup ids are dealt round-robin to the 8 XCDs, each with an L2 of its own.
+// Neighbouring runs of output elements read neighbouring (often line-sharing) stretches of the
+// matrix rows, so the kernels below renumber their workgroups: every XCD gets one contiguous
+// range of runs and walks it in order, and a cache line that two neighbouring runs share is
+// fetched from HBM once instead of once per XCD.
+__device__ __forceinline__ int xcd_contiguous_block() {
+  const int total = gridDim.x;
+  const int per = total >> 3, rem = total & 7;
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  return xcd * per + min(xcd, rem) + slot;
+}
+
 // ---------------------------------------------------------------------------------------
 // Lifting phase fused with the bias add.  Each thread produces VEC consecutive output
 // elements (one 16-byte store); for a fixed tap the lanes of a wave read consecutive
@@ -19,7 +31,7 @@ __global__ __launch_bounds__(TPB) void lift_kernel(const float* __restrict__ rt,
                                                    const float* __restrict__ bias, int total, int O,
                                                    WinMap m, FastDiv divWt, FastDiv divPl,
                                                    FastDiv divO) {
-  const int t0 = (blockIdx.x * TPB + threadIdx.x) * VEC;   // total < 2^31 checked by the launcher
+  const int t0 = (xcd_contiguous_block() * TPB + threadIdx.x) * VEC;   // total < 2^31 checked by the launcher
   if (t0 >= total) return;
   const long long kk = (long long)m.Ki * m.Kj;
   const int PcG = m.Ha * m.Wb;
@@ -84,7 +96,7 @@ __global__ __launch_bounds__(TPB) void inv_lower_kernel(const float* __restrict_
                                                         float* __restrict__ dx, int total, int C,
                                                         WinMap m, FastDiv divWt, FastDiv divPl,
                                                         FastDiv divC, FastDiv divSh, FastDiv divSw) {
-  const int t0 = (blockIdx.x * TPB + threadIdx.x) * VEC;
+  const int t0 = (xcd_contiguous_block() * TPB + threadIdx.x) * VEC;
   if (t0 >= total) return;
   const long long kk = (long long)m.Ki * m.Kj;
   const int PcG = m.Ha * m.Wb;

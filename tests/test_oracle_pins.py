@@ -439,3 +439,82 @@ def test_rejects_bad_shapes():
         oracle.output_dims(Dims(1, 3, 4, 4, 2, 3, 1, 0, 2))      # C % groups != 0
     with pytest.raises(ValueError):
         oracle.output_dims(Dims(1, 1, 2, 2, 1, 3))               # kernel larger than padded input
+
+
+# ---------------------------------------------------------------- ReLU and max pooling (the layers between the convolutions)
+def test_relu_by_hand():
+    x = np.array([-2.0, -0.0, 0.0, 0.5, 3.0], np.float32)
+    dy = np.array([10.0, 20.0, 30.0, 40.0, 50.0], np.float32)
+    assert oracle.relu_forward(x).tolist() == [0.0, 0.0, 0.0, 0.5, 3.0]
+    assert oracle.relu_backward(x, dy).tolist() == [0.0, 0.0, 0.0, 40.0, 50.0]
+
+
+def test_maxpool_output_size_law():
+    P = oracle.PoolDims
+    assert oracle.pool_output_dims(P(1, 1, 55, 55, 3, 2)) == (27, 27)      # CaffeNet pool1
+    assert oracle.pool_output_dims(P(1, 1, 27, 27, 3, 2)) == (13, 13)      # pool2
+    assert oracle.pool_output_dims(P(1, 1, 13, 13, 3, 2)) == (6, 6)        # pool5
+    assert oracle.pool_output_dims(P(1, 1, 6, 7, 3, 2)) == (3, 3)          # ceil: (6-3)/2 = 1.5 -> 2, +1
+    assert oracle.pool_output_dims(P(1, 1, 4, 4, 2, 2, 1)) == (3, 3)       # padded: windows start at -1, 1, 3
+    assert oracle.pool_output_dims(P(1, 1, 5, 5, 3, 1)) == (3, 3)
+
+
+def test_maxpool_by_hand_with_overlapping_windows_and_ceil_clipping():
+    # 4 x 5 plane, 3 x 3 windows, stride 2: Hout = ceil(1/2)+1 = 2, Wout = ceil(2/2)+1 = 2;
+    # the second row / column of windows is clipped at the border
+    x = np.array([[1, 2, 3, 4, 5],
+                  [6, 9, 8, 7, 0],
+                  [3, 3, 3, 3, 3],
+                  [9, 1, 1, 1, 2]], np.float32).reshape(1, 1, 4, 5)
+    d = oracle.PoolDims(1, 1, 4, 5, 3, 2)
+    y, am = oracle.maxpool_forward(d, x)
+    # windows: rows 0-2 x cols 0-2 -> 9 at (1,1); rows 0-2 x cols 2-4 -> 8 at (1,2);
+    #          rows 2-3 x cols 0-2 -> 9 at (3,0); rows 2-3 x cols 2-4 -> 3, first at (2,2)
+    assert y.reshape(2, 2).tolist() == [[9, 8], [9, 3]]
+    assert am.reshape(2, 2).tolist() == [[1 * 5 + 1, 1 * 5 + 2], [3 * 5 + 0, 2 * 5 + 2]]
+    dy = np.array([[1, 10], [100, 1000]], np.float32).reshape(1, 1, 2, 2)
+    want = np.zeros((4, 5), np.float32)
+    want[1, 1], want[1, 2], want[3, 0], want[2, 2] = 1, 10, 100, 1000
+    assert np.array_equal(oracle.maxpool_backward(d, dy, am)[0, 0], want)
+
+
+def test_maxpool_tie_goes_to_first_in_scan_order_and_overlaps_add():
+    d = oracle.PoolDims(1, 1, 5, 5, 3, 2)                       # windows start at 0, 2: pixel (2,2) is in all four
+    x = np.zeros((1, 1, 5, 5), np.float32)
+    y, am = oracle.maxpool_forward(d, x)
+    assert am.reshape(2, 2).tolist() == [[0, 2], [10, 12]]      # top-left pixel of every window
+    x[0, 0, 2, 2] = 1.0
+    y, am = oracle.maxpool_forward(d, x)
+    assert (am == 12).all() and (y == 1).all()
+    dx = oracle.maxpool_backward(d, np.array([1, 2, 4, 8], np.float32).reshape(1, 1, 2, 2), am)
+    assert dx[0, 0, 2, 2] == 15 and dx.sum() == 15
+
+
+@pytest.mark.parametrize("N,C,H,W,K,s,p", [(2, 3, 55, 55, 3, 2, 0), (1, 4, 27, 27, 3, 2, 0), (2, 2, 9, 11, 2, 2, 0),
+                                           (1, 3, 10, 7, 3, 1, 1), (1, 2, 8, 8, 3, 2, 1)])
+def test_maxpool_against_torch_cpu_on_tie_free_data(N, C, H, W, K, s, p):
+    import torch
+    import torch.nn.functional as F
+    rng = np.random.default_rng(77)
+    x = rng.permutation(N * C * H * W).astype(np.float32).reshape(N, C, H, W)    # all values distinct
+    d = oracle.PoolDims(N, C, H, W, K, s, p)
+    y, am = oracle.maxpool_forward(d, x)
+    tx = torch.from_numpy(x).requires_grad_()
+    ty, tidx = F.max_pool2d(tx, K, s, p, ceil_mode=True, return_indices=True)
+    assert tuple(ty.shape) == y.shape
+    assert np.array_equal(y, ty.detach().numpy())
+    assert np.array_equal(am, tidx.numpy().astype(np.int32))
+    dy = rng.standard_normal(y.shape).astype(np.float32)
+    ty.backward(torch.from_numpy(dy))
+    np.testing.assert_allclose(oracle.maxpool_backward(d, dy, am), tx.grad.numpy(), rtol=1e-6, atol=1e-6)
+
+
+def test_relu_against_torch_cpu():
+    import torch
+    x = rnd(3, 4, 5, 6)
+    dy = rnd(3, 4, 5, 6)
+    tx = torch.from_numpy(x).requires_grad_()
+    ty = torch.relu(tx)
+    ty.backward(torch.from_numpy(dy))
+    assert np.array_equal(oracle.relu_forward(x), ty.detach().numpy())
+    assert np.array_equal(oracle.relu_backward(x, dy), tx.grad.numpy())
