@@ -218,6 +218,37 @@ int cct_lower(const cct_conv_desc_t* desc, cct_lowering_t lowering, const float*
               void* hip_stream);
 
 /*
+ * The two layers between CaffeNet's convolutional layers (Sec. 1: the system optimises all layers
+ * with the same techniques and matches Caffe's output layer by layer; Sec. 2.2: whole-batch
+ * processing applies to every layer).  The paper does not define them; the semantics are Caffe's.
+ * All pointers are device pointers; outputs are overwritten; nothing is allocated.
+ *
+ * ReLU: y[i] = max(x[i], 0) for i < n.  Backward: dx[i] = dy[i] where x[i] > 0, else 0 (x may be
+ * the layer's input or its output: the test agrees).  y may alias x and dx may alias dy.
+ */
+int cct_relu_forward(const float* x, float* y, int64_t n, void* hip_stream);
+int cct_relu_backward(const float* x, const float* dy, float* dx, int64_t n, void* hip_stream);
+
+/*
+ * Max pooling over K x K windows with stride `stride` and zero-excluded padding `pad` (< K) of an
+ * N x C x H x W tensor.  Output size per axis: ceil((in + 2*pad - K)/stride) + 1, minus one if the
+ * last window would start beyond the image (Caffe's rule; CaffeNet: 55 -> 27, 27 -> 13 with K = 3,
+ * stride 2).  Windows are clipped to the image; y[n,c,r,q] is the maximum of its window and
+ * argmax[n,c,r,q] (N*C*Hout*Wout int32, may be NULL in the forward call) the plane index h*W + w of
+ * the FIRST maximum in row-major order of the window.  Backward: dx[n,c,h,w] = sum of dy over the
+ * windows whose argmax is (h,w); computed as a gather, bit-reproducible.
+ */
+typedef struct {
+  int32_t N, C, H, W;
+  int32_t K, stride, pad;
+} cct_pool_desc_t;
+int cct_pool_output_dims(const cct_pool_desc_t* desc, int32_t* Hout, int32_t* Wout);
+int cct_maxpool_forward(const cct_pool_desc_t* desc, const float* x, float* y, int32_t* argmax,
+                        void* hip_stream);
+int cct_maxpool_backward(const cct_pool_desc_t* desc, const float* dy, const int32_t* argmax,
+                         float* dx, void* hip_stream);
+
+/*
  * Measurement aid (used by bench.py for the per-kernel roofline figures).  While enabled,
  * every kernel launch of the library is bracketed by two HIP events on the launching stream.
  * This is the one place where the library creates HIP objects (events, host side only); it

@@ -32,6 +32,8 @@ EXPORTS = [
     "cct_conv_workspace_bytes_for_chunk", "cct_conv_forward", "cct_conv_backward_data",
     "cct_conv_backward_weights", "cct_lowered_ld", "cct_lower", "cct_profile_enable",
     "cct_profile_read", "cct_calibration_copy", "cct_conv_forward_static",
+    "cct_relu_forward", "cct_relu_backward", "cct_pool_output_dims", "cct_maxpool_forward",
+    "cct_maxpool_backward",
 ]
 
 
@@ -66,6 +68,19 @@ _lib.cct_conv_forward_static.argtypes = [_dp, _vp, _vp, _vp, _vp, _vp]
 _lib.cct_conv_backward_data.argtypes = [_dp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.cct_conv_backward_weights.argtypes = [_dp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.cct_lower.argtypes = [_dp, ctypes.c_int, _vp, _vp, _vp]
+
+
+class PoolDesc(ctypes.Structure):
+    """cct_pool_desc_t."""
+    _fields_ = [(k, ctypes.c_int32) for k in ("N", "C", "H", "W", "K", "stride", "pad")]
+
+
+_pp = ctypes.POINTER(PoolDesc)
+_lib.cct_relu_forward.argtypes = [_vp, _vp, _i64, _vp]
+_lib.cct_relu_backward.argtypes = [_vp, _vp, _vp, _i64, _vp]
+_lib.cct_pool_output_dims.argtypes = [_pp, ctypes.POINTER(_i32), ctypes.POINTER(_i32)]
+_lib.cct_maxpool_forward.argtypes = [_pp, _vp, _vp, _vp, _vp]
+_lib.cct_maxpool_backward.argtypes = [_pp, _vp, _vp, _vp, _vp]
 
 
 class ProfileEntry(ctypes.Structure):
@@ -255,3 +270,51 @@ def cct_lower(desc: ConvDesc, lowering: int, x, dhat) -> None:
     ld = cct_lowered_ld(desc, lowering)
     _check(_lib.cct_lower(ctypes.byref(desc), int(lowering), _ptr(x, "x", xs),
                           _ptr(dhat, "dhat", (desc.groups * cols, ld)), _stream()), "cct_lower")
+
+
+# ---- ReLU and max pooling -------------------------------------------------------------------
+
+def make_pool_desc(N, C, H, W, K, stride, pad=0) -> PoolDesc:
+    return PoolDesc(N, C, H, W, K, stride, pad)
+
+
+def cct_pool_output_dims(desc: PoolDesc):
+    ho, wo = _i32(), _i32()
+    _check(_lib.cct_pool_output_dims(ctypes.byref(desc), ctypes.byref(ho), ctypes.byref(wo)),
+           "cct_pool_output_dims")
+    return ho.value, wo.value
+
+
+def cct_relu_forward(x, y) -> None:
+    _check(_lib.cct_relu_forward(_ptr(x, "x"), _ptr(y, "y", x.shape), x.numel(), _stream()),
+           "cct_relu_forward")
+
+
+def cct_relu_backward(x, dy, dx) -> None:
+    _check(_lib.cct_relu_backward(_ptr(x, "x"), _ptr(dy, "dy", x.shape), _ptr(dx, "dx", x.shape),
+                                  x.numel(), _stream()), "cct_relu_backward")
+
+
+def _iptr(t, name, shape):
+    import torch
+    if not isinstance(t, torch.Tensor) or not t.is_cuda or t.dtype != torch.int32 or \
+            not t.is_contiguous() or tuple(t.shape) != tuple(shape):
+        raise TypeError("%s must be a contiguous int32 GPU tensor of shape %s" % (name, tuple(shape)))
+    return t.data_ptr()
+
+
+def cct_maxpool_forward(desc: PoolDesc, x, y, argmax=None) -> None:
+    ho, wo = cct_pool_output_dims(desc)
+    ys = (desc.N, desc.C, ho, wo)
+    _check(_lib.cct_maxpool_forward(ctypes.byref(desc), _ptr(x, "x", (desc.N, desc.C, desc.H, desc.W)),
+                                    _ptr(y, "y", ys),
+                                    None if argmax is None else _iptr(argmax, "argmax", ys),
+                                    _stream()), "cct_maxpool_forward")
+
+
+def cct_maxpool_backward(desc: PoolDesc, dy, argmax, dx) -> None:
+    ho, wo = cct_pool_output_dims(desc)
+    ys = (desc.N, desc.C, ho, wo)
+    _check(_lib.cct_maxpool_backward(ctypes.byref(desc), _ptr(dy, "dy", ys), _iptr(argmax, "argmax", ys),
+                                     _ptr(dx, "dx", (desc.N, desc.C, desc.H, desc.W)), _stream()),
+           "cct_maxpool_backward")

@@ -1,0 +1,140 @@
+"""GPU parity of the ReLU and max-pooling entry points against the CPU oracle: values, argmax
+indices and ReLU gradients bit-exact; pooling gradients (a sum of at most four fp32 terms against
+the oracle's fp64 sum) within 1e-6."""
+import numpy as np
+import pytest
+
+import oracle
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    import torch
+    assert torch.cuda.is_available()
+    from paper_1504_04343_amd import binding
+    return binding
+
+
+def dev(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+@pytest.mark.parametrize("n", [1, 3, 4, 1023, 4096, 1 << 20, (1 << 20) + 5])
+def test_relu_forward_backward_bit_exact(B, n):
+    import torch
+    rng = np.random.default_rng(n)
+    x = rng.standard_normal(n).astype(np.float32)
+    x[::7] = 0.0
+    x[1::11] = -0.0
+    dy = rng.standard_normal(n).astype(np.float32)
+    tx, tdy = dev(x), dev(dy)
+    y = torch.full_like(tx, float("nan"))
+    dx = torch.full_like(tx, float("nan"))
+    B.cct_relu_forward(tx, y)
+    B.cct_relu_backward(tx, tdy, dx)
+    torch.cuda.synchronize()
+    assert y.cpu().numpy().tobytes() == oracle.relu_forward(x).tobytes()
+    assert dx.cpu().numpy().tobytes() == oracle.relu_backward(x, dy).tobytes()
+    # the mask may be taken from the output instead of the input, and both calls work in place
+    B.cct_relu_backward(y, tdy, tdy)
+    B.cct_relu_forward(tx, tx)
+    torch.cuda.synchronize()
+    assert tdy.cpu().numpy().tobytes() == oracle.relu_backward(x, dy).tobytes()
+    assert tx.cpu().numpy().tobytes() == oracle.relu_forward(x).tobytes()
+
+
+def test_relu_on_a_misaligned_view(B):
+    import torch
+    x = np.random.default_rng(5).standard_normal(1001).astype(np.float32)
+    base = dev(np.concatenate([[0.0], x]).astype(np.float32))
+    tx = base[1:]                                   # 4 bytes past a 16-byte boundary
+    y = torch.empty(1001, device="cuda")
+    B.cct_relu_forward(tx, y)
+    torch.cuda.synchronize()
+    assert y.cpu().numpy().tobytes() == oracle.relu_forward(x).tobytes()
+
+
+POOLS = [
+    # N, C, H, W, K, s, p
+    (2, 3, 55, 55, 3, 2, 0),      # CaffeNet pool1 geometry
+    (3, 5, 27, 27, 3, 2, 0),      # pool2
+    (2, 4, 13, 13, 3, 2, 0),      # pool5
+    (1, 2, 6, 7, 3, 2, 0),        # ceil: clipped last windows
+    (2, 3, 9, 11, 2, 2, 0),
+    (1, 3, 10, 7, 3, 1, 1),       # padded, overlapping
+    (2, 2, 8, 8, 3, 2, 1),
+    (1, 1, 1, 1, 1, 1, 0),
+    (1, 2, 5, 4, 5, 3, 2),
+]
+
+
+@pytest.mark.parametrize("case", POOLS)
+@pytest.mark.parametrize("relu_input", [False, True], ids=["normal", "relu_ties"])
+def test_maxpool_forward_backward(B, case, relu_input):
+    import torch
+    N, C, H, W, K, s, p = case
+    rng = np.random.default_rng(sum(case))
+    x = rng.standard_normal((N, C, H, W)).astype(np.float32)
+    if relu_input:
+        x = np.maximum(x, 0)                        # about half zeros: windows with tied maxima
+    od = oracle.PoolDims(N, C, H, W, K, s, p)
+    d = B.make_pool_desc(N, C, H, W, K, s, p)
+    assert B.cct_pool_output_dims(d) == oracle.pool_output_dims(od)
+    ho, wo = B.cct_pool_output_dims(d)
+    y = torch.full((N, C, ho, wo), float("nan"), device="cuda")
+    am = torch.full((N, C, ho, wo), -7, dtype=torch.int32, device="cuda")
+    B.cct_maxpool_forward(d, dev(x), y, am)
+    y2 = torch.full_like(y, float("nan"))
+    B.cct_maxpool_forward(d, dev(x), y2)            # argmax is optional
+    want_y, want_am = oracle.maxpool_forward(od, x)
+    torch.cuda.synchronize()
+    assert y.cpu().numpy().tobytes() == want_y.tobytes()
+    assert y2.cpu().numpy().tobytes() == want_y.tobytes()
+    assert np.array_equal(am.cpu().numpy(), want_am)
+    dy = rng.standard_normal((N, C, ho, wo)).astype(np.float32)
+    dx = torch.full((N, C, H, W), float("nan"), device="cuda")
+    B.cct_maxpool_backward(d, dev(dy), am, dx)
+    torch.cuda.synchronize()
+    want_dx = oracle.maxpool_backward(od, dy, want_am)
+    got = dx.cpu().numpy()
+    assert np.isfinite(got).all()
+    assert np.abs(got - want_dx).max() <= 1e-6 * max(1.0, np.abs(want_dx).max())
+
+
+@pytest.mark.parametrize("name,C,H", [("pool1", 96, 55), ("pool2", 256, 27)])
+def test_maxpool_full_size_batch_256(B, name, C, H):
+    """CaffeNet's pool1 / pool2 at batch 256 on post-ReLU data, every element."""
+    import torch
+    print("full-size", name, flush=True)
+    N = 256
+    rng = np.random.default_rng(3)
+    x = np.maximum(rng.standard_normal((N, C, H, H), dtype=np.float32), np.float32(0))
+    od = oracle.PoolDims(N, C, H, H, 3, 2, 0)
+    d = B.make_pool_desc(N, C, H, H, 3, 2, 0)
+    ho, wo = B.cct_pool_output_dims(d)
+    y = torch.empty((N, C, ho, wo), device="cuda")
+    am = torch.empty((N, C, ho, wo), dtype=torch.int32, device="cuda")
+    tx = dev(x)
+    B.cct_maxpool_forward(d, tx, y, am)
+    want_y, want_am = oracle.maxpool_forward(od, x)
+    torch.cuda.synchronize()
+    assert y.cpu().numpy().tobytes() == want_y.tobytes()
+    assert np.array_equal(am.cpu().numpy(), want_am)
+    dy = rng.standard_normal((N, C, ho, wo), dtype=np.float32)
+    dx = torch.empty_like(tx)
+    B.cct_maxpool_backward(d, dev(dy), am, dx)
+    torch.cuda.synchronize()
+    want_dx = oracle.maxpool_backward(od, dy, want_am)
+    assert np.abs(dx.cpu().numpy() - want_dx).max() <= 1e-6 * np.abs(want_dx).max()
+
+
+def test_pool_rejects_bad_descriptors(B):
+    for bad in (dict(N=0), dict(K=0), dict(stride=0), dict(pad=3), dict(pad=-1), dict(H=0)):
+        kw = dict(N=1, C=1, H=5, W=5, K=3, stride=2, pad=0)
+        kw.update(bad)
+        with pytest.raises(B.CctError) as e:
+            B.cct_pool_output_dims(B.make_pool_desc(**kw))
+        assert e.value.code == B.EINVAL
