@@ -71,6 +71,10 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-stream-leg", action="store_true",
                     help="skip the extra leg that times the lowering / lifting kernels")
+    ap.add_argument("--stream-leg-only", action="store_true",
+                    help="run only the leg that times the lowering / lifting kernels (for profilers)")
+    ap.add_argument("--stream-leg-type", type=int, default=0,
+                    help="with --stream-leg-only: force this materialised layout only (0 = all three)")
     ap.add_argument("--cpu-sample-images", type=int, default=64)
     ap.add_argument("--per-kernel", action="store_true", help="also print the per-kernel table")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -151,7 +155,7 @@ def profiled(B, step, steps):
     return B.cct_profile_read(64)
 
 
-def stream_kernel_leg(B, synth, batch, prec, steps=2):
+def stream_kernel_leg(B, synth, batch, prec, steps=2, types=(1, 2, 3)):
     """Rates of the lowering / lifting kernels and their adjoints: AUTO runs most passes fused, so
     they are timed in a leg of their own that forces each materialised layout (a layout the cost
     model prices at more than 5x the cheapest for a layer and pass is skipped: Type 3 of conv1
@@ -159,7 +163,7 @@ def stream_kernel_leg(B, synth, batch, prec, steps=2):
     import torch
     out = {}
     agg = {}
-    for lowering in (1, 2, 3):
+    for lowering in types:
         for L in synth.caffenet(batch):
             d0 = B.make_desc(L.N, L.C, L.H, L.W, L.O, L.K, L.stride, L.pad, L.groups, 0, prec)
             d = B.make_desc(L.N, L.C, L.H, L.W, L.O, L.K, L.stride, L.pad, L.groups, lowering, prec)
@@ -416,7 +420,13 @@ def main():
         B.cct_calibration_copy(src, dst)
         torch.cuda.synchronize()
         del src, dst
-    if args.config == "sweep":
+    if args.stream_leg_only:
+        types = (args.stream_leg_type,) if args.stream_leg_type else (1, 2, 3)
+        prec = B.PREC_F32 if args.precision == "f32" else B.PREC_BF16_IN_F32_ACC
+        print(json.dumps({"config": "materialised layouts %s, CaffeNet conv1-5, batch %d" % (
+            list(types), args.batch or 256),
+            "kernels": stream_kernel_leg(B, synth, args.batch or 256, prec, 2, types)}))
+    elif args.config == "sweep":
         run_sweep(args, B, synth, torch)
     elif args.config == "batching":
         run_batching(args, B, synth, torch)

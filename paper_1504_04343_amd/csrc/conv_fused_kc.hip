@@ -436,9 +436,19 @@ __global__ __launch_bounds__(256) void pack_fused_kc_kernel(const float* __restr
 
 }  // namespace
 
+// Row tile of this kernel: the GEMM family's choice (64 / 96 / 128), except that a row count that
+// is a multiple of 192 takes 192-row tiles (waves of 96 x 64: more MFMAs per operand read than the
+// 96 x 32 waves of the 96-row tile).
+static int kc_row_tile(const GemmTN& p, int* BNt) {
+  int BM, BKt;
+  gemm_tn_tile(p.M, p.Ncols, &BM, BNt, &BKt);
+  if (BM == 96 && p.Mpad % 192 == 0) BM = 192;
+  return BM;
+}
+
 bool conv_fused_kc_fits(const GemmTN& p) {
-  int BM, BNt, BKt;
-  gemm_tn_tile(p.M, p.Ncols, &BM, &BNt, &BKt);
+  int BNt;
+  const int BM = kc_row_tile(p, &BNt);
   KcGeom fg;
   size_t lds;
   return BNt == BN && make_kc_geom(p, BM, &fg, &lds);
@@ -466,12 +476,13 @@ int launch_conv_fused_kc(const GemmTN& p0, hipStream_t st) {
   GemmTN p = p0;
   colmap_prepare(&p.bmap);
   colmap_prepare(&p.cmap);
-  int BM, BNt, BKt;
-  gemm_tn_tile(p.M, p.Ncols, &BM, &BNt, &BKt);
+  int BNt;
+  const int BM = kc_row_tile(p, &BNt);
   KcGeom fg;
   size_t lds;
   if (BNt != BN || p.Mpad % BM || !make_kc_geom(p, BM, &fg, &lds)) return CCT_EUNSUPPORTED;
   if (p.Kpad != (long long)fg.ngroups * CG * fg.KK) return CCT_EINVAL;
+  if (BM == 192) return launch_variant<192, 3, 2>(p, fg, lds, st);
   if (BM == 64) return launch_variant<64, 1, 2>(p, fg, lds, st);
   if (BM == 96) return launch_variant<96, 3, 1>(p, fg, lds, st);
   return launch_variant<128, 2, 2>(p, fg, lds, st);
