@@ -204,7 +204,8 @@ def stream_kernel_leg(B, synth, batch, prec, steps=2, types=(1, 2, 3)):
             del x, w, dy, y, dx, dw
     for k, (nbytes, ms, n) in sorted(agg.items()):
         gbs = nbytes / (ms * 1e-3) / 1e9
-        out[k] = {"GBps": round(gbs, 1), "frac_of_hbm_peak": round(gbs / PEAK_HBM_GBS, 4), "launches": n}
+        out[k] = {"GBps": round(gbs, 1), "frac_of_hbm_peak": round(gbs / PEAK_HBM_GBS, 4), "launches": n,
+                  "algorithmic_MB_per_launch": round(nbytes / n / 1e6, 1), "avg_launch_ms": round(ms / n, 4)}
     return out
 
 

@@ -75,6 +75,46 @@ Geom make_geom(const cct_conv_desc_t& d, int type) {
   return g;
 }
 
+// Backward-data of a strided layer as ONE stride-1 convolution of dy (Sec. 2.1 "Fusion" applied to
+// the adjoint): with h + p = s*a + rh, a pixel (h, w) only receives taps i = rh + s*u, so each of
+// the s*s residue classes (rh, rw) is a convolution of dy with a sub-kernel of U x U taps,
+// U = ceil(K/s), on the grid (a, b) of Ah x Aw cells; the s*s*Cg results of a cell are the pixels of
+// its s x s block (depth-to-space).  Taps whose index reaches K are zero: the kernel does
+// (U*s/K)^2 times the useful work.
+struct StridedBwd {
+  int U, Ah, Aw, M;
+};
+inline StridedBwd strided_bwd(const cct_conv_desc_t& d, const Geom& g) {
+  StridedBwd sb;
+  sb.U = (d.K + d.stride - 1) / d.stride;
+  sb.Ah = (d.H - 1 + d.pad) / d.stride + 1;
+  sb.Aw = (d.W - 1 + d.pad) / d.stride + 1;
+  sb.M = g.Cg * d.stride * d.stride;
+  return sb;
+}
+// The operand description of one chunk of `ni` images (pack at `pack`, or null for a fit check).
+GemmTN strided_bwd_problem(const cct_conv_desc_t& d, const Geom& g, const void* pack, int Mpad,
+                           int Kpad_kc, const float* dyc, float* dxc, long long ni) {
+  const StridedBwd sb = strided_bwd(d, g);
+  GemmTN p;
+  std::memset(&p, 0, sizeof(p));
+  p.A = pack;
+  p.Mpad = Mpad;
+  p.Kpad = Kpad_kc;
+  p.a_gs = (long long)Mpad * Kpad_kc;
+  p.B = dyc;
+  p.bmap = ColMap{1, 0};
+  p.gather = 1;
+  p.gC = d.O; p.gH = g.Hout; p.gW = g.Wout; p.gHout = sb.Ah; p.gWout = sb.Aw;
+  p.gs = 1; p.gp = sb.U - 1; p.gCg = g.Og; p.gK = sb.U; p.gKK = sb.U * sb.U;
+  p.M = sb.M; p.Ncols = (int)(ni * sb.Ah * sb.Aw); p.Kdim = g.Og * sb.U * sb.U; p.G = d.groups;
+  p.C = dxc;
+  p.cmap = ColMap{1, 0};
+  p.d2s = 1; p.dS = d.stride; p.dP = d.pad; p.dH = d.H; p.dW = d.W; p.dCg = g.Cg; p.dCtot = d.C;
+  p.prof_flops = 2.0 * (double)ni * d.O * g.Hout * g.Wout * g.Cg * d.K * d.K;
+  return p;
+}
+
 inline int esize(const cct_conv_desc_t& d) { return d.precision == CCT_PREC_BF16_IN_F32_ACC ? 2 : 4; }
 
 // Workspace layout of one pass for a given chunk size.
@@ -127,6 +167,18 @@ bool make_layout(const cct_conv_desc_t& d, int pass, int type, const Geom& g, lo
       take(dt_rows * L->ld * es, &L->dt_off, &L->dt_bytes);
       if (type != CCT_LOWER_TYPE1) take(rt_rows * L->ld * 4, &L->rt_off, &L->rt_bytes);
     }
+  } else if (pass == CCT_PASS_BACKWARD_DATA && type == CCT_LOWER_FUSED && d.stride > 1) {
+    // a stride-1 convolution of dy with s*s sub-kernels of U x U taps: M = Cg*s*s, K dim = Og*U*U
+    const StridedBwd sb = strided_bwd(d, g);
+    if (nc * sb.Ah * sb.Aw >= kIntMax - 256 || (long long)g.Cg * d.stride * d.stride >= kIntMax)
+      return false;
+    int BM, BN, BK;
+    gemm_tn_tile(sb.M, (int)(nc * sb.Ah * sb.Aw), &BM, &BN, &BK);
+    L->Mpad = (int)align_up(sb.M, BM);
+    const long long kc = conv_fused_kc_kpad(g.Og, sb.U);
+    if (kc >= kIntMax) return false;
+    L->Kpad = L->Kpad_kc = (int)kc;
+    take((long long)d.groups * L->Mpad * kc * 4, &L->pack_off, &L->pack_bytes);
   } else if (pass == CCT_PASS_BACKWARD_DATA && type == CCT_LOWER_FUSED) {
     // a stride-1 convolution of dy with the flipped kernels: M = Cg, K dim = Og*K*K
     if (nc * d.H * d.W >= kIntMax - 256) return false;
@@ -194,8 +246,22 @@ bool type_supported(const cct_conv_desc_t& d, int pass, int type) {
           !(d.pad == 0 && gemm_nt_gather_fits(d.C, d.H, d.W, d.O, Ho, Wo)))
         return false;
     }
-    // backward-data is fused as a convolution of dy with the flipped kernels: stride 1 only
-    if (pass == CCT_PASS_BACKWARD_DATA && (d.stride != 1 || d.pad > d.K - 1)) return false;
+    // backward-data is fused as a convolution of dy with the flipped kernels (stride 1), or with
+    // the s*s sub-kernels of a strided layer when the channel-contiguous kernel can stage it
+    if (pass == CCT_PASS_BACKWARD_DATA && d.stride == 1 && d.pad > d.K - 1) return false;
+    if (pass == CCT_PASS_BACKWARD_DATA && d.stride > 1) {
+      const Geom gg = make_geom(d, CCT_LOWER_FUSED);
+      const StridedBwd sb = strided_bwd(d, gg);
+      if ((long long)gg.Cg * d.stride * d.stride >= kIntMax || (long long)sb.Ah * sb.Aw >= kIntMax)
+        return false;
+      int BM, BN, BK;
+      gemm_tn_tile(sb.M, sb.Ah * sb.Aw, &BM, &BN, &BK);
+      const long long kc = conv_fused_kc_kpad(gg.Og, sb.U);
+      if (kc >= kIntMax) return false;
+      if (!conv_fused_kc_fits(strided_bwd_problem(d, gg, nullptr, (int)align_up(sb.M, BM), (int)kc,
+                                                  nullptr, nullptr, 1)))
+        return false;
+    }
     if ((long long)d.C * d.H * d.W >= kIntMax) return false;  // 32-bit offsets inside one image
   }
   const Geom g = make_geom(d, type);
@@ -219,7 +285,8 @@ constexpr double kLaunchSec = 4.0e-6;
 constexpr double kFusedGemmFactor = 0.95; // fused kernels vs the GEMM on a materialised matrix
 
 // time = sum over index-map kernels of bytes / stream rate
-//      + max(GEMM flops / MFMA rate, GEMM bytes / GEMM stream rate)     (loads overlap the MFMAs)
+//      + max(t_mfma, t_mem) + 0.3 * min(t_mfma, t_mem),  t_mfma = GEMM flops / MFMA rate,
+//        t_mem = GEMM bytes / GEMM stream rate              (loads mostly overlap the MFMAs)
 //      + launches * launch latency
 double model_cost(const cct_conv_desc_t& d, int pass, int type) {
   const Geom g = make_geom(d, type);
@@ -233,12 +300,12 @@ double model_cost(const cct_conv_desc_t& d, int pass, int type) {
   double gemm_flops = 2.0 * cols * (double)g.Mr * (double)g.Kd * d.groups;
   // Row-tile efficiency of the GEMM family: the launchers cut the rows into tiles of 64 (up to
   // 64 rows), 96 (multiples of 96 that are not multiples of 128) or 128; rows beyond the true
-  // count are wasted work, and the narrower tiles run their MFMAs below the 128-row tile's rate
-  // (measured: about 0.8 for 64 rows, 0.95 for 96).
+  // count are wasted work, and the 96-row tile (waves of 96 x 32) runs its MFMAs a little below
+  // the other two (measured: about 0.95).
   auto eff = [](double dim) {
     const long long m = (long long)dim;
     const double tile = m <= 64 ? 64.0 : ((m % 128 != 0 && m % 96 == 0) ? 96.0 : 128.0);
-    const double speed = tile == 64.0 ? 0.8 : (tile == 96.0 ? 0.95 : 1.0);
+    const double speed = tile == 96.0 ? 0.95 : 1.0;
     return dim / (std::ceil(dim / tile) * tile) * speed;
   };
   auto short_k = [](double k) { return std::min(1.0, std::max(0.25, k / 64.0)); };
@@ -263,6 +330,13 @@ double model_cost(const cct_conv_desc_t& d, int pass, int type) {
       launches += 1.0;
     }
     rate *= eff(g.Mr) * fill(g.Mr, cols) * short_k(g.Kd);
+  } else if (pass == CCT_PASS_BACKWARD_DATA && type == CCT_LOWER_FUSED && d.stride > 1) {
+    // a convolution of dy with s*s sub-kernels of U x U taps: the zero taps are executed too
+    const StridedBwd sb = strided_bwd(d, g);
+    const double pos = N * sb.Ah * sb.Aw;
+    gemm_bytes = x_bytes + y_bytes;
+    gemm_flops = 2.0 * pos * (double)sb.M * (double)g.Og * sb.U * sb.U * d.groups;
+    rate *= kFusedGemmFactor * eff(sb.M) * fill(sb.M, pos);
   } else if (pass == CCT_PASS_BACKWARD_DATA && type == CCT_LOWER_FUSED) {
     // a convolution of dy with the flipped kernels: Cg output rows per group, one column per pixel
     const double pos = N * d.H * d.W;
@@ -302,8 +376,12 @@ double model_cost(const cct_conv_desc_t& d, int pass, int type) {
     launches += 2.0;
     rate *= eff(g.Mr) * eff(g.Kd);
   }
-  return index_bytes / kStreamBytesPerSec +
-         std::max(gemm_flops / rate, gemm_bytes / kGemmBytesPerSec) + launches * kLaunchSec;
+  // the GEMM's operand / result streams overlap its MFMAs, but not completely: a GEMM that is
+  // heavy on both (conv1's backward-data pass writes 1.1 GB of lowered gradient) takes about the
+  // longer of the two plus a third of the shorter
+  const double t_mfma = gemm_flops / rate, t_mem = gemm_bytes / kGemmBytesPerSec;
+  return index_bytes / kStreamBytesPerSec + std::max(t_mfma, t_mem) + 0.3 * std::min(t_mfma, t_mem) +
+         launches * kLaunchSec;
 }
 
 int pick(const cct_conv_desc_t& d, int pass) {
@@ -677,6 +755,19 @@ int cct_conv_backward_data(const cct_conv_desc_t* desc, const float* w, const fl
   const long long P = (long long)g.Hout * g.Wout;
   const long long HW = (long long)d.H * d.W;
 
+  if (type == CCT_LOWER_FUSED && d.stride > 1) {
+    // one kernel per chunk: the s*s residue classes of dx as one stride-1 convolution of dy
+    float* pack = reinterpret_cast<float*>(ws + L.pack_off);
+    rc = launch_pack_fused_kc_strided(w, pack, d.groups, g.Og, g.Cg, d.K, d.stride, L.Mpad, st);
+    if (rc) return rc;
+    for (long long n0 = 0; n0 < d.N; n0 += nc) {
+      const long long ni = std::min<long long>(nc, d.N - n0);
+      rc = launch_conv_fused_kc(strided_bwd_problem(d, g, pack, L.Mpad, L.Kpad_kc, dy + n0 * d.O * P,
+                                                    dx + n0 * d.C * HW, ni), st);
+      if (rc) return rc;
+    }
+    return CCT_OK;
+  }
   if (type == CCT_LOWER_FUSED) {
     // one kernel per chunk: dx = convolution of dy (O channels, Hout x Wout) with the flipped
     // kernels, stride 1, pad K-1-p; lowering of dy happens in LDS (or as a gather), never in HBM

@@ -78,6 +78,14 @@ struct GemmTN {
   int tapmajor, gCpad, tKi, tKj, tph, tpw;
   unsigned g_divKK_M, g_divK_M;  // fast division by K*K and by K
   int g_divKK_sh, g_divK_sh;
+  // Depth-to-space epilogue of the channel-contiguous fused kernel (d2s != 0), used for the
+  // backward-data pass of a strided layer: row m = (ci*dS + rh)*dS + rw of the product at grid
+  // position (a, b) of image n is pixel (h, w) = (a*dS + rh - dP, b*dS + rw - dP) of channel
+  // g*dCg + ci of the dCtot-channel, dH x dW tensor at C; pixels outside the tensor are dropped.
+  int d2s, dS, dP, dH, dW, dCg, dCtot;
+  double prof_flops;  // algorithmic flops to book for the launch when they differ from 2*M*N*K*G (else 0)
+  unsigned d_divSS_M, d_divS_M;  // fast division by dS*dS and by dS
+  int d_divSS_sh, d_divS_sh;
 };
 // Cpart[s][g][m][n] = sum_{col in split s} A(m, col) * B(n, col); both operands col-contiguous.
 struct GemmNT {
@@ -113,6 +121,12 @@ bool conv_fused_kc_fits(const GemmTN& p);
 long long conv_fused_kc_kpad(int channels_per_group, int K);
 int launch_pack_fused_kc(const float* w, float* pack, int G, int Og, int Cg, int K, int Mpad,
                          int flipped, hipStream_t st);
+// Kernel pack of the strided backward-data pass computed as a stride-1 convolution of dy with
+// s*s sub-kernels of U x U taps, U = ceil(K/s): rows m = (ci*s + rh)*s + rw, channels = kernels oo,
+// pack[q][grp][(u',v')][m][c] = w[q*Og + grp*16 + c, ci, rh + s*(U-1-u'), rw + s*(U-1-v')] (0 where
+// that tap index is >= K).
+int launch_pack_fused_kc_strided(const float* w, float* pack, int G, int Og, int Cg, int K, int s,
+                                 int Mpad, hipStream_t st);
 int launch_conv_fused_kc(const GemmTN& p, hipStream_t st);
 // Fused backward-weights pass: split partial products of dy (NCHW, read in place) with the
 // Type-1 lowering of x built in LDS.  Cpart[s][q][oo][(ci,i,j)], compact, S splits of split_len

@@ -28,6 +28,8 @@
 //   - epilogue = Type-1 lifting + bias, as in the plain GEMM.
 #include <stdio.h>
 
+#include <algorithm>
+
 #include "cct_internal.h"
 #include "gemm_common.h"
 
@@ -319,9 +321,37 @@ __global__ __launch_bounds__(NT) void conv_fused_kc_f32(GemmTN p, KcGeom fg, int
 #undef CCT_STAGE_STORE
 
   // ---- epilogue: Type-1 lifting + bias (same accumulator layout as the plain GEMM) -------------
+  const int mw = m0 + wave_m * WM * 32;
+  if (p.d2s) {
+    // depth-to-space: a lane's four consecutive rows are four sub-pixels of its grid position
+    float* __restrict__ D = p.C;
+    const int ss = p.dS * p.dS;
+#pragma unroll
+    for (int j = 0; j < WN; ++j) {
+      const int col = n0 + bn + j * 32;
+      if (col >= ce) continue;
+      const int n = col / P, pix = col - n * P;
+      const int ga = pix / p.gWout, gb = pix - ga * p.gWout;
+      const long long img = ((long long)n * p.dCtot + (long long)g * p.dCg) * p.dH;
+#pragma unroll
+      for (int i = 0; i < WM; ++i) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int m = mw + i * 32 + (r >> 2) * 8 + (r & 3) + lane_hi * 4;
+          if (m < p.M) {
+            const int ci = fdiv_u(m, p.d_divSS_M, p.d_divSS_sh), rem = m - ci * ss;
+            const int rh = fdiv_u(rem, p.d_divS_M, p.d_divS_sh), rw = rem - rh * p.dS;
+            const int h = ga * p.dS + rh - p.dP, w = gb * p.dS + rw - p.dP;
+            if ((unsigned)h < (unsigned)p.dH && (unsigned)w < (unsigned)p.dW)
+              D[((img + (long long)ci * p.dH) + h) * p.dW + w] = acc[i][j][r];
+          }
+        }
+      }
+    }
+    return;
+  }
   float* __restrict__ C = p.C + (long long)g * p.c_gs;
   const float* bias = p.bias ? p.bias + (long long)g * p.bias_gs : nullptr;
-  const int mw = m0 + wave_m * WM * 32;
   const bool full_m = m0 + BM <= p.M;
 #pragma unroll
   for (int j = 0; j < WN; ++j) {
@@ -348,7 +378,10 @@ __global__ __launch_bounds__(NT) void conv_fused_kc_f32(GemmTN p, KcGeom fg, int
 bool make_kc_geom(const GemmTN& p, int BM, KcGeom* fg, size_t* lds) {
   if (!p.gather || p.bf16 || p.tapmajor || p.gK < 2 || p.gCg < 1) return false;
   fg->KK = p.gK * p.gK;
-  fg->Wp = p.gW + 2 * p.gp;
+  // staged row width: the padded input row, or what the last grid column's window reaches if the
+  // caller's grid is wider than the convolution arithmetic gives (columns beyond the input load
+  // as zeros like any padding)
+  fg->Wp = std::max(p.gW + 2 * p.gp, (p.gWout - 1) * p.gs + p.gK);
   fg->ngroups = (p.gCg + CG - 1) / CG;
   // channels are padded to whole groups of 16: not worth it when that wastes over an eighth
   if ((long long)fg->ngroups * CG * 8 > (long long)p.gCg * 9) return false;
@@ -391,10 +424,12 @@ int launch_variant(const GemmTN& p, const KcGeom& fg, size_t lds, hipStream_t st
   const int tiles_n = (int)tn;
   dim3 grid((unsigned)blocks, (unsigned)p.G);
   char name[96];
-  snprintf(name, sizeof(name), "conv_fused_kc_f32<%d, %d, %d>", BM, WM, WN);
-  const double x_bytes = 4.0 * ((double)p.Ncols / (p.gHout * p.gWout)) * p.gC * p.gH * p.gW;
-  ProfScope ps(name, 2.0 * p.M * p.Ncols * p.Kdim * p.G,
-               x_bytes + 4.0 * ((double)p.M * p.Ncols + (double)p.M * p.Kdim) * p.G, st);
+  snprintf(name, sizeof(name), "conv_fused_kc_f32<%d, %d, %d>%s", BM, WM, WN, p.d2s ? " strided" : "");
+  const double nimg = (double)p.Ncols / (p.gHout * p.gWout);
+  const double x_bytes = 4.0 * nimg * p.gC * p.gH * p.gW;
+  const double y_bytes = p.d2s ? 4.0 * nimg * p.dCtot * p.dH * p.dW : 4.0 * (double)p.M * p.Ncols * p.G;
+  ProfScope ps(name, p.prof_flops > 0 ? p.prof_flops : 2.0 * p.M * p.Ncols * p.Kdim * p.G,
+               x_bytes + y_bytes + 4.0 * (double)p.M * p.Kdim * p.G, st);
   constexpr auto kern = conv_fused_kc_f32<BM, WM, WN>;
   if (const int rc = ensure_dynamic_lds<kern>(kLdsCap)) return rc;
   hipLaunchKernelGGL(kern, grid, dim3(NT), lds, st, p, fg, tiles_m, tiles_n);
@@ -430,6 +465,34 @@ __global__ __launch_bounds__(256) void pack_fused_kc_kernel(const float* __restr
   } else {
     if (m < Cg && ch < Og)
       v = w[((((long long)q * Og + ch) * Cg + m) * K + (K - 1 - i)) * K + (K - 1 - j)];
+  }
+  pack[t] = v;
+}
+
+// Kernel pack of the strided backward-data pass (see launch_pack_fused_kc_strided).
+__global__ __launch_bounds__(256) void pack_fused_kc_strided_kernel(const float* __restrict__ w,
+                                                                    float* __restrict__ pack, int G,
+                                                                    int Og, int Cg, int K, int s, int U,
+                                                                    int Mpad, int ngroups) {
+  const int UU = U * U;
+  const long long per_group = (long long)ngroups * UU * Mpad * CG;
+  const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (t >= per_group * G) return;
+  const int q = (int)(t / per_group);
+  long long e = t - q * per_group;
+  const int c = (int)(e % CG);
+  e /= CG;
+  const int m = (int)(e % Mpad);
+  e /= Mpad;
+  const int tap = (int)(e % UU), grp = (int)(e / UU);
+  const int up = tap / U, vp = tap - up * U;
+  const int oo = grp * CG + c;
+  float v = 0.0f;
+  if (m < Cg * s * s && oo < Og) {
+    const int ci = m / (s * s), rem = m - ci * s * s;
+    const int rh = rem / s, rw = rem - rh * s;
+    const int i = rh + s * (U - 1 - up), j = rw + s * (U - 1 - vp);
+    if (i < K && j < K) v = w[((((long long)q * Og + oo) * Cg + ci) * K + i) * K + j];
   }
   pack[t] = v;
 }
@@ -471,11 +534,30 @@ int launch_pack_fused_kc(const float* w, float* pack, int G, int Og, int Cg, int
   return CCT_OK;
 }
 
+int launch_pack_fused_kc_strided(const float* w, float* pack, int G, int Og, int Cg, int K, int s,
+                                 int Mpad, hipStream_t st) {
+  const int U = (K + s - 1) / s;
+  const int ngroups = (Og + CG - 1) / CG;
+  const long long total = (long long)G * ngroups * U * U * Mpad * CG;
+  const long long blocks = (total + 255) / 256;
+  if (blocks <= 0 || blocks >= 2147483647LL) return CCT_EUNSUPPORTED;
+  ProfScope ps("pack_fused_kc_strided_kernel", 0.0, 4.0 * G * Og * Cg * K * K + 4.0 * total, st);
+  hipLaunchKernelGGL(pack_fused_kc_strided_kernel, dim3((unsigned)blocks), dim3(256), 0, st, w, pack,
+                     G, Og, Cg, K, s, U, Mpad, ngroups);
+  CCT_CHECK_LAUNCH();
+  return CCT_OK;
+}
+
 // p.A must have been written by launch_pack_fused_kc; p.Kpad = conv_fused_kc_kpad(...).
 int launch_conv_fused_kc(const GemmTN& p0, hipStream_t st) {
   GemmTN p = p0;
   colmap_prepare(&p.bmap);
   colmap_prepare(&p.cmap);
+  if (p.d2s) {
+    if (p.dS < 1 || p.M != p.dCg * p.dS * p.dS) return CCT_EINVAL;
+    make_fastdiv_parts(p.dS * p.dS, &p.d_divSS_M, &p.d_divSS_sh);
+    make_fastdiv_parts(p.dS, &p.d_divS_M, &p.d_divS_sh);
+  }
   int BNt;
   const int BM = kc_row_tile(p, &BNt);
   KcGeom fg;

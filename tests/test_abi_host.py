@@ -152,7 +152,7 @@ def test_selector_degenerate_and_strided_cases(B):
     conv1 = B.make_desc(256, 3, 227, 227, 96, 11, 4, 0, 1)
     assert B.cct_pick_lowering(conv1, B.PASS_FORWARD) in (1, 4)  # stride 4: Types 2/3 waste s, s^2 work
     assert B.cct_pick_lowering(conv1, B.PASS_BACKWARD_WEIGHTS) in (1, 4)
-    assert B.cct_pick_lowering(conv1, B.PASS_BACKWARD_DATA) == 1   # no fused form at stride 4
+    assert B.cct_pick_lowering(conv1, B.PASS_BACKWARD_DATA) in (1, 4)
     for p in (B.PASS_FORWARD, B.PASS_BACKWARD_DATA, B.PASS_BACKWARD_WEIGHTS):
         for L in __import__("paper_1504_04343_amd.synth", fromlist=["x"]).caffenet(256):
             dd = B.make_desc(L.N, L.C, L.H, L.W, L.O, L.K, L.stride, L.pad, L.groups)
@@ -174,8 +174,11 @@ def test_fused_support_rules(B):
     conv1 = (256, 3, 227, 227, 96, 11, 4, 0, 1)
     conv3 = (256, 256, 13, 13, 384, 3, 1, 1, 1)
     assert supported(conv1, B.PASS_FORWARD) and supported(conv3, B.PASS_FORWARD)
-    assert not supported(conv1, B.PASS_BACKWARD_DATA)      # stride 4: no convolution with flipped kernels
+    assert supported(conv1, B.PASS_BACKWARD_DATA)          # stride 4: 16 residue classes, 96 kernels = 6 groups of 16
     assert supported(conv3, B.PASS_BACKWARD_DATA)
+    few_kernels = (4, 8, 15, 15, 5, 3, 2, 1, 1)             # strided with 5 kernels: a group of 16 would be 2/3 empty
+    assert not supported(few_kernels, B.PASS_BACKWARD_DATA)
+    assert not supported((4, 8, 15, 15, 32, 3, 1, 3, 1), B.PASS_BACKWARD_DATA)   # stride 1 with pad > K-1
     assert supported(conv1, B.PASS_BACKWARD_WEIGHTS)       # unpadded: rows gathered inside the GEMM
     assert supported(conv3, B.PASS_BACKWARD_WEIGHTS)       # rows staged in LDS
     padded_wide = (2, 6, 14, 400, 9, 4, 3, 1, 3)            # padded, rows too wide for LDS staging

@@ -122,12 +122,47 @@ def test_forward_is_deterministic(B):
 
 
 # ------------------------------------------------------------------ backward
+FUSED_BWDD_UNSUPPORTED = {"stride2_floor", "pad_gt_k", "stride3_g3"}
+STRIDED = [
+    layer("s2_k3", 3, 16, 15, 17, 32, 3, 2, 1, 1),               # U = 2: 4 residue classes, 4 taps each
+    layer("s2_k5_g2", 2, 8, 21, 19, 64, 5, 2, 2, 2),             # U = 3, groups, 32 kernels per group
+    layer("s3_k7", 2, 5, 29, 23, 16, 7, 3, 0, 1),                # U = 3, unpadded, (H - K) % s != 0
+    layer("s4_k11_p1", 2, 3, 51, 47, 48, 11, 4, 1, 1),           # conv1-like with padding
+    layer("s2_k4_deep", 2, 4, 18, 14, 80, 4, 2, 1, 1),           # 5 channel groups of 16 kernels
+]
+
+
+def test_backward_data_fused_strided_without_overlap_is_unsupported(B):
+    """K <= stride leaves one tap per residue class (a 1x1 sub-kernel): not a fused form."""
+    for L in (layer("s2_k2", 2, 6, 12, 12, 16, 2, 2, 0, 1), layer("s3_k2", 1, 4, 14, 14, 16, 2, 3, 0, 1)):
+        _, w, _, dy = inputs(L)
+        with pytest.raises(B.CctError) as e:
+            gpu_backward_data(B, L, w, dy, B.LOWER_FUSED)
+        assert e.value.code == B.EUNSUPPORTED
+        want = oracle.conv_backward_data(odims(oracle, L), w, dy)     # AUTO still runs them
+        assert rel_err(gpu_backward_data(B, L, w, dy, B.LOWER_AUTO), want) <= TOL_F32
+
+
+@pytest.mark.parametrize("L", STRIDED, ids=[L.name for L in STRIDED])
+def test_backward_data_fused_strided_matches_oracle(B, L):
+    """Backward-data of strided layers through the fused kernel (s*s residue classes of dx as one
+    stride-1 convolution of dy, written back depth-to-space)."""
+    _, w, _, dy = inputs(L, 7)
+    want = oracle.conv_backward_data(odims(oracle, L), w, dy)
+    got = gpu_backward_data(B, L, w, dy, B.LOWER_FUSED)
+    assert np.isfinite(got).all()                   # NaN prefill: every pixel was written
+    assert rel_err(got, want) <= TOL_F32
+    assert np.array_equal(got, gpu_backward_data(B, L, w, dy, B.LOWER_FUSED, chunk=1))
+
+
 @pytest.mark.parametrize("L", SMALL, ids=IDS)
 @pytest.mark.parametrize("lowering", [1, 2, 3, 4])
 def test_backward_data_matches_oracle(B, L, lowering):
     _, w, _, dy = inputs(L)
-    if lowering == 4 and (L.stride != 1 or L.pad > L.K - 1):
-        # the fused backward-data pass is a stride-1 convolution of dy with the flipped kernels
+    # the fused backward-data pass is a stride-1 convolution of dy: with the flipped kernels at
+    # stride 1 (pad <= K-1), with the s*s residue sub-kernels at stride s when the kernels fill
+    # groups of 16; anything else has no fused form and must say so before launching anything
+    if lowering == 4 and L.name in FUSED_BWDD_UNSUPPORTED:
         with pytest.raises(B.CctError) as e:
             gpu_backward_data(B, L, w, dy, lowering)
         assert e.value.code == B.EUNSUPPORTED
