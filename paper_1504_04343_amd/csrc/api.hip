@@ -308,6 +308,8 @@ double model_cost(const cct_conv_desc_t& d, int pass, int type) {
     const double speed = tile == 96.0 ? 0.95 : 1.0;
     return dim / (std::ceil(dim / tile) * tile) * speed;
   };
+  // the fused kernels have a 48-row form on 16 x 16 MFMA blocks: no padding rows up to 48
+  auto eff_fused = [&](double dim) { return dim <= 48.0 ? dim / 48.0 * 0.97 : eff(dim); };
   auto short_k = [](double k) { return std::min(1.0, std::max(0.25, k / 64.0)); };
   // a GEMM with fewer than ~2 workgroups (128 x 128 tiles) per CU cannot fill the chip
   auto fill = [&](double rows, double ncols) {
@@ -318,7 +320,7 @@ double model_cost(const cct_conv_desc_t& d, int pass, int type) {
   if (pass == CCT_PASS_FORWARD && type == CCT_LOWER_FUSED) {
     // no lowered matrix at all; building the operand in the kernel costs the GEMM some of its rate
     gemm_bytes = x_bytes + y_bytes;
-    rate *= kFusedGemmFactor * eff(g.Mr) * fill(g.Mr, cols) * short_k(g.Kd);
+    rate *= kFusedGemmFactor * eff_fused(g.Mr) * fill(g.Mr, cols) * short_k(g.Kd);
   } else if (pass == CCT_PASS_FORWARD) {
     index_bytes += x_bytes + dt_elems * es;      // lowering: read x, write D^T
     gemm_bytes += dt_elems * es;                 // GEMM reads D^T
@@ -336,13 +338,13 @@ double model_cost(const cct_conv_desc_t& d, int pass, int type) {
     const double pos = N * sb.Ah * sb.Aw;
     gemm_bytes = x_bytes + y_bytes;
     gemm_flops = 2.0 * pos * (double)sb.M * (double)g.Og * sb.U * sb.U * d.groups;
-    rate *= kFusedGemmFactor * eff(sb.M) * fill(sb.M, pos);
+    rate *= kFusedGemmFactor * eff_fused(sb.M) * fill(sb.M, pos);
   } else if (pass == CCT_PASS_BACKWARD_DATA && type == CCT_LOWER_FUSED) {
     // a convolution of dy with the flipped kernels: Cg output rows per group, one column per pixel
     const double pos = N * d.H * d.W;
     gemm_bytes = x_bytes + y_bytes;
     gemm_flops = 2.0 * pos * (double)g.Cg * (double)g.Og * d.K * d.K * d.groups;
-    rate *= kFusedGemmFactor * eff(g.Cg) * fill(g.Cg, pos);
+    rate *= kFusedGemmFactor * eff_fused(g.Cg) * fill(g.Cg, pos);
   } else if (pass == CCT_PASS_BACKWARD_DATA) {
     if (type == CCT_LOWER_TYPE1 || (type == CCT_LOWER_TYPE2 && d.stride == 1 && es == 4.0)) {
       gemm_bytes += y_bytes;                     // GEMM reads (Type 2: gathers) dy in place

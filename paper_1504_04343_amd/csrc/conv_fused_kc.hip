@@ -56,8 +56,15 @@ struct KcGeom {
 template <int BM, int WM, int WN>
 __global__ __launch_bounds__(NT) void conv_fused_kc_f32(GemmTN p, KcGeom fg, int tiles_m,
                                                         int tiles_n) {
-  constexpr int WAVES_N = BN / (32 * WN);
-  constexpr int WAVES_M = BM / (32 * WM);
+  // BM == 48: at most 48 rows (kernels, or sub-pixel channels of a strided backward-data pass),
+  // computed with v_mfma_f32_16x16x4_f32 on 16 x 16 blocks so that no MFMA works on padding rows:
+  // WM = 3 row blocks, WN = 2 column blocks per wave, all four waves side by side along the
+  // positions.  A lane quarter (lane / 16) then supplies four of a tile's 16 reduction indices,
+  // so ONE 16-byte read per block covers the whole tile.
+  constexpr bool M16 = BM == 48;
+  constexpr int MB = M16 ? 16 : 32;  // block edge
+  constexpr int WAVES_N = BN / (MB * WN);
+  constexpr int WAVES_M = BM / (MB * WM);
   static_assert(WAVES_M * WAVES_N == 4, "4 waves per workgroup");
   constexpr int A_VECS = BM * CG / 4;
   constexpr int A_IT = (A_VECS + NT - 1) / NT;
@@ -73,7 +80,8 @@ __global__ __launch_bounds__(NT) void conv_fused_kc_f32(GemmTN p, KcGeom fg, int
   const int lane = tid & 63;
   const int wave = tid >> 6;
   const int wave_m = wave / WAVES_N, wave_n = wave % WAVES_N;
-  const int lane_lo = lane & 31, lane_hi = lane >> 5;
+  const int lane_lo = M16 ? (lane & 15) : (lane & 31);  // row / column inside a block
+  const int lane_hi = M16 ? (lane >> 4) : (lane >> 5);  // which reduction indices the lane supplies
 
   // consecutive workgroup ids go round-robin over the 8 XCDs: give every XCD a contiguous run of
   // column tiles with the M tiles of one column tile next to each other (they share x through L2)
@@ -190,38 +198,42 @@ __global__ __launch_bounds__(NT) void conv_fused_kc_f32(GemmTN p, KcGeom fg, int
     a_dst[it] = (v >> 2) * CS + (v & 3) * 4;
   }
   const long long a_step = (long long)p.Mpad * CG;
-  f32x4 ra[A_IT];
-#define CCT_LOAD_A()                                                                        \
+  f32x4 ra[2][A_IT];  // the 16-row form keeps two tiles in flight (its tiles are short), set 0 else
+#define CCT_LOAD_A_SET(SET)                                                                 \
   {                                                                                         \
     _Pragma("unroll") for (int it = 0; it < A_IT; ++it) {                                   \
-      if (A_VECS % NT == 0 || tid + it * NT < A_VECS) ra[it] = *(gptr_f32x4)(a_src[it]);    \
+      if (A_VECS % NT == 0 || tid + it * NT < A_VECS) ra[SET][it] = *(gptr_f32x4)(a_src[it]); \
       a_src[it] += a_step;                                                                  \
     }                                                                                       \
   }
-#define CCT_STORE_A(BUF)                                                                    \
+#define CCT_STORE_A_SET(BUF, SET)                                                           \
   {                                                                                         \
     _Pragma("unroll") for (int it = 0; it < A_IT; ++it) {                                   \
       if (A_VECS % NT == 0 || tid + it * NT < A_VECS)                                       \
-        *reinterpret_cast<f32x4*>(&As[(BUF) * A_BUF + a_dst[it]]) = ra[it];                 \
+        *reinterpret_cast<f32x4*>(&As[(BUF) * A_BUF + a_dst[it]]) = ra[SET][it];            \
     }                                                                                       \
   }
+#define CCT_LOAD_A() CCT_LOAD_A_SET(0)
+#define CCT_STORE_A(BUF) CCT_STORE_A_SET(BUF, 0)
 
-  floatx16 acc[WM][WN];
+  constexpr int AR = M16 ? 4 : 16;  // accumulator registers per block
+  typedef float acc_t __attribute__((ext_vector_type(AR)));
+  acc_t acc[WM][WN];
 #pragma unroll
   for (int i = 0; i < WM; ++i)
 #pragma unroll
     for (int j = 0; j < WN; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+      for (int r = 0; r < AR; ++r) acc[i][j][r] = 0.f;
 
   // per-lane operand bases (float offsets): kernel row, and the cell of each owned position
-  const int am = wave_m * WM * 32 + lane_lo;
-  const int bn = wave_n * WN * 32 + lane_lo;
+  const int am = wave_m * WM * MB + lane_lo;
+  const int bn = wave_n * WN * MB + lane_lo;
   const int a_lds = am * CS + lane_hi * 4;
   int bbase[WN];
 #pragma unroll
   for (int j = 0; j < WN; ++j) {
-    const int col = n0 + bn + j * 32;
+    const int col = n0 + bn + j * MB;
     int cb = 0;
     if (col < ce) {
       const int n = col / P, pix = col - n * P;
@@ -236,21 +248,84 @@ __global__ __launch_bounds__(NT) void conv_fused_kc_f32(GemmTN p, KcGeom fg, int
   CCT_LOAD_A();
   CCT_STORE_A(0);
   __syncthreads();  // tap table, slot 0 and the first kernel tile are visible
-  if (ktiles > 1) CCT_LOAD_A();
+  if (M16) {
+    if (ktiles > 1) CCT_LOAD_A_SET(1);
+    if (ktiles > 2) CCT_LOAD_A_SET(0);
+  } else if (ktiles > 1) {
+    CCT_LOAD_A();
+  }
 
-  // operands: [q parity][block] of four reduction indices each
+  // operands: [q parity][block] of four reduction indices each (16-row form: [tile parity])
   f32x4 a[2][WM], b[2][WN];
   int boff[WN];     // float offset of the current tile's cells (slot + tap folded in)
 #pragma unroll
   for (int j = 0; j < WN; ++j) boff[j] = bbase[j] + tab[0];
 #pragma unroll
-  for (int i = 0; i < WM; ++i) a[0][i] = *reinterpret_cast<const f32x4*>(&As[a_lds + i * 32 * CS]);
+  for (int i = 0; i < WM; ++i) a[0][i] = *reinterpret_cast<const f32x4*>(&As[a_lds + i * MB * CS]);
 #pragma unroll
   for (int j = 0; j < WN; ++j) b[0][j] = *reinterpret_cast<const f32x4*>(&Xs[boff[j]]);
 
   int tt = 0;    // tap inside the current channel group
   int grp = 0;   // current channel group
   int slot = 0;  // ring slot of the current group
+  if constexpr (M16) {
+    // One 16-byte read per block feeds the four MFMA groups of a whole tile, so the operands of
+    // tile t+1 are fetched right after the barrier in the middle of tile t, into the other set.
+    // The kernel tile of t+1 goes to LDS behind the first MFMA group, and the registers it leaves
+    // are reloaded at once with tile t+3: tiles are short here, two of them stay in flight.
+#define CCT_MFMA16(SET, E)                                                                  \
+  {                                                                                         \
+    __builtin_amdgcn_sched_barrier(0);                                                      \
+    _Pragma("unroll") for (int i = 0; i < WM; ++i)                                          \
+      _Pragma("unroll") for (int j = 0; j < WN; ++j)                                        \
+        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[SET][i][E], b[SET][j][E],        \
+                                                         acc[i][j], 0, 0, 0);               \
+    __builtin_amdgcn_sched_barrier(0);                                                      \
+  }
+#define CCT_TILE16(CUR, NXT)                                                                \
+  {                                                                                         \
+    const int buf = t & 1;                                                                  \
+    const bool more = t + 1 < ktiles;                                                       \
+    int tt_n = tt + 1, grp_n = grp, slot_n = slot;                                          \
+    if (tt_n == fg.KK) {                                                                    \
+      tt_n = 0;                                                                             \
+      grp_n = grp + 1;                                                                      \
+      slot_n = slot ^ 1;                                                                    \
+    }                                                                                       \
+    CCT_MFMA16(CUR, 0);                                                                     \
+    if (more) CCT_STORE_A_SET(buf ^ 1, NXT);                                                \
+    if (t + 3 < ktiles) CCT_LOAD_A_SET(NXT);                                                \
+    CCT_MFMA16(CUR, 1);                                                                     \
+    if (more) {                                                                             \
+      if (tt == fg.KK - 1 && grp + 1 < fg.ngroups) CCT_STAGE_STORE(slot ^ 1);               \
+      if (tt == 0 && t > 0 && grp + 1 < fg.ngroups) CCT_STAGE_LOAD(grp + 1);                \
+      const int tapo = tab[tt_n] + slot_n * slot_floats;                                    \
+      _Pragma("unroll") for (int j = 0; j < WN; ++j) boff[j] = bbase[j] + tapo;             \
+    }                                                                                       \
+    __builtin_amdgcn_sched_barrier(0);                                                      \
+    __syncthreads();                                                                        \
+    if (more) {                                                                             \
+      _Pragma("unroll") for (int i = 0; i < WM; ++i) a[NXT][i] =                            \
+          *reinterpret_cast<const f32x4*>(&As[(buf ^ 1) * A_BUF + a_lds + i * MB * CS]);    \
+      _Pragma("unroll") for (int j = 0; j < WN; ++j) b[NXT][j] =                            \
+          *reinterpret_cast<const f32x4*>(&Xs[boff[j]]);                                    \
+    }                                                                                       \
+    CCT_MFMA16(CUR, 2);                                                                     \
+    CCT_MFMA16(CUR, 3);                                                                     \
+    tt = tt_n;                                                                              \
+    grp = grp_n;                                                                            \
+    slot = slot_n;                                                                          \
+    ++t;                                                                                    \
+  }
+    int t = 0;
+    while (t < ktiles) {
+      CCT_TILE16(0, 1);
+      if (t >= ktiles) break;
+      CCT_TILE16(1, 0);
+    }
+#undef CCT_TILE16
+#undef CCT_MFMA16
+  } else {
   for (int t = 0; t < ktiles; ++t) {
     const int buf = t & 1;
     const bool more = t + 1 < ktiles;
@@ -314,21 +389,29 @@ __global__ __launch_bounds__(NT) void conv_fused_kc_f32(GemmTN p, KcGeom fg, int
     grp = grp_n;
     slot = slot_n;
   }
+  }
 #undef CCT_MFMA_GROUP
 #undef CCT_LOAD_A
 #undef CCT_STORE_A
+#undef CCT_LOAD_A_SET
+#undef CCT_STORE_A_SET
 #undef CCT_STAGE_LOAD
 #undef CCT_STAGE_STORE
 
-  // ---- epilogue: Type-1 lifting + bias (same accumulator layout as the plain GEMM) -------------
-  const int mw = m0 + wave_m * WM * 32;
+  // ---- epilogue: Type-1 lifting + bias.  Accumulator register r of block row i is row
+  // i*32 + 8*(r/4) + 4*(lane/32) + r%4 of the wave's rows (32 x 32 blocks), or
+  // i*16 + 4*(lane/16) + r (16 x 16 blocks): four consecutive rows per lane either way.
+  const int mw = m0 + wave_m * WM * MB;
+  auto row_of = [&](int i, int r) {
+    return M16 ? i * 16 + lane_hi * 4 + r : i * 32 + (r >> 2) * 8 + (r & 3) + lane_hi * 4;
+  };
   if (p.d2s) {
     // depth-to-space: a lane's four consecutive rows are four sub-pixels of its grid position
     float* __restrict__ D = p.C;
     const int ss = p.dS * p.dS;
 #pragma unroll
     for (int j = 0; j < WN; ++j) {
-      const int col = n0 + bn + j * 32;
+      const int col = n0 + bn + j * MB;
       if (col >= ce) continue;
       const int n = col / P, pix = col - n * P;
       const int ga = pix / p.gWout, gb = pix - ga * p.gWout;
@@ -336,8 +419,8 @@ __global__ __launch_bounds__(NT) void conv_fused_kc_f32(GemmTN p, KcGeom fg, int
 #pragma unroll
       for (int i = 0; i < WM; ++i) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int m = mw + i * 32 + (r >> 2) * 8 + (r & 3) + lane_hi * 4;
+        for (int r = 0; r < AR; ++r) {
+          const int m = mw + row_of(i, r);
           if (m < p.M) {
             const int ci = fdiv_u(m, p.d_divSS_M, p.d_divSS_sh), rem = m - ci * ss;
             const int rh = fdiv_u(rem, p.d_divS_M, p.d_divS_sh), rw = rem - rh * p.dS;
@@ -355,15 +438,17 @@ __global__ __launch_bounds__(NT) void conv_fused_kc_f32(GemmTN p, KcGeom fg, int
   const bool full_m = m0 + BM <= p.M;
 #pragma unroll
   for (int j = 0; j < WN; ++j) {
-    const int col = n0 + bn + j * 32;
+    const int col = n0 + bn + j * MB;
     if (col >= ce) continue;
+    // one 64-bit base per column block (the lane's column and its first row); the row of each
+    // accumulator register is a uniform multiple of the row stride on top of it
     float* __restrict__ cl = C + col_offset(p.cmap, col) + (long long)(mw + lane_hi * 4) * p.c_ms;
     const float* bl = bias ? bias + mw + lane_hi * 4 : nullptr;
 #pragma unroll
     for (int i = 0; i < WM; ++i) {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = i * 32 + (r >> 2) * 8 + (r & 3);  // relative to mw + 4*lane_hi
+      for (int r = 0; r < AR; ++r) {
+        const int row = M16 ? i * 16 + r : i * 32 + (r >> 2) * 8 + (r & 3);  // relative to mw + 4*lane_hi
         if (full_m || mw + row + lane_hi * 4 < p.M) {
           float v = acc[i][j][r];
           if (bl) v += bl[row];
@@ -416,7 +501,7 @@ bool make_kc_geom(const GemmTN& p, int BM, KcGeom* fg, size_t* lds) {
 
 template <int BM, int WM, int WN>
 int launch_variant(const GemmTN& p, const KcGeom& fg, size_t lds, hipStream_t st) {
-  const int tiles_m = p.Mpad / BM;
+  const int tiles_m = BM == 48 ? 1 : p.Mpad / BM;
   const long long tn = fg.tpi > 0 ? (long long)fg.tpi * (p.Ncols / (p.gHout * p.gWout))
                                   : ((long long)p.Ncols + BN - 1) / BN;
   const long long blocks = (long long)tiles_m * tn;
@@ -506,6 +591,7 @@ static int kc_row_tile(const GemmTN& p, int* BNt) {
   int BM, BKt;
   gemm_tn_tile(p.M, p.Ncols, &BM, BNt, &BKt);
   if (BM == 96 && p.Mpad % 192 == 0) BM = 192;
+  if (p.M <= 48) BM = 48;  // 16 x 16 MFMA blocks: no work on padding rows beyond the 48th
   return BM;
 }
 
@@ -562,8 +648,10 @@ int launch_conv_fused_kc(const GemmTN& p0, hipStream_t st) {
   const int BM = kc_row_tile(p, &BNt);
   KcGeom fg;
   size_t lds;
-  if (BNt != BN || p.Mpad % BM || !make_kc_geom(p, BM, &fg, &lds)) return CCT_EUNSUPPORTED;
+  if (BNt != BN || (BM == 48 ? p.Mpad < 48 : p.Mpad % BM != 0) || !make_kc_geom(p, BM, &fg, &lds))
+    return CCT_EUNSUPPORTED;
   if (p.Kpad != (long long)fg.ngroups * CG * fg.KK) return CCT_EINVAL;
+  if (BM == 48) return launch_variant<48, 3, 2>(p, fg, lds, st);
   if (BM == 192) return launch_variant<192, 3, 2>(p, fg, lds, st);
   if (BM == 64) return launch_variant<64, 1, 2>(p, fg, lds, st);
   if (BM == 96) return launch_variant<96, 3, 1>(p, fg, lds, st);
