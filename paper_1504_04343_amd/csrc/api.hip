@@ -111,7 +111,61 @@ GemmTN strided_bwd_problem(const cct_conv_desc_t& d, const Geom& g, const void* 
   p.C = dxc;
   p.cmap = ColMap{1, 0};
   p.d2s = 1; p.dS = d.stride; p.dP = d.pad; p.dH = d.H; p.dW = d.W; p.dCg = g.Cg; p.dCtot = d.C;
+  p.bf16 = d.precision == CCT_PREC_BF16_IN_F32_ACC;
   p.prof_flops = 2.0 * (double)ni * d.O * g.Hout * g.Wout * g.Cg * d.K * d.K;
+  return p;
+}
+
+// Fused forward pass over `ni` images: Type-1 arithmetic, the B operand gathered from x.
+GemmTN fused_fwd_problem(const cct_conv_desc_t& d, const Geom& g, const void* pack, int Mpad, int Kpad,
+                         const float* xc, float* yc, const float* bias, long long ni) {
+  const long long P = (long long)g.Hout * g.Wout;
+  GemmTN p;
+  std::memset(&p, 0, sizeof(p));
+  p.A = pack;
+  p.Mpad = Mpad;
+  p.Kpad = Kpad;
+  p.a_gs = (long long)Mpad * Kpad;
+  p.B = xc;
+  p.bmap = ColMap{1, 0};  // not a plain matrix
+  p.gather = 1;
+  p.gC = d.C; p.gH = d.H; p.gW = d.W; p.gHout = g.Hout; p.gWout = g.Wout;
+  p.gs = d.stride; p.gp = d.pad; p.gCg = g.Cg; p.gK = d.K; p.gKK = d.K * d.K;
+  make_fastdiv_parts(p.gKK, &p.g_divKK_M, &p.g_divKK_sh);
+  make_fastdiv_parts(p.gK, &p.g_divK_M, &p.g_divK_sh);
+  p.M = g.Mr; p.Ncols = (int)(ni * g.Pc); p.Kdim = g.Kd; p.G = d.groups;
+  p.C = yc;
+  p.c_ms = P; p.c_gs = (long long)g.Og * P;
+  p.cmap = ColMap{(int)P, (long long)d.O * P};
+  p.bias = bias; p.bias_gs = g.Og;
+  p.bf16 = d.precision == CCT_PREC_BF16_IN_F32_ACC;
+  return p;
+}
+
+// Fused backward-data pass of a stride-1 layer over `ni` images: dx = convolution of dy (O channels,
+// Hout x Wout) with the flipped kernels, stride 1, pad K-1-p.
+GemmTN fused_bwd_problem(const cct_conv_desc_t& d, const Geom& g, const void* pack, int Mpad, int Kpad,
+                         const float* dyc, float* dxc, long long ni) {
+  const long long HW = (long long)d.H * d.W;
+  GemmTN p;
+  std::memset(&p, 0, sizeof(p));
+  p.A = pack;
+  p.Mpad = Mpad;
+  p.Kpad = Kpad;
+  p.a_gs = (long long)Mpad * Kpad;
+  p.B = dyc;
+  p.bmap = ColMap{1, 0};
+  p.gather = 1;
+  p.gC = d.O; p.gH = g.Hout; p.gW = g.Wout; p.gHout = d.H; p.gWout = d.W;
+  p.gs = 1; p.gp = d.K - 1 - d.pad; p.gCg = g.Og; p.gK = d.K; p.gKK = d.K * d.K;
+  make_fastdiv_parts(p.gKK, &p.g_divKK_M, &p.g_divKK_sh);
+  make_fastdiv_parts(p.gK, &p.g_divK_M, &p.g_divK_sh);
+  // the layout accepted this chunk size only if ni*H*W fits 31 bits
+  p.M = g.Cg; p.Ncols = (int)(ni * HW); p.Kdim = g.Og * d.K * d.K; p.G = d.groups;
+  p.C = dxc;
+  p.c_ms = HW; p.c_gs = (long long)g.Cg * HW;
+  p.cmap = ColMap{(int)HW, (long long)d.C * HW};
+  p.bf16 = d.precision == CCT_PREC_BF16_IN_F32_ACC;
   return p;
 }
 
@@ -157,10 +211,11 @@ bool make_layout(const cct_conv_desc_t& d, int pass, int type, const Geom& g, lo
     L->Kpad = (int)align_up(g.Kd, BK);
     long long kp = L->Kpad;
     if (type == CCT_LOWER_FUSED) {
-      const long long kc = conv_fused_kc_kpad(g.Cg, d.K);
+      const long long kc = conv_fused_kc_kpad(g.Cg, d.K, es == 2);
       if (kc >= kIntMax) return false;
       L->Kpad_kc = (int)kc;
       kp = std::max(kp, kc);
+      if (es == 2) L->Mpad = conv_fused_kc_bf16_mpad(g.Mr);  // the bf16 form has its own row tiles
     }
     take((long long)d.groups * L->Mpad * kp * es, &L->pack_off, &L->pack_bytes);
     if (type != CCT_LOWER_FUSED) {  // the fused layout has no D^T
@@ -174,8 +229,8 @@ bool make_layout(const cct_conv_desc_t& d, int pass, int type, const Geom& g, lo
       return false;
     int BM, BN, BK;
     gemm_tn_tile(sb.M, (int)(nc * sb.Ah * sb.Aw), &BM, &BN, &BK);
-    L->Mpad = (int)align_up(sb.M, BM);
-    const long long kc = conv_fused_kc_kpad(g.Og, sb.U);
+    L->Mpad = es == 2 ? conv_fused_kc_bf16_mpad(sb.M) : (int)align_up(sb.M, BM);
+    const long long kc = conv_fused_kc_kpad(g.Og, sb.U, es == 2);
     if (kc >= kIntMax) return false;
     L->Kpad = L->Kpad_kc = (int)kc;
     take((long long)d.groups * L->Mpad * kc * 4, &L->pack_off, &L->pack_bytes);
@@ -184,9 +239,9 @@ bool make_layout(const cct_conv_desc_t& d, int pass, int type, const Geom& g, lo
     if (nc * d.H * d.W >= kIntMax - 256) return false;
     int BM, BN, BK;
     gemm_tn_tile(g.Cg, (int)(nc * d.H * d.W), &BM, &BN, &BK);
-    L->Mpad = (int)align_up(g.Cg, BM);
+    L->Mpad = es == 2 ? conv_fused_kc_bf16_mpad(g.Cg) : (int)align_up(g.Cg, BM);
     L->Kpad = (int)align_up((long long)g.Og * d.K * d.K, BK);
-    const long long kc = conv_fused_kc_kpad(g.Og, d.K);
+    const long long kc = conv_fused_kc_kpad(g.Og, d.K, es == 2);
     if (kc >= kIntMax) return false;
     L->Kpad_kc = (int)kc;
     take((long long)d.groups * L->Mpad * std::max<long long>(L->Kpad, kc) * 4, &L->pack_off,
@@ -236,31 +291,47 @@ bool type_supported(const cct_conv_desc_t& d, int pass, int type) {
   if (type < CCT_LOWER_TYPE1 || type > CCT_LOWER_FUSED) return false;
   if (d.groups > 65535) return false;  // groups are the second grid dimension of every GEMM launch
   if (type == CCT_LOWER_FUSED) {
-    if (d.precision != CCT_PREC_F32) return false;
+    const bool bf16 = d.precision == CCT_PREC_BF16_IN_F32_ACC;
+    const Geom gg = make_geom(d, CCT_LOWER_FUSED);
     // backward-weights: the input rows of 32 positions must fit in LDS; an unpadded layer can
-    // also gather its lowered rows inside the split-K GEMM
+    // also gather its lowered rows inside the split-K GEMM (fp32 operands only)
     if (pass == CCT_PASS_BACKWARD_WEIGHTS) {
-      const int Ho = (d.H + 2 * d.pad - d.K) / d.stride + 1, Wo = (d.W + 2 * d.pad - d.K) / d.stride + 1;
-      if (!conv_bwdw_fused_fits(d.C, d.H, d.W, d.K, d.stride, d.pad, Ho, Wo, d.C / d.groups,
-                                d.O / d.groups, d.O) &&
-          !(d.pad == 0 && gemm_nt_gather_fits(d.C, d.H, d.W, d.O, Ho, Wo)))
+      if (bf16) return false;
+      if (!conv_bwdw_fused_fits(d.C, d.H, d.W, d.K, d.stride, d.pad, gg.Hout, gg.Wout, gg.Cg, gg.Og,
+                                d.O) &&
+          !(d.pad == 0 && gemm_nt_gather_fits(d.C, d.H, d.W, d.O, gg.Hout, gg.Wout)))
+        return false;
+    }
+    // with bf16 operands only the channel-contiguous kernel exists (fp32 falls back to the other
+    // fused forms when it cannot stage a shape)
+    if (pass == CCT_PASS_FORWARD && bf16) {
+      const long long kc = conv_fused_kc_kpad(gg.Cg, d.K, bf16);
+      if (kc >= kIntMax || (long long)gg.Pc >= kIntMax ||
+          !conv_fused_kc_bf16_fits(fused_fwd_problem(d, gg, nullptr, conv_fused_kc_bf16_mpad(gg.Mr),
+                                                     (int)kc, nullptr, nullptr, nullptr, 1)))
         return false;
     }
     // backward-data is fused as a convolution of dy with the flipped kernels (stride 1), or with
     // the s*s sub-kernels of a strided layer when the channel-contiguous kernel can stage it
     if (pass == CCT_PASS_BACKWARD_DATA && d.stride == 1 && d.pad > d.K - 1) return false;
+    if (pass == CCT_PASS_BACKWARD_DATA && d.stride == 1 && bf16) {
+      const long long kc = conv_fused_kc_kpad(gg.Og, d.K, bf16);
+      if (kc >= kIntMax || (long long)d.H * d.W >= kIntMax ||
+          !conv_fused_kc_bf16_fits(fused_bwd_problem(d, gg, nullptr, conv_fused_kc_bf16_mpad(gg.Cg),
+                                                     (int)kc, nullptr, nullptr, 1)))
+        return false;
+    }
     if (pass == CCT_PASS_BACKWARD_DATA && d.stride > 1) {
-      const Geom gg = make_geom(d, CCT_LOWER_FUSED);
       const StridedBwd sb = strided_bwd(d, gg);
       if ((long long)gg.Cg * d.stride * d.stride >= kIntMax || (long long)sb.Ah * sb.Aw >= kIntMax)
         return false;
       int BM, BN, BK;
       gemm_tn_tile(sb.M, sb.Ah * sb.Aw, &BM, &BN, &BK);
-      const long long kc = conv_fused_kc_kpad(gg.Og, sb.U);
+      const long long kc = conv_fused_kc_kpad(gg.Og, sb.U, bf16);
       if (kc >= kIntMax) return false;
-      if (!conv_fused_kc_fits(strided_bwd_problem(d, gg, nullptr, (int)align_up(sb.M, BM), (int)kc,
-                                                  nullptr, nullptr, 1)))
-        return false;
+      const int mpad = bf16 ? conv_fused_kc_bf16_mpad(sb.M) : (int)align_up(sb.M, BM);
+      const GemmTN p = strided_bwd_problem(d, gg, nullptr, mpad, (int)kc, nullptr, nullptr, 1);
+      if (!(bf16 ? conv_fused_kc_bf16_fits(p) : conv_fused_kc_fits(p))) return false;
     }
     if ((long long)d.C * d.H * d.W >= kIntMax) return false;  // 32-bit offsets inside one image
   }
@@ -632,32 +703,16 @@ int forward_on_workspace(const cct_conv_desc_t* desc, const float* x, const floa
 
   // the fused pass: the operand description of one chunk (lowering, multiply and lifting in one
   // kernel: the GEMM gathers its B tiles from x)
-  auto fused_chunk = [&](const float* xc, float* yc, long long ncols, bool kc) {
-    GemmTN p;
-    std::memset(&p, 0, sizeof(p));
-    p.A = ws + L.pack_off;
-    p.Mpad = L.Mpad;
-    p.Kpad = kc ? L.Kpad_kc : L.Kpad;
-    p.a_gs = (long long)p.Mpad * p.Kpad;
-    p.B = xc;
-    p.bmap = ColMap{1, 0};  // not a plain matrix
-    p.gather = 1;
-    p.gC = d.C; p.gH = d.H; p.gW = d.W; p.gHout = g.Hout; p.gWout = g.Wout;
-    p.gs = d.stride; p.gp = d.pad; p.gCg = g.Cg; p.gK = d.K; p.gKK = d.K * d.K;
-    make_fastdiv_parts(p.gKK, &p.g_divKK_M, &p.g_divKK_sh);
-    make_fastdiv_parts(p.gK, &p.g_divK_M, &p.g_divK_sh);
-    p.M = g.Mr; p.Ncols = (int)ncols; p.Kdim = g.Kd; p.G = d.groups;
-    p.C = yc;
-    p.c_ms = P; p.c_gs = (long long)g.Og * P;
-    p.cmap = ColMap{(int)P, (long long)d.O * P};
-    p.bias = bias; p.bias_gs = g.Og;
-    return p;
+  auto fused_chunk = [&](const float* xc, float* yc, long long ni, bool kc) {
+    return fused_fwd_problem(d, g, ws + L.pack_off, L.Mpad, kc ? L.Kpad_kc : L.Kpad, xc, yc, bias, ni);
   };
   // channel-contiguous form of the fused kernel when the shape allows it (it has its own pack)
-  const bool kc = type == CCT_LOWER_FUSED && conv_fused_kc_fits(fused_chunk(x, y, nc * g.Pc, true));
+  const bool kc = type == CCT_LOWER_FUSED &&
+                  (bf16 ? conv_fused_kc_bf16_fits(fused_chunk(x, y, nc, true))
+                        : conv_fused_kc_fits(fused_chunk(x, y, nc, true)));
+  if (type == CCT_LOWER_FUSED && bf16 && !kc) return CCT_EUNSUPPORTED;
   if (kc)
-    rc = launch_pack_fused_kc(w, reinterpret_cast<float*>(ws + L.pack_off), d.groups, g.Og, g.Cg, d.K,
-                              L.Mpad, 0, st);
+    rc = launch_pack_fused_kc(w, ws + L.pack_off, d.groups, g.Og, g.Cg, d.K, L.Mpad, 0, bf16, st);
   else
     rc = launch_pack_kernel_matrix(w, ws + L.pack_off, make_pack(d, g, L, 0), st);
   if (rc) return rc;
@@ -667,9 +722,9 @@ int forward_on_workspace(const cct_conv_desc_t* desc, const float* x, const floa
     const float* xc = x + n0 * d.C * d.H * d.W;
     float* yc = y + n0 * d.O * P;
     if (type == CCT_LOWER_FUSED) {
-      const GemmTN p = fused_chunk(xc, yc, ncols, kc);
+      const GemmTN p = fused_chunk(xc, yc, ni, kc);
       if (kc) {
-        rc = launch_conv_fused_kc(p, st);
+        rc = bf16 ? launch_conv_fused_kc_bf16(p, st) : launch_conv_fused_kc(p, st);
       } else {
         rc = launch_conv_fused(p, st);                            // LDS-staged lowering
         if (rc == CCT_EUNSUPPORTED) rc = launch_gemm_tn(p, st);  // else gather-fed GEMM
@@ -759,13 +814,14 @@ int cct_conv_backward_data(const cct_conv_desc_t* desc, const float* w, const fl
 
   if (type == CCT_LOWER_FUSED && d.stride > 1) {
     // one kernel per chunk: the s*s residue classes of dx as one stride-1 convolution of dy
-    float* pack = reinterpret_cast<float*>(ws + L.pack_off);
-    rc = launch_pack_fused_kc_strided(w, pack, d.groups, g.Og, g.Cg, d.K, d.stride, L.Mpad, st);
+    void* pack = ws + L.pack_off;
+    rc = launch_pack_fused_kc_strided(w, pack, d.groups, g.Og, g.Cg, d.K, d.stride, L.Mpad, bf16, st);
     if (rc) return rc;
     for (long long n0 = 0; n0 < d.N; n0 += nc) {
       const long long ni = std::min<long long>(nc, d.N - n0);
-      rc = launch_conv_fused_kc(strided_bwd_problem(d, g, pack, L.Mpad, L.Kpad_kc, dy + n0 * d.O * P,
-                                                    dx + n0 * d.C * HW, ni), st);
+      const GemmTN p = strided_bwd_problem(d, g, pack, L.Mpad, L.Kpad_kc, dy + n0 * d.O * P,
+                                           dx + n0 * d.C * HW, ni);
+      rc = bf16 ? launch_conv_fused_kc_bf16(p, st) : launch_conv_fused_kc(p, st);
       if (rc) return rc;
     }
     return CCT_OK;
@@ -774,30 +830,13 @@ int cct_conv_backward_data(const cct_conv_desc_t* desc, const float* w, const fl
     // one kernel per chunk: dx = convolution of dy (O channels, Hout x Wout) with the flipped
     // kernels, stride 1, pad K-1-p; lowering of dy happens in LDS (or as a gather), never in HBM
     auto fused_chunk = [&](const float* dyc, float* dxc, long long ni, bool kc) {
-      GemmTN p;
-      std::memset(&p, 0, sizeof(p));
-      p.A = ws + L.pack_off;
-      p.Mpad = L.Mpad;
-      p.Kpad = kc ? L.Kpad_kc : L.Kpad;
-      p.a_gs = (long long)p.Mpad * p.Kpad;
-      p.B = dyc;
-      p.bmap = ColMap{1, 0};
-      p.gather = 1;
-      p.gC = d.O; p.gH = g.Hout; p.gW = g.Wout; p.gHout = d.H; p.gWout = d.W;
-      p.gs = 1; p.gp = d.K - 1 - d.pad; p.gCg = g.Og; p.gK = d.K; p.gKK = d.K * d.K;
-      make_fastdiv_parts(p.gKK, &p.g_divKK_M, &p.g_divKK_sh);
-      make_fastdiv_parts(p.gK, &p.g_divK_M, &p.g_divK_sh);
-      // make_layout accepted this chunk size only if ni*H*W fits 31 bits
-      p.M = g.Cg; p.Ncols = (int)(ni * HW); p.Kdim = g.Og * d.K * d.K; p.G = d.groups;
-      p.C = dxc;
-      p.c_ms = HW; p.c_gs = (long long)g.Cg * HW;
-      p.cmap = ColMap{(int)HW, (long long)d.C * HW};
-      return p;
+      return fused_bwd_problem(d, g, ws + L.pack_off, L.Mpad, kc ? L.Kpad_kc : L.Kpad, dyc, dxc, ni);
     };
-    const bool kc = conv_fused_kc_fits(fused_chunk(dy, dx, nc, true));
+    const bool kc = bf16 ? conv_fused_kc_bf16_fits(fused_chunk(dy, dx, nc, true))
+                         : conv_fused_kc_fits(fused_chunk(dy, dx, nc, true));
+    if (bf16 && !kc) return CCT_EUNSUPPORTED;
     if (kc)
-      rc = launch_pack_fused_kc(w, reinterpret_cast<float*>(ws + L.pack_off), d.groups, g.Og, g.Cg,
-                                d.K, L.Mpad, 1, st);
+      rc = launch_pack_fused_kc(w, ws + L.pack_off, d.groups, g.Og, g.Cg, d.K, L.Mpad, 1, bf16, st);
     else
       rc = launch_pack_flipped(w, reinterpret_cast<float*>(ws + L.pack_off), d.groups, g.Og, g.Cg,
                                d.K, L.Mpad, L.Kpad, st);
@@ -806,7 +845,7 @@ int cct_conv_backward_data(const cct_conv_desc_t* desc, const float* w, const fl
       const long long ni = std::min<long long>(nc, d.N - n0);
       const GemmTN p = fused_chunk(dy + n0 * d.O * P, dx + n0 * d.C * HW, ni, kc);
       if (kc) {
-        rc = launch_conv_fused_kc(p, st);
+        rc = bf16 ? launch_conv_fused_kc_bf16(p, st) : launch_conv_fused_kc(p, st);
       } else {
         rc = launch_conv_fused(p, st);
         if (rc == CCT_EUNSUPPORTED) rc = launch_gemm_tn(p, st);

@@ -118,16 +118,23 @@ int launch_conv_fused(const GemmTN& p, hipStream_t st);
 // kernels of the fused backward-data pass.  conv_fused_kc_fits: can it run this problem
 // (p filled as for launch_conv_fused)?
 bool conv_fused_kc_fits(const GemmTN& p);
-long long conv_fused_kc_kpad(int channels_per_group, int K);
-int launch_pack_fused_kc(const float* w, float* pack, int G, int Og, int Cg, int K, int Mpad,
-                         int flipped, hipStream_t st);
+// The bf16 form pads the K tiles (taps x groups) of a pack to a multiple of eight with zero tiles.
+long long conv_fused_kc_kpad(int channels_per_group, int K, int bf16);
+// `bf16`: the pack holds bf16 values (rounded to nearest even) for the bf16 form of the kernel.
+int launch_pack_fused_kc(const float* w, void* pack, int G, int Og, int Cg, int K, int Mpad,
+                         int flipped, int bf16, hipStream_t st);
 // Kernel pack of the strided backward-data pass computed as a stride-1 convolution of dy with
 // s*s sub-kernels of U x U taps, U = ceil(K/s): rows m = (ci*s + rh)*s + rw, channels = kernels oo,
 // pack[q][grp][(u',v')][m][c] = w[q*Og + grp*16 + c, ci, rh + s*(U-1-u'), rw + s*(U-1-v')] (0 where
 // that tap index is >= K).
-int launch_pack_fused_kc_strided(const float* w, float* pack, int G, int Og, int Cg, int K, int s,
-                                 int Mpad, hipStream_t st);
+int launch_pack_fused_kc_strided(const float* w, void* pack, int G, int Og, int Cg, int K, int s,
+                                 int Mpad, int bf16, hipStream_t st);
 int launch_conv_fused_kc(const GemmTN& p, hipStream_t st);
+// The bf16-operand form (conv_fused_kc_bf16.hip): p.bf16 set, the pack in bf16 with its rows padded
+// to conv_fused_kc_bf16_mpad(M); x / dy stay fp32 and are rounded while they are staged.
+int conv_fused_kc_bf16_mpad(int M);
+bool conv_fused_kc_bf16_fits(const GemmTN& p);
+int launch_conv_fused_kc_bf16(const GemmTN& p, hipStream_t st);
 // Fused backward-weights pass: split partial products of dy (NCHW, read in place) with the
 // Type-1 lowering of x built in LDS.  Cpart[s][q][oo][(ci,i,j)], compact, S splits of split_len
 // positions (a multiple of 32) over the nimg*Hout*Wout positions.

@@ -31,27 +31,15 @@
 #include <algorithm>
 
 #include "cct_internal.h"
+#include "conv_fused_kc_common.h"
 #include "gemm_common.h"
+#include "index_common.h"
 
 namespace cct {
 namespace {
 
-constexpr int NT = 256;
-constexpr int BN = 128;
-constexpr int CG = 16;        // channels per group = reduction indices per K tile
+using namespace kc;
 constexpr int CS = CG + 4;    // floats between cells / kernel rows in LDS
-constexpr int QU = 2;         // cells per thread and slot (R <= QU*256)
-constexpr int kLdsCap = 80 * 1024;  // two workgroups per CU
-
-struct KcGeom {
-  int Wp;       // padded row width W + 2*pad (cells per staged row)
-  int R;        // cells reserved per slot (multiple of 64, >= any workgroup's need)
-  int ngroups;  // channel groups of 16
-  int KK;       // taps
-  int tpi;      // > 0: column tiles never cross an image, tpi tiles per image (the last one
-                // partly empty); used when the rows of a tile that spans two images would not
-                // fit the staging area.  0: tiles are cut from the positions of the whole chunk.
-};
 
 template <int BM, int WM, int WN>
 __global__ __launch_bounds__(NT) void conv_fused_kc_f32(GemmTN p, KcGeom fg, int tiles_m,
@@ -459,44 +447,8 @@ __global__ __launch_bounds__(NT) void conv_fused_kc_f32(GemmTN p, KcGeom fg, int
   }
 }
 
-// Geometry and LDS need; false = this form cannot run the shape.
 bool make_kc_geom(const GemmTN& p, int BM, KcGeom* fg, size_t* lds) {
-  if (!p.gather || p.bf16 || p.tapmajor || p.gK < 2 || p.gCg < 1) return false;
-  fg->KK = p.gK * p.gK;
-  // staged row width: the padded input row, or what the last grid column's window reaches if the
-  // caller's grid is wider than the convolution arithmetic gives (columns beyond the input load
-  // as zeros like any padding)
-  fg->Wp = std::max(p.gW + 2 * p.gp, (p.gWout - 1) * p.gs + p.gK);
-  fg->ngroups = (p.gCg + CG - 1) / CG;
-  // channels are padded to whole groups of 16: not worth it when that wastes over an eighth
-  if ((long long)fg->ngroups * CG * 8 > (long long)p.gCg * 9) return false;
-  const long long P = (long long)p.gHout * p.gWout;
-  // rows of padded input that 128 consecutive positions can touch: at most A output rows spread
-  // over at most T images; t images need (A - t)*stride + t*K rows, largest at t = 1 or t = T
-  const long long A = (BN - 1) / p.gWout + 2, T = (BN - 1) / P + 2;
-  const long long r1 = (A - 1) * p.gs + p.gK;
-  const long long rT = (A > T ? A - T : 0) * p.gs + T * p.gK;
-  auto cells = [&](long long rows) { return (rows * fg->Wp + 63) / 64 * 64; };
-  auto lds_of = [&](long long R) { return 4LL * (2LL * BM * CS + 2LL * R * CS + fg->KK); };
-  long long R = cells(r1 > rT ? r1 : rT);
-  fg->tpi = 0;
-  if (R > QU * NT || lds_of(R) > kLdsCap) {
-    // tiles cut per image need the rows of one image only; worth it while the partly empty last
-    // tile of an image wastes less than a tenth of the launch
-    const long long tpi = (P + BN - 1) / BN;
-    const long long rows1 = (A < p.gHout ? A - 1 : p.gHout - 1) * p.gs + p.gK;
-    R = cells(rows1);
-    if (tpi * BN * 10 > P * 11 || tpi * ((double)p.Ncols / P) >= 2147483647.0) return false;
-    fg->tpi = (int)tpi;
-  }
-  if (R > QU * NT) return false;
-  fg->R = (int)R;
-  // staged cells are addressed with 32-bit byte offsets from the workgroup's first image
-  if ((T + 1) * p.gC * p.gH * p.gW >= (1LL << 29)) return false;
-  const long long need = lds_of(R);
-  if (need > kLdsCap) return false;
-  *lds = (size_t)need;
-  return true;
+  return !p.bf16 && kc::make_geom(p, BM, CS * 4, fg, lds);
 }
 
 template <int BM, int WM, int WN>
@@ -527,12 +479,16 @@ int launch_variant(const GemmTN& p, const KcGeom& fg, size_t lds, hipStream_t st
 //                           value w[q*Og + m, grp*16 + c, i, j],            tap = i*K + j
 //   backward-data (flipped): m = input channel ci < Cg, channel = kernel oo < Og,
 //                           value w[q*Og + grp*16 + c, m, K-1-i, K-1-j],    tap = i*K + j
+// BF16: the pack holds bf16 values (rounded to nearest even) instead of fp32.
+template <bool BF16>
 __global__ __launch_bounds__(256) void pack_fused_kc_kernel(const float* __restrict__ w,
-                                                            float* __restrict__ pack, int G, int Og,
-                                                            int Cg, int K, int Mpad, int ngroups,
+                                                            void* __restrict__ pack, int G, int Og,
+                                                            int Cg, int K, int Mpad, int ktiles,
                                                             int flipped) {
+  // ktiles >= groups of 16 channels x taps; tiles beyond that product decode to channels past the
+  // last one and are written as zeros
   const int KK = K * K;
-  const long long per_group = (long long)ngroups * KK * Mpad * CG;
+  const long long per_group = (long long)ktiles * Mpad * CG;
   const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
   if (t >= per_group * G) return;
   const int q = (int)(t / per_group);
@@ -551,16 +507,17 @@ __global__ __launch_bounds__(256) void pack_fused_kc_kernel(const float* __restr
     if (m < Cg && ch < Og)
       v = w[((((long long)q * Og + ch) * Cg + m) * K + (K - 1 - i)) * K + (K - 1 - j)];
   }
-  pack[t] = v;
+  store_elem<BF16>(pack, t, v);
 }
 
 // Kernel pack of the strided backward-data pass (see launch_pack_fused_kc_strided).
+template <bool BF16>
 __global__ __launch_bounds__(256) void pack_fused_kc_strided_kernel(const float* __restrict__ w,
-                                                                    float* __restrict__ pack, int G,
+                                                                    void* __restrict__ pack, int G,
                                                                     int Og, int Cg, int K, int s, int U,
-                                                                    int Mpad, int ngroups) {
+                                                                    int Mpad, int ktiles) {
   const int UU = U * U;
-  const long long per_group = (long long)ngroups * UU * Mpad * CG;
+  const long long per_group = (long long)ktiles * Mpad * CG;
   const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
   if (t >= per_group * G) return;
   const int q = (int)(t / per_group);
@@ -579,7 +536,7 @@ __global__ __launch_bounds__(256) void pack_fused_kc_strided_kernel(const float*
     const int i = rh + s * (U - 1 - up), j = rw + s * (U - 1 - vp);
     if (i < K && j < K) v = w[((((long long)q * Og + oo) * Cg + ci) * K + i) * K + j];
   }
-  pack[t] = v;
+  store_elem<BF16>(pack, t, v);
 }
 
 }  // namespace
@@ -603,33 +560,47 @@ bool conv_fused_kc_fits(const GemmTN& p) {
   return BNt == BN && make_kc_geom(p, BM, &fg, &lds);
 }
 
-long long conv_fused_kc_kpad(int channels_per_group, int K) {
-  return (long long)((channels_per_group + CG - 1) / CG) * CG * K * K;
+long long conv_fused_kc_kpad(int channels_per_group, int K, int bf16) {
+  const long long ktiles = (long long)((channels_per_group + CG - 1) / CG) * K * K;
+  return (bf16 ? (ktiles + 7) / 8 * 8 : ktiles) * CG;
 }
 
-int launch_pack_fused_kc(const float* w, float* pack, int G, int Og, int Cg, int K, int Mpad,
-                         int flipped, hipStream_t st) {
-  const int ngroups = ((flipped ? Og : Cg) + CG - 1) / CG;
-  const long long total = (long long)G * ngroups * K * K * Mpad * CG;
+int launch_pack_fused_kc(const float* w, void* pack, int G, int Og, int Cg, int K, int Mpad,
+                         int flipped, int bf16, hipStream_t st) {
+  const long long kt = conv_fused_kc_kpad(flipped ? Og : Cg, K, bf16) / CG;
+  if (kt >= 2147483647LL) return CCT_EUNSUPPORTED;
+  const int ktiles = (int)kt;
+  const long long total = (long long)G * ktiles * Mpad * CG;
   const long long blocks = (total + 255) / 256;
   if (blocks <= 0 || blocks >= 2147483647LL) return CCT_EUNSUPPORTED;
-  ProfScope ps("pack_fused_kc_kernel", 0.0, 4.0 * G * Og * Cg * K * K + 4.0 * total, st);
-  hipLaunchKernelGGL(pack_fused_kc_kernel, dim3((unsigned)blocks), dim3(256), 0, st, w, pack, G, Og,
-                     Cg, K, Mpad, ngroups, flipped);
+  ProfScope ps("pack_fused_kc_kernel", 0.0, 4.0 * G * Og * Cg * K * K + (bf16 ? 2.0 : 4.0) * total, st);
+  if (bf16)
+    hipLaunchKernelGGL(pack_fused_kc_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, st, w, pack, G,
+                       Og, Cg, K, Mpad, ktiles, flipped);
+  else
+    hipLaunchKernelGGL(pack_fused_kc_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, st, w, pack, G,
+                       Og, Cg, K, Mpad, ktiles, flipped);
   CCT_CHECK_LAUNCH();
   return CCT_OK;
 }
 
-int launch_pack_fused_kc_strided(const float* w, float* pack, int G, int Og, int Cg, int K, int s,
-                                 int Mpad, hipStream_t st) {
+int launch_pack_fused_kc_strided(const float* w, void* pack, int G, int Og, int Cg, int K, int s,
+                                 int Mpad, int bf16, hipStream_t st) {
   const int U = (K + s - 1) / s;
-  const int ngroups = (Og + CG - 1) / CG;
-  const long long total = (long long)G * ngroups * U * U * Mpad * CG;
+  const long long kt = conv_fused_kc_kpad(Og, U, bf16) / CG;
+  if (kt >= 2147483647LL) return CCT_EUNSUPPORTED;
+  const int ktiles = (int)kt;
+  const long long total = (long long)G * ktiles * Mpad * CG;
   const long long blocks = (total + 255) / 256;
   if (blocks <= 0 || blocks >= 2147483647LL) return CCT_EUNSUPPORTED;
-  ProfScope ps("pack_fused_kc_strided_kernel", 0.0, 4.0 * G * Og * Cg * K * K + 4.0 * total, st);
-  hipLaunchKernelGGL(pack_fused_kc_strided_kernel, dim3((unsigned)blocks), dim3(256), 0, st, w, pack,
-                     G, Og, Cg, K, s, U, Mpad, ngroups);
+  ProfScope ps("pack_fused_kc_strided_kernel", 0.0,
+               4.0 * G * Og * Cg * K * K + (bf16 ? 2.0 : 4.0) * total, st);
+  if (bf16)
+    hipLaunchKernelGGL(pack_fused_kc_strided_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, st, w,
+                       pack, G, Og, Cg, K, s, U, Mpad, ktiles);
+  else
+    hipLaunchKernelGGL(pack_fused_kc_strided_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, st, w,
+                       pack, G, Og, Cg, K, s, U, Mpad, ktiles);
   CCT_CHECK_LAUNCH();
   return CCT_OK;
 }

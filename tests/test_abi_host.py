@@ -183,10 +183,20 @@ def test_fused_support_rules(B):
     assert supported(conv3, B.PASS_BACKWARD_WEIGHTS)       # rows staged in LDS
     padded_wide = (2, 6, 14, 400, 9, 4, 3, 1, 3)            # padded, rows too wide for LDS staging
     assert not supported(padded_wide, B.PASS_BACKWARD_WEIGHTS)
-    # bf16 has no fused path at all
-    d = B.make_desc(*conv3, lowering=B.LOWER_FUSED, precision=B.PREC_BF16_IN_F32_ACC)
-    with pytest.raises(B.CctError):
-        B.cct_conv_workspace_bytes(d, B.PASS_FORWARD)
+    # bf16 operands: only the channel-contiguous kernel exists, so forward and backward-data of
+    # layers with enough channels per group; never backward-weights, never conv1's 3 channels
+    def supported_bf16(desc_args, p):
+        d = B.make_desc(*desc_args, lowering=B.LOWER_FUSED, precision=B.PREC_BF16_IN_F32_ACC)
+        try:
+            B.cct_conv_workspace_bytes(d, p)
+            return True
+        except B.CctError as e:
+            assert e.code == B.EUNSUPPORTED
+            return False
+    assert supported_bf16(conv3, B.PASS_FORWARD) and supported_bf16(conv3, B.PASS_BACKWARD_DATA)
+    assert not supported_bf16(conv3, B.PASS_BACKWARD_WEIGHTS)
+    assert not supported_bf16(conv1, B.PASS_FORWARD)
+    assert supported_bf16(conv1, B.PASS_BACKWARD_DATA)     # 96 kernels = 6 groups of 16 on the reduction side
 
 
 def test_type2_backward_data_needs_no_inverse_lifted_matrix(B):

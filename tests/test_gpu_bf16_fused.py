@@ -1,0 +1,118 @@
+"""The bf16-operand variant without a lowered matrix: forward and backward-data through the
+channel-contiguous fused kernel with bf16 operands and fp32 accumulation.
+
+Two bars.  Against the fp64 oracle on the unrounded inputs: the variant's 2e-2.  And a sharper
+one: the kernel rounds x (or dy) and w to bf16, round to nearest even, and accumulates in fp32;
+products of bf16 values are exact in fp32, so against the oracle applied to inputs rounded the same
+way on the host the result must agree to fp32 accuracy -- a wrong rounding mode, a dropped channel
+of a cell or a mismatched operand half fails this one by orders of magnitude."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_1504_04343_amd import synth
+from gpu_util import (TOL_BF16, TOL_F32, desc_of, gpu_backward_data, gpu_forward, layer, odims, rel_err)
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_1504_04343_amd import binding
+    return binding
+
+
+def bf16_rne(a):
+    """fp32 array rounded to the nearest bf16 value (ties to even), returned as fp32."""
+    u = np.ascontiguousarray(a, np.float32).view(np.uint32).astype(np.uint64)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+    return u.astype(np.uint32).view(np.float32).reshape(a.shape)
+
+
+# name, N, C, H, W, O, K, s, p, g
+SHAPES = [
+    layer("conv2_like", 2, 96, 27, 27, 256, 5, 1, 2, 2),       # 3 channel groups, tiles cut per image
+    layer("conv3_like", 3, 64, 13, 13, 384, 3, 1, 1, 1),       # 3 row tiles; column tiles span images
+    layer("ragged", 3, 30, 11, 9, 72, 3, 1, 1, 1),             # 30 of 32 channels, 72 of 128 rows, H != W
+    layer("small_m", 2, 16, 10, 12, 40, 3, 1, 0, 1),           # 64-row form, unpadded
+    layer("k2_pad1", 2, 32, 9, 9, 64, 2, 1, 1, 1),             # even kernel, output larger than input
+    layer("one_image", 1, 48, 7, 7, 128, 3, 1, 1, 1),          # fewer positions than one column tile
+]
+STRIDED = [
+    layer("s2_k3", 3, 16, 15, 17, 32, 3, 2, 1, 1),
+    layer("s2_k5_g2", 2, 8, 21, 19, 64, 5, 2, 2, 2),
+    layer("s4_k11_p1", 2, 3, 51, 47, 48, 11, 4, 1, 1),         # conv1-like with padding
+    layer("s2_k4_deep", 2, 4, 18, 14, 80, 4, 2, 1, 1),
+]
+
+
+def supported(B, L, p):
+    try:
+        B.cct_conv_workspace_bytes(desc_of(B, L, B.LOWER_FUSED, B.PREC_BF16_IN_F32_ACC), p)
+        return True
+    except B.CctError as e:
+        assert e.code == B.EUNSUPPORTED
+        return False
+
+
+@pytest.mark.parametrize("L", SHAPES, ids=[L.name for L in SHAPES])
+def test_forward_bf16_fused(B, L):
+    assert supported(B, L, B.PASS_FORWARD)
+    x, w, b = synth.make_x(L, 3), synth.make_w(L, 3), synth.make_bias(L, 3)
+    od = odims(oracle, L)
+    got = gpu_forward(B, L, x, w, b, B.LOWER_FUSED, B.PREC_BF16_IN_F32_ACC)
+    assert np.isfinite(got).all()                   # NaN prefill: every output was written
+    assert rel_err(got, oracle.conv_forward(od, x, w, b)) <= TOL_BF16
+    assert rel_err(got, oracle.conv_forward(od, bf16_rne(x), bf16_rne(w), b)) <= TOL_F32
+    assert np.array_equal(got, gpu_forward(B, L, x, w, b, B.LOWER_FUSED, B.PREC_BF16_IN_F32_ACC, chunk=1))
+
+
+@pytest.mark.parametrize("L", SHAPES + STRIDED, ids=[L.name for L in SHAPES + STRIDED])
+def test_backward_data_bf16_fused(B, L):
+    w, dy = synth.make_w(L, 5), synth.make_dy(L, 5)
+    if not supported(B, L, B.PASS_BACKWARD_DATA):
+        # the kernels of a group do not fill whole groups of 16 well enough: AUTO takes another layout
+        assert L.name == "small_m"
+        with pytest.raises(B.CctError) as e:
+            gpu_backward_data(B, L, w, dy, B.LOWER_FUSED, B.PREC_BF16_IN_F32_ACC)
+        assert e.value.code == B.EUNSUPPORTED
+        got = gpu_backward_data(B, L, w, dy, B.LOWER_AUTO, B.PREC_BF16_IN_F32_ACC)
+        assert rel_err(got, oracle.conv_backward_data(odims(oracle, L), w, dy)) <= TOL_BF16
+        return
+    od = odims(oracle, L)
+    got = gpu_backward_data(B, L, w, dy, B.LOWER_FUSED, B.PREC_BF16_IN_F32_ACC)
+    assert np.isfinite(got).all()
+    assert rel_err(got, oracle.conv_backward_data(od, w, dy)) <= TOL_BF16
+    assert rel_err(got, oracle.conv_backward_data(od, bf16_rne(w), bf16_rne(dy))) <= TOL_F32
+    assert np.array_equal(got, gpu_backward_data(B, L, w, dy, B.LOWER_FUSED, B.PREC_BF16_IN_F32_ACC, chunk=1))
+
+
+def test_staging_rounds_to_nearest_even(B):
+    """A 1-tap-like probe of the rounding done while x is staged: with kernels that pick single
+    channels (weights 1, exactly representable) y is x rounded to bf16, so it must equal the host's
+    round-to-nearest-even bit for bit, ties included."""
+    L = layer("probe", 1, 16, 6, 6, 16, 2, 1, 0, 1)
+    rng = np.random.default_rng(11)
+    x = rng.standard_normal((1, 16, 6, 6)).astype(np.float32)
+    # plant exact ties (low 16 bits = 0x8000) with even and odd upper halves, and values just off them
+    u = x.view(np.uint32).copy().ravel()
+    u[0::5] = (u[0::5] & 0xFFFF0000) | 0x8000
+    u[1::5] = (u[1::5] & 0xFFFF0000) | 0x8001
+    u[2::5] = (u[2::5] & 0xFFFF0000) | 0x7FFF
+    x = u.view(np.float32).reshape(x.shape)
+    w = np.zeros((16, 16, 2, 2), np.float32)
+    for o in range(16):
+        w[o, o, 0, 0] = 1.0                         # y[n,o,r,c] = x[n,o,r,c]
+    got = gpu_forward(B, L, x, w, None, B.LOWER_FUSED, B.PREC_BF16_IN_F32_ACC)
+    want = bf16_rne(x)[:, :, :5, :5]
+    assert got.tobytes() == np.ascontiguousarray(want).tobytes()
+
+
+def test_auto_prefers_the_fused_form_for_bf16(B):
+    L = synth.caffenet(256)[2]                      # conv3
+    d = desc_of(B, L, B.LOWER_AUTO, B.PREC_BF16_IN_F32_ACC)
+    assert B.cct_pick_lowering(d, B.PASS_FORWARD) == B.LOWER_FUSED
+    assert B.cct_pick_lowering(d, B.PASS_BACKWARD_DATA) == B.LOWER_FUSED
+    assert B.cct_pick_lowering(d, B.PASS_BACKWARD_WEIGHTS) in (1, 2, 3)

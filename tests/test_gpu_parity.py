@@ -278,8 +278,8 @@ def test_unsupported_and_workspace_errors(B):
     assert e.value.code == B.EWORKSPACE
     with pytest.raises(ValueError):
         B.cct_conv_forward(d, dev(x)[:2], dev(w), dev(b), y, B.alloc_workspace(d, 0))
-    # there is no fused bf16 path, and no fused backward-weights pass for a padded layer whose
-    # input rows do not fit in LDS
+    # the fused bf16 kernel needs whole groups of 16 channels (this layer has 3), and there is no
+    # fused backward-weights pass for a padded layer whose input rows do not fit in LDS
     df = desc_of(B, L, B.LOWER_FUSED, B.PREC_BF16_IN_F32_ACC)
     with pytest.raises(B.CctError) as e:
         B.cct_conv_workspace_bytes(df, B.PASS_FORWARD)
