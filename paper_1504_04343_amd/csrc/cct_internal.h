@@ -118,7 +118,8 @@ int launch_conv_fused(const GemmTN& p, hipStream_t st);
 // kernels of the fused backward-data pass.  conv_fused_kc_fits: can it run this problem
 // (p filled as for launch_conv_fused)?
 bool conv_fused_kc_fits(const GemmTN& p);
-// The bf16 form pads the K tiles (taps x groups) of a pack to a multiple of eight with zero tiles.
+// A pack carries zero tiles up to a multiple of four K tiles (taps x groups); the bf16 form up to a
+// multiple of eight.
 long long conv_fused_kc_kpad(int channels_per_group, int K, int bf16);
 // `bf16`: the pack holds bf16 values (rounded to nearest even) for the bf16 form of the kernel.
 int launch_pack_fused_kc(const float* w, void* pack, int G, int Og, int Cg, int K, int Mpad,

@@ -1,7 +1,6 @@
-// Fused forward / stride-1 backward-data pass (the "Fusion" of Sec. 2.1), second form: the
-// reduction index is ordered (channel group of 16, tap, channel) and both operands are kept
-// CHANNEL-CONTIGUOUS in LDS, so that a lane fetches four reduction indices of its row / position
-// with ONE 16-byte LDS read.
+// Fused forward / backward-data pass (the "Fusion" of Sec. 2.1) with channel-contiguous operands:
+// the reduction index is ordered (channel group of 16, tap, channel), so that a lane fetches four
+// reduction indices of its row / position with ONE 16-byte access.
 //
 // Why: on gfx950 the rate of an LDS-fed v_mfma_f32_32x32x2_f32 loop depends on how many LDS
 // instructions accompany each MFMA.  With 4-byte operand reads (one LDS instruction per MFMA)
@@ -19,13 +18,18 @@
 //     cells over all LDS banks for 16-byte accesses), in a two-slot ring: the global loads of
 //     group g+1 are in flight while group g is multiplied;
 //   - one K tile = one tap of one channel group = 16 reduction indices.  The B operand of a lane
-//     is the 16 channels of cell  base(position) + tap offset, the A operand the 16 channels of
-//     its kernel row; reduction index q*8 + half*4 + e goes to MFMA (q, e), lane half `half`, on
-//     both sides;
-//   - the kernel matrix comes packed as [group][tap][kernel][16 channels] (pack_fused_kc_kernel),
-//     so a K tile of it is one contiguous block that is copied to LDS with 16-byte loads and
-//     stores, double buffered;
-//   - epilogue = Type-1 lifting + bias, as in the plain GEMM.
+//     is the 16 channels of cell  base(position) + tap offset;
+//   - the kernel matrix comes packed as [group][tap][kernel][16 channels] (pack_fused_kc_kernel)
+//     and never passes through LDS: a K tile of the pack is Mpad rows of 64 bytes, a lane needs 16
+//     of them per block (twice per tile on 32 x 32 blocks), and it loads them straight from the
+//     pack with 16-byte buffer loads issued two (four) tiles ahead, the tile in the scalar offset.
+//     The loads cost no address arithmetic and their latency (an L2 hit) is covered by whole
+//     tiles of MFMAs.  Against staging the kernel tile through LDS this takes 6 of 11 LDS
+//     instructions per tile, the tap-table read and the workgroup barrier per tile out of the
+//     loop: the workgroup meets once per channel group, when the next group's cells are published;
+//   - reduction index q*8 + half*4 + e goes to MFMA (q, e), lane half `half`, on both sides;
+//   - epilogue = Type-1 lifting + bias, as in the plain GEMM, or the depth-to-space store of a
+//     strided backward-data pass.
 #include <stdio.h>
 
 #include <algorithm>
@@ -39,30 +43,25 @@ namespace cct {
 namespace {
 
 using namespace kc;
-constexpr int CS = CG + 4;    // floats between cells / kernel rows in LDS
+constexpr int CS = CG + 4;  // floats between cells in LDS
 
 template <int BM, int WM, int WN>
 __global__ __launch_bounds__(NT) void conv_fused_kc_f32(GemmTN p, KcGeom fg, int tiles_m,
-                                                        int tiles_n) {
+                                                         int tiles_n) {
   // BM == 48: at most 48 rows (kernels, or sub-pixel channels of a strided backward-data pass),
   // computed with v_mfma_f32_16x16x4_f32 on 16 x 16 blocks so that no MFMA works on padding rows:
   // WM = 3 row blocks, WN = 2 column blocks per wave, all four waves side by side along the
   // positions.  A lane quarter (lane / 16) then supplies four of a tile's 16 reduction indices,
-  // so ONE 16-byte read per block covers the whole tile.
+  // so ONE 16-byte load / read per block covers the whole tile.
   constexpr bool M16 = BM == 48;
   constexpr int MB = M16 ? 16 : 32;  // block edge
   constexpr int WAVES_N = BN / (MB * WN);
   constexpr int WAVES_M = BM / (MB * WM);
   static_assert(WAVES_M * WAVES_N == 4, "4 waves per workgroup");
-  constexpr int A_VECS = BM * CG / 4;
-  constexpr int A_IT = (A_VECS + NT - 1) / NT;
-  constexpr int A_BUF = BM * CS;  // floats per kernel-tile buffer
 
   extern __shared__ __attribute__((aligned(16))) float smem[];
-  float* As = smem;                          // [2][BM][CS]
-  float* Xs = smem + 2 * A_BUF;              // [2][R][CS]
-  const int slot_floats = fg.R * CS;
-  int* tab = reinterpret_cast<int*>(Xs + 2 * slot_floats);  // [KK] tap -> float offset of the cell
+  float* Xs = smem;  // [2][R][CS]
+  const int slot_h = fg.R * CS;
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -77,8 +76,8 @@ __global__ __launch_bounds__(NT) void conv_fused_kc_f32(GemmTN p, KcGeom fg, int
   {
     const int total = tiles_m * tiles_n;
     const int per = total >> 3, rem = total & 7;
-    const int xcd = bid & 7, slot = bid >> 3;
-    bid = xcd * per + min(xcd, rem) + slot;
+    const int xcd = bid & 7, idx = bid >> 3;
+    bid = xcd * per + min(xcd, rem) + idx;
   }
   const int tile_n = bid / tiles_m;
   const int tile_m = bid - tile_n * tiles_m;
@@ -124,15 +123,10 @@ __global__ __launch_bounds__(NT) void conv_fused_kc_f32(GemmTN p, KcGeom fg, int
   };
   const long long chan_stride = (long long)p.gH * p.gW;
 
-  for (int e = tid; e < fg.KK; e += NT) {
-    const int ti = e / p.gK, tj = e - ti * p.gK;
-    tab[e] = (ti * fg.Wp + tj) * CS;
-  }
-
   // ---- staging: a thread owns cells tid + u*256 of every group.  The cell's byte offset inside
   // the tensor never changes; dead cells get an offset that fails the buffer range check and load
   // as zero; the channel enters through the scalar offset of the buffer load, channels past the
-  // group's last one through an empty range.  So staging 16 channels costs no vector-ALU work.
+  // group's last one through an empty range.
   unsigned stg_voff[QU];
   float stg[QU * CG];
   const float* Xb = reinterpret_cast<const float*>(p.B) +
@@ -165,7 +159,7 @@ __global__ __launch_bounds__(NT) void conv_fused_kc_f32(GemmTN p, KcGeom fg, int
         _Pragma("unroll") for (int v = 0; v < CG / 4; ++v) {                                \
           f32x4 val;                                                                        \
           _Pragma("unroll") for (int e = 0; e < 4; ++e) val[e] = stg[u * CG + v * 4 + e];   \
-          *reinterpret_cast<f32x4*>(&Xs[(SLOT) * slot_floats + q * CS + v * 4]) = val;      \
+          *reinterpret_cast<f32x4*>(&Xs[(SLOT) * slot_h + q * CS + v * 4]) = val;           \
         }                                                                                   \
       }                                                                                     \
     }                                                                                       \
@@ -174,35 +168,28 @@ __global__ __launch_bounds__(NT) void conv_fused_kc_f32(GemmTN p, KcGeom fg, int
   CCT_STAGE_STORE(0);
   if (fg.ngroups > 1) CCT_STAGE_LOAD(1);
 
-  // ---- kernel-matrix tiles: a K tile is BM*16 contiguous floats [kernel][16 channels] ----------
-  const int ktiles = fg.ngroups * fg.KK;
-  gptr_f32 Ag = (gptr_f32)(p.A) + (long long)g * p.a_gs + (long long)m0 * CG;
-  gptr_f32 a_src[A_IT];
-  int a_dst[A_IT];
-#pragma unroll
-  for (int it = 0; it < A_IT; ++it) {
-    const int v = tid + it * NT;
-    a_src[it] = Ag + v * 4;
-    a_dst[it] = (v >> 2) * CS + (v & 3) * 4;
-  }
-  const long long a_step = (long long)p.Mpad * CG;
-  f32x4 ra[2][A_IT];  // the 16-row form keeps two tiles in flight (its tiles are short), set 0 else
-#define CCT_LOAD_A_SET(SET)                                                                 \
+  // ---- kernel-matrix operands come straight from the pack (L2) into registers, AD tiles ahead.
+  // Tiles are taken AD at a time: the pack carries zero tiles up to a multiple of four, whose
+  // B operands are cells of the last group again (finite data times zero).  The 16 x 16 form has
+  // shorter tiles (24 MFMAs of 8 passes against 32 of 16), so it looks further ahead.
+  constexpr int AD = M16 ? 4 : 2;
+  constexpr int NQ = M16 ? 1 : 2;  // 16-byte loads per block and tile
+  const int ktiles = (fg.ngroups * fg.KK + AD - 1) / AD * AD;
+  const float* Abase = reinterpret_cast<const float*>(p.A) + ((long long)g * p.a_gs + (long long)m0 * CG);
+  const __amdgpu_buffer_rsrc_t a_rs =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(Abase), 0, 0x7fffffff, 0x00020000);
+  const int a_voff = ((wave_m * WM * MB + lane_lo) * CG + lane_hi * 4) * 4;  // bytes inside a tile
+  const unsigned a_tile_bytes = (unsigned)p.Mpad * CG * 4u;
+  // [tile mod AD][block][q]: reduction indices 8q + 4*half + e (32 x 32), 4*quarter + e (16 x 16)
+  f32x4 ra[AD][WM][NQ];
+#define CCT_LOAD_A(SET, T)                                                                  \
   {                                                                                         \
-    _Pragma("unroll") for (int it = 0; it < A_IT; ++it) {                                   \
-      if (A_VECS % NT == 0 || tid + it * NT < A_VECS) ra[SET][it] = *(gptr_f32x4)(a_src[it]); \
-      a_src[it] += a_step;                                                                  \
-    }                                                                                       \
+    _Pragma("unroll") for (int i = 0; i < WM; ++i)                                          \
+      _Pragma("unroll") for (int q = 0; q < NQ; ++q)                                        \
+        ra[SET][i][q] = __builtin_bit_cast(                                                 \
+            f32x4, __builtin_amdgcn_raw_buffer_load_b128(a_rs, a_voff + (i * MB * CG + q * 8) * 4, \
+                                                         (int)((unsigned)(T) * a_tile_bytes), 0)); \
   }
-#define CCT_STORE_A_SET(BUF, SET)                                                           \
-  {                                                                                         \
-    _Pragma("unroll") for (int it = 0; it < A_IT; ++it) {                                   \
-      if (A_VECS % NT == 0 || tid + it * NT < A_VECS)                                       \
-        *reinterpret_cast<f32x4*>(&As[(BUF) * A_BUF + a_dst[it]]) = ra[SET][it];            \
-    }                                                                                       \
-  }
-#define CCT_LOAD_A() CCT_LOAD_A_SET(0)
-#define CCT_STORE_A(BUF) CCT_STORE_A_SET(BUF, 0)
 
   constexpr int AR = M16 ? 4 : 16;  // accumulator registers per block
   typedef float acc_t __attribute__((ext_vector_type(AR)));
@@ -214,10 +201,8 @@ __global__ __launch_bounds__(NT) void conv_fused_kc_f32(GemmTN p, KcGeom fg, int
 #pragma unroll
       for (int r = 0; r < AR; ++r) acc[i][j][r] = 0.f;
 
-  // per-lane operand bases (float offsets): kernel row, and the cell of each owned position
-  const int am = wave_m * WM * MB + lane_lo;
+  // per-lane base of each owned position's cell (element offsets)
   const int bn = wave_n * WN * MB + lane_lo;
-  const int a_lds = am * CS + lane_hi * 4;
   int bbase[WN];
 #pragma unroll
   for (int j = 0; j < WN; ++j) {
@@ -233,156 +218,140 @@ __global__ __launch_bounds__(NT) void conv_fused_kc_f32(GemmTN p, KcGeom fg, int
     bbase[j] = cb * CS + lane_hi * 4;
   }
 
-  CCT_LOAD_A();
-  CCT_STORE_A(0);
-  __syncthreads();  // tap table, slot 0 and the first kernel tile are visible
-  if (M16) {
-    if (ktiles > 1) CCT_LOAD_A_SET(1);
-    if (ktiles > 2) CCT_LOAD_A_SET(0);
-  } else if (ktiles > 1) {
-    CCT_LOAD_A();
-  }
+#pragma unroll
+  for (int e = 0; e < AD; ++e) CCT_LOAD_A(e, e);  // ktiles >= AD
+  __syncthreads();                                  // slot 0 is visible
 
-  // operands: [q parity][block] of four reduction indices each (16-row form: [tile parity])
-  f32x4 a[2][WM], b[2][WN];
-  int boff[WN];     // float offset of the current tile's cells (slot + tap folded in)
+  f32x4 b[2][WN];              // [q][block]
+  int tt = 0, ti = 0, tj = 0;  // tap inside the current channel group, and its (row, column)
+  int grp = 0;                 // current channel group
+  int slot = 0;                // ring slot of the current group
 #pragma unroll
-  for (int j = 0; j < WN; ++j) boff[j] = bbase[j] + tab[0];
-#pragma unroll
-  for (int i = 0; i < WM; ++i) a[0][i] = *reinterpret_cast<const f32x4*>(&As[a_lds + i * MB * CS]);
-#pragma unroll
-  for (int j = 0; j < WN; ++j) b[0][j] = *reinterpret_cast<const f32x4*>(&Xs[boff[j]]);
+  for (int j = 0; j < WN; ++j) b[0][j] = *reinterpret_cast<const f32x4*>(&Xs[bbase[j]]);
 
-  int tt = 0;    // tap inside the current channel group
-  int grp = 0;   // current channel group
-  int slot = 0;  // ring slot of the current group
   if constexpr (M16) {
-    // One 16-byte read per block feeds the four MFMA groups of a whole tile, so the operands of
-    // tile t+1 are fetched right after the barrier in the middle of tile t, into the other set.
-    // The kernel tile of t+1 goes to LDS behind the first MFMA group, and the registers it leaves
-    // are reloaded at once with tile t+3: tiles are short here, two of them stay in flight.
-#define CCT_MFMA16(SET, E)                                                                  \
+    // One tile: the B operands of the next tap are read before this tile's MFMAs, which cover the
+    // read; the registers of this tile's A operand are reloaded with tile t + AD right after them.
+    // At a group's last tap: publish the next group's cells, barrier, first read from the new slot.
+#define CCT_TILE16(SET, CUR, NXT)                                                           \
   {                                                                                         \
-    __builtin_amdgcn_sched_barrier(0);                                                      \
-    _Pragma("unroll") for (int i = 0; i < WM; ++i)                                          \
-      _Pragma("unroll") for (int j = 0; j < WN; ++j)                                        \
-        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[SET][i][E], b[SET][j][E],        \
-                                                         acc[i][j], 0, 0, 0);               \
-    __builtin_amdgcn_sched_barrier(0);                                                      \
-  }
-#define CCT_TILE16(CUR, NXT)                                                                \
-  {                                                                                         \
-    const int buf = t & 1;                                                                  \
-    const bool more = t + 1 < ktiles;                                                       \
-    int tt_n = tt + 1, grp_n = grp, slot_n = slot;                                          \
-    if (tt_n == fg.KK) {                                                                    \
-      tt_n = 0;                                                                             \
-      grp_n = grp + 1;                                                                      \
-      slot_n = slot ^ 1;                                                                    \
+    const bool last_tap = tt == fg.KK - 1;                                                  \
+    int tj_n = tj + 1, ti_n = ti;                                                           \
+    if (tj_n == p.gK) {                                                                     \
+      tj_n = 0;                                                                             \
+      ti_n = ti + 1;                                                                        \
     }                                                                                       \
-    CCT_MFMA16(CUR, 0);                                                                     \
-    if (more) CCT_STORE_A_SET(buf ^ 1, NXT);                                                \
-    if (t + 3 < ktiles) CCT_LOAD_A_SET(NXT);                                                \
-    CCT_MFMA16(CUR, 1);                                                                     \
-    if (more) {                                                                             \
-      if (tt == fg.KK - 1 && grp + 1 < fg.ngroups) CCT_STAGE_STORE(slot ^ 1);               \
-      if (tt == 0 && t > 0 && grp + 1 < fg.ngroups) CCT_STAGE_LOAD(grp + 1);                \
-      const int tapo = tab[tt_n] + slot_n * slot_floats;                                    \
-      _Pragma("unroll") for (int j = 0; j < WN; ++j) boff[j] = bbase[j] + tapo;             \
-    }                                                                                       \
-    __builtin_amdgcn_sched_barrier(0);                                                      \
-    __syncthreads();                                                                        \
-    if (more) {                                                                             \
-      _Pragma("unroll") for (int i = 0; i < WM; ++i) a[NXT][i] =                            \
-          *reinterpret_cast<const f32x4*>(&As[(buf ^ 1) * A_BUF + a_lds + i * MB * CS]);    \
+    if (!last_tap) {                                                                        \
+      const int tapo = (ti_n * fg.Wp + tj_n) * CS + slot * slot_h;                          \
       _Pragma("unroll") for (int j = 0; j < WN; ++j) b[NXT][j] =                            \
-          *reinterpret_cast<const f32x4*>(&Xs[boff[j]]);                                    \
+          *reinterpret_cast<const f32x4*>(&Xs[bbase[j] + tapo]);                            \
     }                                                                                       \
-    CCT_MFMA16(CUR, 2);                                                                     \
-    CCT_MFMA16(CUR, 3);                                                                     \
-    tt = tt_n;                                                                              \
-    grp = grp_n;                                                                            \
-    slot = slot_n;                                                                          \
+    _Pragma("unroll") for (int e = 0; e < 4; ++e) {                                         \
+      __builtin_amdgcn_sched_barrier(0);                                                    \
+      _Pragma("unroll") for (int i = 0; i < WM; ++i)                                        \
+        _Pragma("unroll") for (int j = 0; j < WN; ++j)                                      \
+          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(ra[SET][i][0][e], b[CUR][j][e],  \
+                                                           acc[i][j], 0, 0, 0);             \
+      __builtin_amdgcn_sched_barrier(0);                                                    \
+    }                                                                                       \
+    if (t + AD < ktiles) CCT_LOAD_A(SET, t + AD);                                           \
+    if (last_tap) {                                                                         \
+      const bool more_groups = grp + 1 < fg.ngroups; /* false inside the zero tiles too */  \
+      if (more_groups) CCT_STAGE_STORE(slot ^ 1);                                           \
+      __syncthreads();                                                                      \
+      if (more_groups) slot ^= 1;                                                           \
+      ++grp;                                                                                \
+      if (grp + 1 < fg.ngroups) CCT_STAGE_LOAD(grp + 1);                                    \
+      tt = 0;                                                                               \
+      ti = 0;                                                                               \
+      tj = 0;                                                                               \
+      const int tapo = slot * slot_h;                                                       \
+      _Pragma("unroll") for (int j = 0; j < WN; ++j) b[NXT][j] =                            \
+          *reinterpret_cast<const f32x4*>(&Xs[bbase[j] + tapo]);                            \
+    } else {                                                                                \
+      ++tt;                                                                                 \
+      ti = ti_n;                                                                            \
+      tj = tj_n;                                                                            \
+    }                                                                                       \
     ++t;                                                                                    \
   }
+    static_assert(AD == 4 || !M16, "the loop below is unrolled by AD");
     int t = 0;
-    while (t < ktiles) {
-      CCT_TILE16(0, 1);
-      if (t >= ktiles) break;
-      CCT_TILE16(1, 0);
+    while (t < ktiles) {  // one exit: ktiles is a multiple of AD
+      CCT_TILE16(0, 0, 1);
+      CCT_TILE16(1, 1, 0);
+      CCT_TILE16(2, 0, 1);
+      CCT_TILE16(3, 1, 0);
     }
 #undef CCT_TILE16
-#undef CCT_MFMA16
   } else {
-  for (int t = 0; t < ktiles; ++t) {
-    const int buf = t & 1;
-    const bool more = t + 1 < ktiles;
-    int tt_n = tt + 1, grp_n = grp, slot_n = slot;
-    if (tt_n == fg.KK) {
-      tt_n = 0;
-      grp_n = grp + 1;
-      slot_n = slot ^ 1;
-    }
-    // ---- first half of the tile (reduction indices 0..7): its operands are in a[0], b[0] ------
-#pragma unroll
-    for (int i = 0; i < WM; ++i)
-      a[1][i] = *reinterpret_cast<const f32x4*>(&As[buf * A_BUF + a_lds + i * 32 * CS + 8]);
-#pragma unroll
-    for (int j = 0; j < WN; ++j) b[1][j] = *reinterpret_cast<const f32x4*>(&Xs[boff[j] + 8]);
-    // The workgroup's other per-tile duties are issued BETWEEN the four MFMA groups of this half,
-    // not after them: a wave issues in order, so whatever follows the last MFMA of a group goes
-    // out while that MFMA still occupies the matrix pipe, whereas work placed after all sixteen
-    // would run with the wave's MFMA queue empty.
-#define CCT_MFMA_GROUP(SET, E)                                                              \
+  // One tile = 16 reduction indices = two halves (q) of four MFMA groups (e) each.  The second
+  // half's B operands are read before the first half's MFMAs and the next tile's first half behind
+  // them, so every LDS read is covered by sixteen MFMAs; the registers of this tile's A operand are
+  // reloaded with tile t + AD at its end.  The workgroup meets once per channel group: in the middle
+  // of a group's last tap every thread publishes its cells of the next group (loaded while this
+  // group was multiplied), the barrier makes them visible and frees the other slot, and the loads of
+  // the group after start.
+#define CCT_MFMA_GROUP(SET, Q, E)                                                           \
   {                                                                                         \
     __builtin_amdgcn_sched_barrier(0);                                                      \
     _Pragma("unroll") for (int i = 0; i < WM; ++i)                                          \
       _Pragma("unroll") for (int j = 0; j < WN; ++j)                                        \
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[SET][i][E], b[SET][j][E],        \
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(ra[SET][i][Q][E], b[Q][j][E],      \
                                                          acc[i][j], 0, 0, 0);               \
     __builtin_amdgcn_sched_barrier(0);                                                      \
   }
-    CCT_MFMA_GROUP(0, 0);
-    // the next kernel tile (loaded one tile ago) goes to the other buffer
-    if (more) CCT_STORE_A(buf ^ 1);
-    CCT_MFMA_GROUP(0, 1);
-    // the loads of the tile after it
-    if (t + 2 < ktiles) CCT_LOAD_A();
-    CCT_MFMA_GROUP(0, 2);
-    if (more) {
-      // last tile of a group: publish the next group's cells (their loads were issued at the
-      // group's first tile); first tile of a group: start loading the group after it
-      if (tt == fg.KK - 1 && grp + 1 < fg.ngroups) CCT_STAGE_STORE(slot ^ 1);
-      if (tt == 0 && t > 0 && grp + 1 < fg.ngroups) CCT_STAGE_LOAD(grp + 1);
-      const int tapo = tab[tt_n] + slot_n * slot_floats;
-#pragma unroll
-      for (int j = 0; j < WN; ++j) boff[j] = bbase[j] + tapo;
-    }
-    CCT_MFMA_GROUP(0, 3);
-    // ---- second half (indices 8..15): the barrier that publishes the next tile sits before its
-    // MFMAs, which then cover the latency of the next tile's first operand reads
-    __syncthreads();
-    if (more) {
-#pragma unroll
-      for (int i = 0; i < WM; ++i)
-        a[0][i] = *reinterpret_cast<const f32x4*>(&As[(buf ^ 1) * A_BUF + a_lds + i * 32 * CS]);
-#pragma unroll
-      for (int j = 0; j < WN; ++j) b[0][j] = *reinterpret_cast<const f32x4*>(&Xs[boff[j]]);
-    }
-    CCT_MFMA_GROUP(1, 0);
-    CCT_MFMA_GROUP(1, 1);
-    CCT_MFMA_GROUP(1, 2);
-    CCT_MFMA_GROUP(1, 3);
-    tt = tt_n;
-    grp = grp_n;
-    slot = slot_n;
+#define CCT_TILE(SET)                                                                       \
+  {                                                                                         \
+    const bool last_tap = tt == fg.KK - 1;                                                  \
+    {                                                                                       \
+      const int cur = (ti * fg.Wp + tj) * CS + slot * slot_h + 8;                           \
+      _Pragma("unroll") for (int j = 0; j < WN; ++j) b[1][j] =                              \
+          *reinterpret_cast<const f32x4*>(&Xs[bbase[j] + cur]);                             \
+    }                                                                                       \
+    CCT_MFMA_GROUP(SET, 0, 0);                                                              \
+    CCT_MFMA_GROUP(SET, 0, 1);                                                              \
+    CCT_MFMA_GROUP(SET, 0, 2);                                                              \
+    CCT_MFMA_GROUP(SET, 0, 3);                                                              \
+    if (last_tap) {                                                                         \
+      const bool more_groups = grp + 1 < fg.ngroups; /* false inside the zero tile too */   \
+      if (more_groups) CCT_STAGE_STORE(slot ^ 1);                                           \
+      __syncthreads();                                                                      \
+      if (more_groups) slot ^= 1;                                                           \
+      ++grp;                                                                                \
+      if (grp + 1 < fg.ngroups) CCT_STAGE_LOAD(grp + 1);                                    \
+      tt = 0;                                                                               \
+      ti = 0;                                                                               \
+      tj = 0;                                                                               \
+    } else {                                                                                \
+      ++tt;                                                                                 \
+      if (++tj == p.gK) {                                                                   \
+        tj = 0;                                                                             \
+        ++ti;                                                                               \
+      }                                                                                     \
+    }                                                                                       \
+    {                                                                                       \
+      const int nxt = (ti * fg.Wp + tj) * CS + slot * slot_h;                               \
+      _Pragma("unroll") for (int j = 0; j < WN; ++j) b[0][j] =                              \
+          *reinterpret_cast<const f32x4*>(&Xs[bbase[j] + nxt]);                             \
+    }                                                                                       \
+    CCT_MFMA_GROUP(SET, 1, 0);                                                              \
+    CCT_MFMA_GROUP(SET, 1, 1);                                                              \
+    CCT_MFMA_GROUP(SET, 1, 2);                                                              \
+    CCT_MFMA_GROUP(SET, 1, 3);                                                              \
+    if (t + AD < ktiles) CCT_LOAD_A(SET, t + AD);                                           \
+    ++t;                                                                                    \
   }
-  }
+    static_assert(AD == 2 || M16, "the loop below is unrolled by AD");
+    int t = 0;
+    while (t < ktiles) {  // one exit: ktiles is a multiple of AD
+      CCT_TILE(0);
+      CCT_TILE(1);
+    }
 #undef CCT_MFMA_GROUP
+  }
+#undef CCT_TILE
 #undef CCT_LOAD_A
-#undef CCT_STORE_A
-#undef CCT_LOAD_A_SET
-#undef CCT_STORE_A_SET
 #undef CCT_STAGE_LOAD
 #undef CCT_STAGE_STORE
 
@@ -390,9 +359,6 @@ __global__ __launch_bounds__(NT) void conv_fused_kc_f32(GemmTN p, KcGeom fg, int
   // i*32 + 8*(r/4) + 4*(lane/32) + r%4 of the wave's rows (32 x 32 blocks), or
   // i*16 + 4*(lane/16) + r (16 x 16 blocks): four consecutive rows per lane either way.
   const int mw = m0 + wave_m * WM * MB;
-  auto row_of = [&](int i, int r) {
-    return M16 ? i * 16 + lane_hi * 4 + r : i * 32 + (r >> 2) * 8 + (r & 3) + lane_hi * 4;
-  };
   if (p.d2s) {
     // depth-to-space: a lane's four consecutive rows are four sub-pixels of its grid position
     float* __restrict__ D = p.C;
@@ -408,7 +374,7 @@ __global__ __launch_bounds__(NT) void conv_fused_kc_f32(GemmTN p, KcGeom fg, int
       for (int i = 0; i < WM; ++i) {
 #pragma unroll
         for (int r = 0; r < AR; ++r) {
-          const int m = mw + row_of(i, r);
+          const int m = mw + (M16 ? i * 16 + r : i * 32 + (r >> 2) * 8 + (r & 3)) + lane_hi * 4;
           if (m < p.M) {
             const int ci = fdiv_u(m, p.d_divSS_M, p.d_divSS_sh), rem = m - ci * ss;
             const int rh = fdiv_u(rem, p.d_divS_M, p.d_divS_sh), rw = rem - rh * p.dS;
@@ -428,8 +394,6 @@ __global__ __launch_bounds__(NT) void conv_fused_kc_f32(GemmTN p, KcGeom fg, int
   for (int j = 0; j < WN; ++j) {
     const int col = n0 + bn + j * MB;
     if (col >= ce) continue;
-    // one 64-bit base per column block (the lane's column and its first row); the row of each
-    // accumulator register is a uniform multiple of the row stride on top of it
     float* __restrict__ cl = C + col_offset(p.cmap, col) + (long long)(mw + lane_hi * 4) * p.c_ms;
     const float* bl = bias ? bias + mw + lane_hi * 4 : nullptr;
 #pragma unroll
@@ -447,8 +411,10 @@ __global__ __launch_bounds__(NT) void conv_fused_kc_f32(GemmTN p, KcGeom fg, int
   }
 }
 
-bool make_kc_geom(const GemmTN& p, int BM, KcGeom* fg, size_t* lds) {
-  return !p.bf16 && kc::make_geom(p, BM, CS * 4, fg, lds);
+// Geometry and LDS need; false = this form cannot run the shape.  No kernel tiles live in LDS
+// (row count 0); the pack of one group is addressed with 32-bit byte offsets.
+bool make_kc_geom(const GemmTN& p, KcGeom* fg, size_t* lds) {
+  return !p.bf16 && (long long)p.Mpad * p.Kpad * 4 < (1LL << 31) && kc::make_geom(p, 0, CS * 4, fg, lds);
 }
 
 template <int BM, int WM, int WN>
@@ -557,12 +523,13 @@ bool conv_fused_kc_fits(const GemmTN& p) {
   const int BM = kc_row_tile(p, &BNt);
   KcGeom fg;
   size_t lds;
-  return BNt == BN && make_kc_geom(p, BM, &fg, &lds);
+  (void)BM;
+  return BNt == BN && make_kc_geom(p, &fg, &lds);
 }
 
 long long conv_fused_kc_kpad(int channels_per_group, int K, int bf16) {
   const long long ktiles = (long long)((channels_per_group + CG - 1) / CG) * K * K;
-  return (bf16 ? (ktiles + 7) / 8 * 8 : ktiles) * CG;
+  return (bf16 ? (ktiles + 7) / 8 * 8 : (ktiles + 3) / 4 * 4) * CG;
 }
 
 int launch_pack_fused_kc(const float* w, void* pack, int G, int Og, int Cg, int K, int Mpad,
@@ -619,9 +586,9 @@ int launch_conv_fused_kc(const GemmTN& p0, hipStream_t st) {
   const int BM = kc_row_tile(p, &BNt);
   KcGeom fg;
   size_t lds;
-  if (BNt != BN || (BM == 48 ? p.Mpad < 48 : p.Mpad % BM != 0) || !make_kc_geom(p, BM, &fg, &lds))
+  if (BNt != BN || (BM == 48 ? p.Mpad < 48 : p.Mpad % BM != 0) || !make_kc_geom(p, &fg, &lds))
     return CCT_EUNSUPPORTED;
-  if (p.Kpad != (long long)fg.ngroups * CG * fg.KK) return CCT_EINVAL;
+  if (p.Kpad != conv_fused_kc_kpad(p.gCg, p.gK, 0)) return CCT_EINVAL;
   if (BM == 48) return launch_variant<48, 3, 2>(p, fg, lds, st);
   if (BM == 192) return launch_variant<192, 3, 2>(p, fg, lds, st);
   if (BM == 64) return launch_variant<64, 1, 2>(p, fg, lds, st);
