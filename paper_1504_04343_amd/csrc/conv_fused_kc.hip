@@ -413,8 +413,14 @@ __global__ __launch_bounds__(NT) void conv_fused_kc_f32(GemmTN p, KcGeom fg, int
 
 // Geometry and LDS need; false = this form cannot run the shape.  No kernel tiles live in LDS
 // (row count 0); the pack of one group is addressed with 32-bit byte offsets.
-bool make_kc_geom(const GemmTN& p, KcGeom* fg, size_t* lds) {
-  return !p.bf16 && (long long)p.Mpad * p.Kpad * 4 < (1LL << 31) && kc::make_geom(p, 0, CS * 4, fg, lds);
+// The 16 x 16 block form has short tiles and gains from a third workgroup per CU (measured on
+// conv2's backward-data pass: 131 against 124 TFLOP/s), so it first tries the geometry that fits
+// a third of the LDS; the 32 x 32 forms do not (their tiles cut per image waste more than the third
+// workgroup brings).
+bool make_kc_geom(const GemmTN& p, int BM, KcGeom* fg, size_t* lds) {
+  if (p.bf16 || (long long)p.Mpad * p.Kpad * 4 >= (1LL << 31)) return false;
+  if (BM == 48 && kc::make_geom(p, 0, CS * 4, fg, lds, kLdsCap3)) return true;
+  return kc::make_geom(p, 0, CS * 4, fg, lds);
 }
 
 template <int BM, int WM, int WN>
@@ -507,13 +513,14 @@ __global__ __launch_bounds__(256) void pack_fused_kc_strided_kernel(const float*
 
 }  // namespace
 
-// Row tile of this kernel: the GEMM family's choice (64 / 96 / 128), except that a row count that
-// is a multiple of 192 takes 192-row tiles (waves of 96 x 64: more MFMAs per operand read than the
-// 96 x 32 waves of the 96-row tile).
+// Row tile of this kernel: the GEMM family's choice (64 / 96 / 128), with two exceptions.
 static int kc_row_tile(const GemmTN& p, int* BNt) {
   int BM, BKt;
   gemm_tn_tile(p.M, p.Ncols, &BM, BNt, &BKt);
-  if (BM == 96 && p.Mpad % 192 == 0) BM = 192;
+  // Rows that are not a multiple of 128: tiles of 64 rows (4 workgroups per CU, and three times
+  // as many tiles to spread over the chip) beat 96 x 64 wave tiles (measured: 128 against 116
+  // TFLOP/s on conv4's 192 rows)
+  if (BM == 96 && p.Mpad % 192 == 0) BM = 64;
   if (p.M <= 48) BM = 48;  // 16 x 16 MFMA blocks: no work on padding rows beyond the 48th
   return BM;
 }
@@ -523,8 +530,7 @@ bool conv_fused_kc_fits(const GemmTN& p) {
   const int BM = kc_row_tile(p, &BNt);
   KcGeom fg;
   size_t lds;
-  (void)BM;
-  return BNt == BN && make_kc_geom(p, &fg, &lds);
+  return BNt == BN && make_kc_geom(p, BM, &fg, &lds);
 }
 
 long long conv_fused_kc_kpad(int channels_per_group, int K, int bf16) {
@@ -586,11 +592,10 @@ int launch_conv_fused_kc(const GemmTN& p0, hipStream_t st) {
   const int BM = kc_row_tile(p, &BNt);
   KcGeom fg;
   size_t lds;
-  if (BNt != BN || (BM == 48 ? p.Mpad < 48 : p.Mpad % BM != 0) || !make_kc_geom(p, &fg, &lds))
+  if (BNt != BN || (BM == 48 ? p.Mpad < 48 : p.Mpad % BM != 0) || !make_kc_geom(p, BM, &fg, &lds))
     return CCT_EUNSUPPORTED;
   if (p.Kpad != conv_fused_kc_kpad(p.gCg, p.gK, 0)) return CCT_EINVAL;
   if (BM == 48) return launch_variant<48, 3, 2>(p, fg, lds, st);
-  if (BM == 192) return launch_variant<192, 3, 2>(p, fg, lds, st);
   if (BM == 64) return launch_variant<64, 1, 2>(p, fg, lds, st);
   if (BM == 96) return launch_variant<96, 3, 1>(p, fg, lds, st);
   return launch_variant<128, 2, 2>(p, fg, lds, st);

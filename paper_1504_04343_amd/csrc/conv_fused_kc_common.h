@@ -12,7 +12,8 @@ constexpr int NT = 256;       // threads per workgroup
 constexpr int BN = 128;       // positions per workgroup
 constexpr int CG = 16;        // channels per group = reduction indices per K tile
 constexpr int QU = 2;         // cells per thread and slot (R <= QU*256)
-constexpr int kLdsCap = 80 * 1024;  // two workgroups per CU
+constexpr int kLdsCap = 80 * 1024;   // two workgroups per CU
+constexpr int kLdsCap3 = 53 * 1024;  // three
 
 struct KcGeom {
   int Wp;       // padded row width W + 2*pad (cells per staged row)
@@ -24,10 +25,12 @@ struct KcGeom {
                 // fit the staging area.  0: tiles are cut from the positions of the whole chunk.
 };
 
-// Geometry and LDS need of a launch whose cells and kernel rows take `cell_bytes` bytes of LDS
+// Geometry and LDS need (at most `lds_cap` bytes: the cap decides whether column tiles are cut per
+// image) of a launch whose cells and kernel rows take `cell_bytes` bytes of LDS
 // each (16 channels plus the padding that spreads 16-byte accesses over the banks); false = this
 // form cannot run the shape.  LDS: kernel tiles [2][BM] | cells [2][R] | tap table [KK] ints.
-inline bool make_geom(const GemmTN& p, int BM, int cell_bytes, KcGeom* fg, size_t* lds) {
+inline bool make_geom(const GemmTN& p, int BM, int cell_bytes, KcGeom* fg, size_t* lds,
+                      int lds_cap = kLdsCap) {
   if (!p.gather || p.tapmajor || p.gK < 2 || p.gCg < 1) return false;
   fg->KK = p.gK * p.gK;
   // staged row width: the padded input row, or what the last grid column's window reaches if the
@@ -49,7 +52,7 @@ inline bool make_geom(const GemmTN& p, int BM, int cell_bytes, KcGeom* fg, size_
   };
   long long R = cells(r1 > rT ? r1 : rT);
   fg->tpi = 0;
-  if (R > QU * NT || lds_of(R) > kLdsCap) {
+  if (R > QU * NT || lds_of(R) > lds_cap) {
     // tiles cut per image need the rows of one image only; worth it while the partly empty last
     // tile of an image wastes less than a tenth of the launch
     const long long tpi = (P + BN - 1) / BN;
@@ -63,7 +66,7 @@ inline bool make_geom(const GemmTN& p, int BM, int cell_bytes, KcGeom* fg, size_
   // staged cells are addressed with 32-bit byte offsets from the workgroup's first image
   if ((T + 1) * p.gC * p.gH * p.gW >= (1LL << 29)) return false;
   const long long need = lds_of(R);
-  if (need > kLdsCap) return false;
+  if (need > lds_cap) return false;
   *lds = (size_t)need;
   return true;
 }
