@@ -116,3 +116,51 @@ def test_auto_prefers_the_fused_form_for_bf16(B):
     assert B.cct_pick_lowering(d, B.PASS_FORWARD) == B.LOWER_FUSED
     assert B.cct_pick_lowering(d, B.PASS_BACKWARD_DATA) == B.LOWER_FUSED
     assert B.cct_pick_lowering(d, B.PASS_BACKWARD_WEIGHTS) in (1, 2, 3)
+
+
+def random_wide_layers(count, seed):
+    """Seeded random geometries with enough channels per group for cells of 16."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        g = int(rng.choice([1, 2]))
+        C = g * int(rng.integers(15, 72))
+        O = g * int(rng.integers(15, 150))
+        K = int(rng.choice([2, 3, 3, 5]))
+        s = int(rng.choice([1, 1, 2]))
+        p = int(rng.integers(0, K))
+        H = int(rng.integers(K, 30))
+        W = int(rng.integers(K, 30))
+        N = int(rng.integers(2, 13))
+        out.append(layer("rnd%d" % len(out), N, C, H, W, O, K, s, p, g))
+    return out
+
+
+RANDOM = random_wide_layers(14, 5)
+
+
+@pytest.mark.parametrize("L", RANDOM, ids=[
+    "%s_N%d_C%d_%dx%d_O%d_K%d_s%d_p%d_g%d" % (L.name, L.N, L.C, L.H, L.W, L.O, L.K, L.stride, L.pad,
+                                               L.groups) for L in RANDOM])
+def test_random_shapes_bf16_fused(B, L):
+    """Whatever the fused bf16 layout accepts must meet the sharp bar; what it rejects must be
+    rejected at run time too, and AUTO must still give the variant's accuracy."""
+    x, w, b, dy = synth.make_x(L, 9), synth.make_w(L, 9), synth.make_bias(L, 9), synth.make_dy(L, 9)
+    od = odims(oracle, L)
+    P16 = B.PREC_BF16_IN_F32_ACC
+    if supported(B, L, B.PASS_FORWARD):
+        got = gpu_forward(B, L, x, w, b, B.LOWER_FUSED, P16)
+        assert rel_err(got, oracle.conv_forward(od, bf16_rne(x), bf16_rne(w), b)) <= TOL_F32
+    else:
+        with pytest.raises(B.CctError):
+            gpu_forward(B, L, x, w, b, B.LOWER_FUSED, P16)
+    assert rel_err(gpu_forward(B, L, x, w, b, B.LOWER_AUTO, P16), oracle.conv_forward(od, x, w, b)) <= TOL_BF16
+    if supported(B, L, B.PASS_BACKWARD_DATA):
+        got = gpu_backward_data(B, L, w, dy, B.LOWER_FUSED, P16)
+        assert np.isfinite(got).all()
+        assert rel_err(got, oracle.conv_backward_data(od, bf16_rne(w), bf16_rne(dy))) <= TOL_F32
+    else:
+        with pytest.raises(B.CctError):
+            gpu_backward_data(B, L, w, dy, B.LOWER_FUSED, P16)
+    assert rel_err(gpu_backward_data(B, L, w, dy, B.LOWER_AUTO, P16),
+                   oracle.conv_backward_data(od, w, dy)) <= TOL_BF16
