@@ -5,8 +5,8 @@ Thin ctypes binding over ``conv_oracle.c`` (plain C, fp64 accumulation).  Only
 ``bench.py`` may import this package; the product path never does, and this
 package imports nothing from the HIP path.
 
-``layers_oracle.c`` holds the rectified linear unit and max pooling (Caffe's definitions), the
-two layers between CaffeNet's convolutions.
+``layers_oracle.c`` holds the rectified linear unit, max pooling and local response normalisation
+(Caffe's definitions), the layers between CaffeNet's convolutions.
 
 Part A is the direct definition (eq. (1) of the paper plus Caffe-style stride /
 pad / groups / bias) and its two adjoints; Part B is the paper's three lowerings
@@ -324,4 +324,44 @@ def maxpool_backward(d: PoolDims, dy, argmax) -> np.ndarray:
     _check(_load().oracle_maxpool_backward(ctypes.byref(d._c()), _p(dy, ctypes.c_float),
                                            _p(argmax, ctypes.c_int32), _p(dx, ctypes.c_float)),
            "maxpool_backward")
+    return dx
+
+
+class _Lrn(ctypes.Structure):
+    _fields_ = [(k, ctypes.c_int) for k in ("N", "C", "H", "W", "size")] + \
+               [(k, ctypes.c_double) for k in ("alpha", "beta", "k")]
+
+
+@dataclass(frozen=True)
+class LrnDims:
+    """Local response normalisation across `size` channels of an N x C x H x W tensor."""
+    N: int
+    C: int
+    H: int
+    W: int
+    size: int = 5
+    alpha: float = 1e-4
+    beta: float = 0.75
+    k: float = 1.0
+
+    def _c(self) -> _Lrn:
+        return _Lrn(self.N, self.C, self.H, self.W, self.size, self.alpha, self.beta, self.k)
+
+
+def lrn_forward(d: LrnDims, x) -> np.ndarray:
+    x = _f32(x)
+    _expect(x, (d.N, d.C, d.H, d.W), "x")
+    y = np.empty_like(x)
+    _check(_load().oracle_lrn_forward(ctypes.byref(d._c()), _p(x, ctypes.c_float), _p(y, ctypes.c_float)),
+           "lrn_forward")
+    return y
+
+
+def lrn_backward(d: LrnDims, x, dy) -> np.ndarray:
+    x, dy = _f32(x), _f32(dy)
+    _expect(x, (d.N, d.C, d.H, d.W), "x")
+    _expect(dy, x.shape, "dy")
+    dx = np.empty_like(x)
+    _check(_load().oracle_lrn_backward(ctypes.byref(d._c()), _p(x, ctypes.c_float), _p(dy, ctypes.c_float),
+                                       _p(dx, ctypes.c_float)), "lrn_backward")
     return dx

@@ -14,13 +14,24 @@
  *             in row-major scan order of the window (strict > when scanning); the backward pass
  *             routes dy[n,c,r,q] to that position and sums where windows overlap.
  *
+ *   LRN       local response normalisation across channels (the layer after pool1 and pool2):
+ *             scale[n,c,h,w] = k + (alpha/size) * sum of x[n,c',h,w]^2 over the `size` channels
+ *             centred on c (size odd; channels outside [0,C) contribute nothing),
+ *             y = x * scale^(-beta).  Backward is the exact derivative of that map:
+ *             dx[c] = dy[c]*scale[c]^(-beta)
+ *                     - (2*alpha*beta/size) * x[c] * sum over c' with |c'-c| <= (size-1)/2 of
+ *                       dy[c'] * x[c'] * scale[c']^(-beta-1).
+ *
  * Plain loops, one output at a time, exact (comparisons and copies of fp32 values; the backward
- * sum of the few overlapping windows is done in fp64).
+ * sum of the few overlapping windows is done in fp64); LRN is computed in fp64 and rounded once.
  *
  * Pins (tests/test_oracle_pins.py): values worked out by hand, the output-size law at CaffeNet's
  * 55 -> 27 and 27 -> 13, torch's CPU max_pool2d (ceil mode) and its autograd on tie-free data,
- * the tie rule on a constant image.
+ * the tie rule on a constant image; for LRN a hand-worked three-channel case, the closed form on a
+ * constant tensor (edge channels see fewer neighbours), size 1 = a pointwise power law, torch's CPU
+ * local_response_norm and its autograd, and a finite-difference check of the backward pass.
  */
+#include <math.h>
 #include <stdint.h>
 #include <stddef.h>
 #include <stdlib.h>
@@ -115,5 +126,61 @@ int oracle_maxpool_backward(const oracle_pool_t* d, const float* dy, const int32
     for (int t = 0; t < d->H * d->W; ++t) dx[pl * d->H * d->W + t] = (float)acc[t];
   }
   free(acc);
+  return 0;
+}
+
+/* ---- local response normalisation across channels -------------------------------------- */
+typedef struct {
+  int N, C, H, W, size;
+  double alpha, beta, k;
+} oracle_lrn_t;
+
+static int lrn_ok(const oracle_lrn_t* d) {
+  return d && d->N > 0 && d->C > 0 && d->H > 0 && d->W > 0 && d->size > 0 && (d->size & 1) &&
+         d->k > 0.0 && d->alpha >= 0.0;
+}
+
+static double lrn_scale(const oracle_lrn_t* d, const float* xp, int64_t hw, int c) {
+  const int half = (d->size - 1) / 2;
+  double s = 0.0;
+  for (int cc = c - half; cc <= c + half; ++cc)
+    if (cc >= 0 && cc < d->C) s += (double)xp[cc * hw] * (double)xp[cc * hw];
+  return d->k + d->alpha / d->size * s;
+}
+
+int oracle_lrn_forward(const oracle_lrn_t* d, const float* x, float* y) {
+  if (!lrn_ok(d) || !x || !y) return -1;
+  const int64_t hw = (int64_t)d->H * d->W;
+#pragma omp parallel for schedule(static)
+  for (int64_t t = 0; t < (int64_t)d->N * hw; ++t) {
+    const int64_t n = t / hw, pix = t % hw;
+    const float* xp = x + n * d->C * hw + pix; /* channel c of this pixel is xp[c*hw] */
+    float* yp = y + n * d->C * hw + pix;
+    for (int c = 0; c < d->C; ++c)
+      yp[c * hw] = (float)((double)xp[c * hw] * pow(lrn_scale(d, xp, hw, c), -d->beta));
+  }
+  return 0;
+}
+
+int oracle_lrn_backward(const oracle_lrn_t* d, const float* x, const float* dy, float* dx) {
+  if (!lrn_ok(d) || !x || !dy || !dx) return -1;
+  const int64_t hw = (int64_t)d->H * d->W;
+  const int half = (d->size - 1) / 2;
+#pragma omp parallel for schedule(static)
+  for (int64_t t = 0; t < (int64_t)d->N * hw; ++t) {
+    const int64_t n = t / hw, pix = t % hw;
+    const float* xp = x + n * d->C * hw + pix;
+    const float* gp = dy + n * d->C * hw + pix;
+    float* op = dx + n * d->C * hw + pix;
+    for (int c = 0; c < d->C; ++c) {
+      double cross = 0.0;
+      for (int cc = c - half; cc <= c + half; ++cc)
+        if (cc >= 0 && cc < d->C)
+          cross += (double)gp[cc * hw] * (double)xp[cc * hw] *
+                   pow(lrn_scale(d, xp, hw, cc), -d->beta - 1.0);
+      op[c * hw] = (float)((double)gp[c * hw] * pow(lrn_scale(d, xp, hw, c), -d->beta) -
+                           2.0 * d->alpha * d->beta / d->size * (double)xp[c * hw] * cross);
+    }
+  }
   return 0;
 }

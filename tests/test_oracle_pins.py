@@ -518,3 +518,75 @@ def test_relu_against_torch_cpu():
     ty.backward(torch.from_numpy(dy))
     assert np.array_equal(oracle.relu_forward(x), ty.detach().numpy())
     assert np.array_equal(oracle.relu_backward(x, dy), tx.grad.numpy())
+
+
+# ------------------------------------------------------------------ local response normalisation
+def test_lrn_by_hand_three_channels():
+    """size 3, alpha 3, beta 1, k 1 on one pixel with channels (1, 2, 3): the sums of squares over
+    the windows are 1+4, 1+4+9, 4+9, so scale = 1 + (3/3)*(5, 14, 13) = (6, 15, 14) and y = x/scale."""
+    d = oracle.LrnDims(1, 3, 1, 1, size=3, alpha=3.0, beta=1.0, k=1.0)
+    x = np.array([1.0, 2.0, 3.0], np.float32).reshape(1, 3, 1, 1)
+    y = oracle.lrn_forward(d, x).ravel()
+    np.testing.assert_allclose(y, [1 / 6, 2 / 15, 3 / 14], rtol=1e-7)
+    # backward by hand for dy = (1, 0, 0): dx0 = 1/6 - 2*x0*(x0/36) = 1/6 - 1/18, dx1 = -2*x1*(x0/36),
+    # dx2 = 0 (channel 0 is outside the window of channel 2)
+    dx = oracle.lrn_backward(d, x, np.array([1.0, 0.0, 0.0], np.float32).reshape(1, 3, 1, 1)).ravel()
+    np.testing.assert_allclose(dx, [1 / 6 - 2 * 1 * (1 / 36), -2 * 2 * (1 / 36), 0.0], rtol=1e-6, atol=1e-9)
+
+
+def test_lrn_constant_tensor_closed_form_and_edge_channels():
+    """On a constant tensor v the window of an inner channel holds `size` squares, that of an edge
+    channel fewer (zero padding across channels): y = v * (k + alpha/size * m * v^2)^-beta."""
+    d = oracle.LrnDims(2, 7, 3, 2, size=5, alpha=0.5, beta=0.75, k=2.0)
+    v = 1.5
+    y = oracle.lrn_forward(d, np.full((2, 7, 3, 2), v, np.float32))
+    counts = [3, 4, 5, 5, 5, 4, 3]
+    for c, m in enumerate(counts):
+        want = v * (2.0 + 0.5 / 5 * m * v * v) ** -0.75
+        np.testing.assert_allclose(y[:, c], want, rtol=1e-6)
+
+
+def test_lrn_size_one_is_a_pointwise_power_law():
+    d = oracle.LrnDims(1, 4, 2, 2, size=1, alpha=2.0, beta=0.5, k=1.0)
+    x = np.random.default_rng(3).standard_normal((1, 4, 2, 2)).astype(np.float32)
+    want = x.astype(np.float64) * (1.0 + 2.0 * x.astype(np.float64) ** 2) ** -0.5
+    np.testing.assert_allclose(oracle.lrn_forward(d, x), want, rtol=1e-6)
+
+
+@pytest.mark.parametrize("N,C,H,W,size", [(2, 9, 4, 3, 5), (1, 5, 2, 2, 3), (2, 3, 3, 3, 5)])
+def test_lrn_against_torch_cpu(N, C, H, W, size):
+    import torch
+    d = oracle.LrnDims(N, C, H, W, size=size, alpha=0.3, beta=0.75, k=1.0)
+    rng = np.random.default_rng(5)
+    x = rng.standard_normal((N, C, H, W)).astype(np.float32) * 2
+    dy = rng.standard_normal((N, C, H, W)).astype(np.float32)
+    tx = torch.tensor(x, dtype=torch.float64, requires_grad=True)
+    ty = torch.nn.functional.local_response_norm(tx, size, alpha=0.3, beta=0.75, k=1.0)
+    ty.backward(torch.tensor(dy, dtype=torch.float64))
+    np.testing.assert_allclose(oracle.lrn_forward(d, x), ty.detach().numpy(), rtol=2e-6, atol=1e-7)
+    np.testing.assert_allclose(oracle.lrn_backward(d, x, dy), tx.grad.numpy(), rtol=2e-5, atol=1e-6)
+
+
+def test_lrn_backward_is_the_derivative_of_forward():
+    """Central differences in fp64 on the oracle's own forward formula written out in numpy."""
+    d = oracle.LrnDims(1, 6, 1, 2, size=5, alpha=0.8, beta=0.75, k=1.0)
+    rng = np.random.default_rng(8)
+    x = rng.standard_normal((1, 6, 1, 2))
+    dy = rng.standard_normal((1, 6, 1, 2))
+
+    def f(xx):
+        out = np.zeros_like(xx)
+        for c in range(6):
+            lo, hi = max(0, c - 2), min(6, c + 3)
+            scale = 1.0 + 0.8 / 5 * (xx[:, lo:hi] ** 2).sum(axis=1)
+            out[:, c] = xx[:, c] * scale ** -0.75
+        return out
+    want = np.zeros_like(x)
+    h = 1e-6
+    for idx in np.ndindex(*x.shape):
+        xp, xm = x.copy(), x.copy()
+        xp[idx] += h
+        xm[idx] -= h
+        want[idx] = ((f(xp) - f(xm)) * dy).sum() / (2 * h)
+    got = oracle.lrn_backward(d, x.astype(np.float32), dy.astype(np.float32))
+    np.testing.assert_allclose(got, want, rtol=2e-4, atol=2e-6)
