@@ -249,6 +249,26 @@ int cct_maxpool_backward(const cct_pool_desc_t* desc, const float* dy, const int
                          float* dx, void* hip_stream);
 
 /*
+ * Local response normalisation across channels, the layer CaffeNet puts after its first two
+ * pooling layers (Sec. 1 names the non-convolutional layers only collectively; the definition is
+ * Caffe's):  scale[n,c,h,w] = k + (alpha/size) * sum of x[n,c',h,w]^2 over the `size` channels
+ * centred on c (size odd; channels outside [0,C) contribute nothing),  y = x * scale^(-beta).
+ * Backward is the exact derivative, computed from x and dy (scale is recomputed, nothing is kept
+ * from the forward pass).  x, y, dy, dx: device, contiguous NCHW fp32, N*C*H*W elements; y / dx
+ * are overwritten and must not alias x.  size must be 1, 3, 5, 7 or 9 (CCT_EUNSUPPORTED
+ * otherwise), k > 0, alpha >= 0 (CCT_EINVAL otherwise).  CaffeNet: size 5, alpha 1e-4, beta 0.75,
+ * k 1.  Arithmetic is fp32 (powf).
+ */
+typedef struct {
+  int32_t N, C, H, W;
+  int32_t size;
+  float alpha, beta, k;
+} cct_lrn_desc_t;
+int cct_lrn_forward(const cct_lrn_desc_t* desc, const float* x, float* y, void* hip_stream);
+int cct_lrn_backward(const cct_lrn_desc_t* desc, const float* x, const float* dy, float* dx,
+                     void* hip_stream);
+
+/*
  * Measurement aid (used by bench.py for the per-kernel roofline figures).  While enabled,
  * every kernel launch of the library is bracketed by two HIP events on the launching stream.
  * This is the one place where the library creates HIP objects (events, host side only); it

@@ -33,7 +33,7 @@ EXPORTS = [
     "cct_conv_backward_weights", "cct_lowered_ld", "cct_lower", "cct_profile_enable",
     "cct_profile_read", "cct_calibration_copy", "cct_conv_forward_static",
     "cct_relu_forward", "cct_relu_backward", "cct_pool_output_dims", "cct_maxpool_forward",
-    "cct_maxpool_backward",
+    "cct_maxpool_backward", "cct_lrn_forward", "cct_lrn_backward",
 ]
 
 
@@ -75,12 +75,20 @@ class PoolDesc(ctypes.Structure):
     _fields_ = [(k, ctypes.c_int32) for k in ("N", "C", "H", "W", "K", "stride", "pad")]
 
 
+class LrnDesc(ctypes.Structure):
+    """cct_lrn_desc_t."""
+    _fields_ = [(k, ctypes.c_int32) for k in ("N", "C", "H", "W", "size")] + \
+               [(k, ctypes.c_float) for k in ("alpha", "beta", "k")]
+
+
 _pp = ctypes.POINTER(PoolDesc)
 _lib.cct_relu_forward.argtypes = [_vp, _vp, _i64, _vp]
 _lib.cct_relu_backward.argtypes = [_vp, _vp, _vp, _i64, _vp]
 _lib.cct_pool_output_dims.argtypes = [_pp, ctypes.POINTER(_i32), ctypes.POINTER(_i32)]
 _lib.cct_maxpool_forward.argtypes = [_pp, _vp, _vp, _vp, _vp]
 _lib.cct_maxpool_backward.argtypes = [_pp, _vp, _vp, _vp, _vp]
+_lib.cct_lrn_forward.argtypes = [ctypes.POINTER(LrnDesc), _vp, _vp, _vp]
+_lib.cct_lrn_backward.argtypes = [ctypes.POINTER(LrnDesc), _vp, _vp, _vp, _vp]
 
 
 class ProfileEntry(ctypes.Structure):
@@ -318,3 +326,19 @@ def cct_maxpool_backward(desc: PoolDesc, dy, argmax, dx) -> None:
     _check(_lib.cct_maxpool_backward(ctypes.byref(desc), _ptr(dy, "dy", ys), _iptr(argmax, "argmax", ys),
                                      _ptr(dx, "dx", (desc.N, desc.C, desc.H, desc.W)), _stream()),
            "cct_maxpool_backward")
+
+
+def make_lrn_desc(N, C, H, W, size=5, alpha=1e-4, beta=0.75, k=1.0) -> LrnDesc:
+    return LrnDesc(N, C, H, W, size, alpha, beta, k)
+
+
+def cct_lrn_forward(desc: LrnDesc, x, y) -> None:
+    shape = (desc.N, desc.C, desc.H, desc.W)
+    _check(_lib.cct_lrn_forward(ctypes.byref(desc), _ptr(x, "x", shape), _ptr(y, "y", shape), _stream()),
+           "cct_lrn_forward")
+
+
+def cct_lrn_backward(desc: LrnDesc, x, dy, dx) -> None:
+    shape = (desc.N, desc.C, desc.H, desc.W)
+    _check(_lib.cct_lrn_backward(ctypes.byref(desc), _ptr(x, "x", shape), _ptr(dy, "dy", shape),
+                                 _ptr(dx, "dx", shape), _stream()), "cct_lrn_backward")

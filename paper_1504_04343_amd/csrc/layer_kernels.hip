@@ -1,10 +1,14 @@
-// The two layers between CaffeNet's convolutional layers, as library entry points: the rectified
-// linear unit and max pooling, forward and backward (Sec. 1: the other layers are built with the
+// The layers between CaffeNet's convolutional layers, as library entry points: the rectified
+// linear unit, max pooling and local response normalisation, forward and backward (Sec. 1: the other layers are built with the
 // same techniques as the convolution and match Caffe layer by layer; Sec. 2.2: processing the
-// whole batch at once applies to every layer).  Both are pure streaming kernels: every element of
+// whole batch at once applies to every layer).  All are pure streaming kernels: every element of
 // the input is read once and every element of the output written once, the whole batch in one
 // launch.  Semantics are Caffe's:
 //   ReLU      y = max(x, 0);  dx = dy where x > 0, else 0.
+//   LRN       across channels: scale = k + (alpha/size) * sum of x^2 over the `size` channels
+//             centred on the channel (zero padded), y = x * scale^(-beta); backward is the exact
+//             derivative.  A thread owns one pixel of one image and walks its channels once,
+//             keeping the window in registers: x (and dy) are read once, y (dx) written once.
 //   max pool  K x K windows with stride s and padding p, clipped to the image, output size
 //             ceil((H + 2p - K)/s) + 1 (minus one if the last window would start beyond the
 //             image); the FIRST maximum in row-major order of the window is the one that
@@ -140,6 +144,142 @@ inline unsigned stream_blocks(long long work_items) {
   return (unsigned)std::max<long long>(1, std::min<long long>(want, 256LL * 64));
 }
 
+
+// ---- local response normalisation -------------------------------------------------------------
+struct LrnGeom {
+  int C;
+  long long hw, pixels;  // H*W, N*H*W
+  float a, beta, k, coef;  // alpha/size; 2*alpha*beta/size
+};
+
+template <int SIZE>
+__global__ __launch_bounds__(TPB) void lrn_forward_kernel(const float* __restrict__ x,
+                                                          float* __restrict__ y, LrnGeom g) {
+  constexpr int HALF = (SIZE - 1) / 2;
+  const long long t = (long long)blockIdx.x * TPB + threadIdx.x;
+  if (t >= g.pixels) return;
+  const long long n = t / g.hw, pix = t - n * g.hw;
+  const float* xp = x + n * g.C * g.hw + pix;  // channel c of this pixel is xp[c*hw]
+  float* yp = y + n * g.C * g.hw + pix;
+  float xs[SIZE];  // x of channels c-HALF .. c+HALF
+#pragma unroll
+  for (int i = 0; i < SIZE; ++i) {
+    const int ch = i - HALF;
+    xs[i] = (ch >= 0 && ch < g.C) ? xp[ch * g.hw] : 0.f;
+  }
+  for (int c = 0; c < g.C; ++c) {
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < SIZE; ++i) sum += xs[i] * xs[i];
+    yp[c * g.hw] = xs[HALF] * powf(g.k + g.a * sum, -g.beta);
+#pragma unroll
+    for (int i = 0; i + 1 < SIZE; ++i) xs[i] = xs[i + 1];
+    const int nx = c + HALF + 1;
+    xs[SIZE - 1] = nx < g.C ? xp[nx * g.hw] : 0.f;
+  }
+}
+
+// dx[c] = dy[c]*scale[c]^-beta - coef * x[c] * sum_{|c'-c| <= HALF} dy[c'] x[c'] scale[c']^(-beta-1).
+// Iteration j computes the terms of channel j and emits channel j - HALF, whose window is then
+// complete.
+template <int SIZE>
+__global__ __launch_bounds__(TPB) void lrn_backward_kernel(const float* __restrict__ x,
+                                                           const float* __restrict__ dy,
+                                                           float* __restrict__ dx, LrnGeom g) {
+  constexpr int HALF = (SIZE - 1) / 2;
+  const long long t = (long long)blockIdx.x * TPB + threadIdx.x;
+  if (t >= g.pixels) return;
+  const long long n = t / g.hw, pix = t - n * g.hw;
+  const float* xp = x + n * g.C * g.hw + pix;
+  const float* gp = dy + n * g.C * g.hw + pix;
+  float* op = dx + n * g.C * g.hw + pix;
+  float xs[SIZE];      // x of channels j-HALF .. j+HALF
+  float tr[SIZE];      // cross terms of channels j-SIZE+1 .. j
+  float ur[HALF + 1];  // direct terms dy*scale^-beta of channels j-HALF .. j
+#pragma unroll
+  for (int i = 0; i < SIZE; ++i) {
+    const int ch = i - HALF;
+    xs[i] = (ch >= 0 && ch < g.C) ? xp[ch * g.hw] : 0.f;
+    tr[i] = 0.f;
+  }
+#pragma unroll
+  for (int i = 0; i <= HALF; ++i) ur[i] = 0.f;
+  for (int j = 0; j < g.C + HALF; ++j) {
+    // shift the term windows and append channel j
+#pragma unroll
+    for (int i = 0; i + 1 < SIZE; ++i) tr[i] = tr[i + 1];
+#pragma unroll
+    for (int i = 0; i < HALF; ++i) ur[i] = ur[i + 1];
+    float tj = 0.f, uj = 0.f;
+    if (j < g.C) {
+      float sum = 0.f;
+#pragma unroll
+      for (int i = 0; i < SIZE; ++i) sum += xs[i] * xs[i];
+      const float scale = g.k + g.a * sum;
+      const float pw = powf(scale, -g.beta);
+      const float gj = gp[j * g.hw];
+      uj = gj * pw;
+      tj = gj * xs[HALF] * pw / scale;
+    }
+    tr[SIZE - 1] = tj;
+    ur[HALF] = uj;
+    const int c = j - HALF;
+    if (c >= 0) {
+      float cross = 0.f;
+#pragma unroll
+      for (int i = 0; i < SIZE; ++i) cross += tr[i];
+      op[c * g.hw] = ur[0] - g.coef * xs[0] * cross;  // xs[0] = x of channel j - HALF
+    }
+#pragma unroll
+    for (int i = 0; i + 1 < SIZE; ++i) xs[i] = xs[i + 1];
+    const int nx = j + HALF + 1;
+    xs[SIZE - 1] = nx < g.C ? xp[nx * g.hw] : 0.f;
+  }
+}
+
+bool lrn_geom(const cct_lrn_desc_t* d, LrnGeom* g) {
+  if (!d || d->N <= 0 || d->C <= 0 || d->H <= 0 || d->W <= 0) return false;
+  if (d->size < 1 || !(d->size & 1) || !(d->k > 0.f) || !(d->alpha >= 0.f)) return false;
+  g->C = d->C;
+  g->hw = (long long)d->H * d->W;
+  g->pixels = g->hw * d->N;
+  g->a = d->alpha / (float)d->size;
+  g->beta = d->beta;
+  g->k = d->k;
+  g->coef = 2.0f * d->alpha * d->beta / (float)d->size;
+  return true;
+}
+
+template <int SIZE>
+void launch_lrn(bool backward, const float* x, const float* dy, float* out, const LrnGeom& g,
+                unsigned blocks, hipStream_t st) {
+  if (backward)
+    hipLaunchKernelGGL(lrn_backward_kernel<SIZE>, dim3(blocks), dim3(TPB), 0, st, x, dy, out, g);
+  else
+    hipLaunchKernelGGL(lrn_forward_kernel<SIZE>, dim3(blocks), dim3(TPB), 0, st, x, out, g);
+}
+
+int run_lrn(const cct_lrn_desc_t* desc, bool backward, const float* x, const float* dy, float* out,
+            hipStream_t st) {
+  LrnGeom g;
+  if (!lrn_geom(desc, &g) || !x || !out || (backward && !dy)) return CCT_EINVAL;
+  const long long blocks = (g.pixels + TPB - 1) / TPB;
+  if (blocks >= 2147483647LL) return CCT_EUNSUPPORTED;
+  const double elems = (double)g.pixels * g.C;
+  ProfScope ps(backward ? "lrn_backward_kernel" : "lrn_forward_kernel", 0.0,
+               (backward ? 12.0 : 8.0) * elems, st);
+  switch (desc->size) {
+    case 1: launch_lrn<1>(backward, x, dy, out, g, (unsigned)blocks, st); break;
+    case 3: launch_lrn<3>(backward, x, dy, out, g, (unsigned)blocks, st); break;
+    case 5: launch_lrn<5>(backward, x, dy, out, g, (unsigned)blocks, st); break;
+    case 7: launch_lrn<7>(backward, x, dy, out, g, (unsigned)blocks, st); break;
+    case 9: launch_lrn<9>(backward, x, dy, out, g, (unsigned)blocks, st); break;
+    default: return CCT_EUNSUPPORTED;  // window sizes are compiled in: 1, 3, 5, 7, 9
+  }
+  CCT_CHECK_LAUNCH();
+  return CCT_OK;
+}
+
 }  // namespace
 }  // namespace cct
 
@@ -209,6 +349,15 @@ int cct_maxpool_backward(const cct_pool_desc_t* desc, const float* dy, const int
                      dx, total, g);
   CCT_CHECK_LAUNCH();
   return CCT_OK;
+}
+
+int cct_lrn_forward(const cct_lrn_desc_t* desc, const float* x, float* y, void* hip_stream) {
+  return run_lrn(desc, false, x, nullptr, y, (hipStream_t)hip_stream);
+}
+
+int cct_lrn_backward(const cct_lrn_desc_t* desc, const float* x, const float* dy, float* dx,
+                     void* hip_stream) {
+  return run_lrn(desc, true, x, dy, dx, (hipStream_t)hip_stream);
 }
 
 }  // extern "C"

@@ -1,8 +1,8 @@
-"""The full-stack configuration run as a real chain on the GPU: conv1 -> ReLU -> pool ->
-conv2 -> ReLU -> pool -> conv3 -> ReLU -> conv4 -> ReLU -> conv5 at batch 256, fp32, AUTO lowering,
-then the gradient back through the same layers (ReLU masks, pooling argmax), with backward-weights
-at every convolution.  CaffeNet's two normalisation layers are left out (they are not part of the
-path built here); everything else is the library's own entry points.
+"""The full-stack configuration run as a real chain on the GPU: conv1 -> ReLU -> pool -> norm ->
+conv2 -> ReLU -> pool -> norm -> conv3 -> ReLU -> conv4 -> ReLU -> conv5 at batch 256, fp32, AUTO
+lowering, then the gradient back through the same layers (normalisation, pooling argmax, ReLU
+masks), with backward-weights at every convolution.  Every layer is one of the library's own
+entry points.
 
 Parity is gated per layer, teacher-forced: each convolution's outputs are compared, on sampled
 elements the oracle computes one by one, with the oracle applied to the exact fp32 tensors that
@@ -71,8 +71,11 @@ def test_caffenet_conv_stack_as_a_chain(B, N, precision):
                 pooled = torch.empty((N, C, ho, wo), device="cuda")
                 am = torch.empty((N, C, ho, wo), dtype=torch.int32, device="cuda")
                 B.cct_maxpool_forward(pd, a, pooled, am)
-                rec.update(pd=pd, am=am)
-                x = pooled
+                ld = B.make_lrn_desc(N, C, ho, wo)                # CaffeNet: size 5, alpha 1e-4, beta 0.75
+                normed = torch.empty_like(pooled)
+                B.cct_lrn_forward(ld, pooled, normed)
+                rec.update(pd=pd, am=am, ld=ld, pooled=pooled)
+                x = normed
             else:
                 x = a
         acts[L.name] = rec
@@ -89,6 +92,7 @@ def test_caffenet_conv_stack_as_a_chain(B, N, precision):
                 if L.name in pool_after:
                     C, H = pool_after[L.name]
                     oa, _ = oracle.maxpool_forward(oracle.PoolDims(k, C, H, H, 3, 2, 0), oa)
+                    oa = oracle.lrn_forward(oracle.LrnDims(k, C, oa.shape[2], oa.shape[3]), oa)
                 ox = oa
         got = host(acts["conv5"]["y"][:k])
         drift = float(np.abs(got - oy).max() / np.abs(oy).max())
@@ -121,8 +125,10 @@ def test_caffenet_conv_stack_as_a_chain(B, N, precision):
         prev = acts[layers[layers.index(L) - 1].name]
         g = dx                                                   # gradient at the previous layer's (pooled) activation
         if "pd" in prev:
+            gp = torch.empty_like(prev["pooled"])
+            B.cct_lrn_backward(prev["ld"], prev["pooled"], g, gp)
             up = torch.empty_like(prev["relu"])
-            B.cct_maxpool_backward(prev["pd"], g, prev["am"], up)
+            B.cct_maxpool_backward(prev["pd"], gp, prev["am"], up)
             g = up
         gy = torch.empty_like(prev["y"])
         B.cct_relu_backward(prev["y"], g, gy)

@@ -1,6 +1,7 @@
-"""GPU parity of the ReLU and max-pooling entry points against the CPU oracle: values, argmax
-indices and ReLU gradients bit-exact; pooling gradients (a sum of at most four fp32 terms against
-the oracle's fp64 sum) within 1e-6."""
+"""GPU parity of the ReLU, max-pooling and local-response-normalisation entry points against the
+CPU oracle: values, argmax indices and ReLU gradients bit-exact; pooling gradients (a sum of at
+most four fp32 terms against the oracle's fp64 sum) within 1e-6; normalisation (fp32 powf against
+fp64) within 1e-5 of the largest value."""
 import numpy as np
 import pytest
 
@@ -138,3 +139,69 @@ def test_pool_rejects_bad_descriptors(B):
         with pytest.raises(B.CctError) as e:
             B.cct_pool_output_dims(B.make_pool_desc(**kw))
         assert e.value.code == B.EINVAL
+
+
+# ------------------------------------------------------------------ local response normalisation
+LRN_CASES = [
+    # N, C, H, W, size, alpha, beta, k
+    (2, 9, 5, 7, 5, 0.3, 0.75, 1.0),          # strong normalisation, odd sizes
+    (3, 3, 4, 4, 5, 1e-2, 0.75, 2.0),         # fewer channels than the window
+    (1, 1, 3, 3, 3, 0.5, 0.5, 1.0),           # one channel
+    (2, 16, 6, 5, 1, 2.0, 0.5, 1.0),          # size 1: pointwise
+    (2, 20, 3, 3, 9, 0.1, 1.25, 1.0),         # widest compiled window
+    (1, 40, 13, 13, 7, 1e-3, 0.75, 1.0),
+]
+
+
+@pytest.mark.parametrize("case", LRN_CASES, ids=["c%d_s%d" % (c[1], c[4]) for c in LRN_CASES])
+def test_lrn_forward_backward(B, case):
+    """fp32 powf against the fp64 oracle: 1e-5 of the largest value (the bar of the fp32 path is 1e-4)."""
+    import torch
+    N, C, H, W, size, alpha, beta, k = case
+    rng = np.random.default_rng(size * 100 + C)
+    x = (rng.standard_normal((N, C, H, W)) * 3).astype(np.float32)
+    dy = rng.standard_normal((N, C, H, W)).astype(np.float32)
+    od = oracle.LrnDims(N, C, H, W, size, alpha, beta, k)
+    d = B.make_lrn_desc(N, C, H, W, size, alpha, beta, k)
+    tx, tdy = dev(x), dev(dy)
+    y = torch.full_like(tx, float("nan"))
+    dx = torch.full_like(tx, float("nan"))
+    B.cct_lrn_forward(d, tx, y)
+    B.cct_lrn_backward(d, tx, tdy, dx)
+    torch.cuda.synchronize()
+    want_y, want_dx = oracle.lrn_forward(od, x), oracle.lrn_backward(od, x, dy)
+    assert np.abs(y.cpu().numpy() - want_y).max() <= 1e-5 * np.abs(want_y).max()
+    assert np.abs(dx.cpu().numpy() - want_dx).max() <= 1e-5 * np.abs(want_dx).max()
+
+
+@pytest.mark.parametrize("name,C,H", [("norm1", 96, 27), ("norm2", 256, 13)])
+def test_lrn_caffenet_layers_batch_256(B, name, C, H):
+    """CaffeNet's two normalisation layers at batch 256 on post-ReLU, post-pooling like data,
+    every element against the oracle."""
+    import torch
+    N = 256
+    rng = np.random.default_rng(C)
+    x = np.maximum(rng.standard_normal((N, C, H, H)) * 20, 0).astype(np.float32)   # activations of tens
+    dy = rng.standard_normal((N, C, H, H)).astype(np.float32)
+    od = oracle.LrnDims(N, C, H, H)
+    d = B.make_lrn_desc(N, C, H, H)
+    tx, tdy = dev(x), dev(dy)
+    y, dx = torch.empty_like(tx), torch.empty_like(tx)
+    B.cct_lrn_forward(d, tx, y)
+    B.cct_lrn_backward(d, tx, tdy, dx)
+    torch.cuda.synchronize()
+    want_y, want_dx = oracle.lrn_forward(od, x), oracle.lrn_backward(od, x, dy)
+    assert np.abs(y.cpu().numpy() - want_y).max() <= 1e-5 * np.abs(want_y).max(), name
+    assert np.abs(dx.cpu().numpy() - want_dx).max() <= 1e-5 * np.abs(want_dx).max(), name
+
+
+def test_lrn_rejects_bad_descriptors(B):
+    import torch
+    t = torch.zeros((1, 4, 2, 2), device="cuda")
+    for bad, code in ((dict(size=4), B.EINVAL), (dict(size=11), B.EUNSUPPORTED), (dict(k=0.0), B.EINVAL),
+                      (dict(alpha=-1.0), B.EINVAL)):
+        kw = dict(size=5, alpha=1e-4, beta=0.75, k=1.0)
+        kw.update(bad)
+        with pytest.raises(B.CctError) as e:
+            B.cct_lrn_forward(B.make_lrn_desc(1, 4, 2, 2, **kw), t, torch.empty_like(t))
+        assert e.value.code == code, bad
