@@ -15,6 +15,9 @@ Other modes (tables on stdout, meant to be kept under profiles/):
                       (C,O) pairs, forward pass, Types 1/2/3, the fused layout and AUTO timed.
   --config batching   the batching study (Sec. 2.2): Type 1 forced, the whole step run with
                       1 .. N images per lowered matrix.
+  --config e2e        one training iteration of CaffeNet's layers that the library has (conv, ReLU,
+                      pooling, normalisation, fully connected as convolutions), with the share of
+                      time per kind of layer (Sec. 1 and 3.2 of the paper time whole iterations).
 """
 import argparse
 import json
@@ -22,6 +25,8 @@ import os
 import statistics
 import sys
 import time
+
+import numpy as np
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
@@ -63,7 +68,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", choices=["caffenet", "sweep", "batching"], default="caffenet")
+    ap.add_argument("--config", choices=["caffenet", "sweep", "batching", "e2e"], default="caffenet")
     ap.add_argument("--batch", type=int, default=None)
     ap.add_argument("--precision", choices=["f32", "bf16"], default="f32")
     ap.add_argument("--lowering", type=int, default=0, help="0 = auto (default), 1..4 = force")
@@ -446,6 +451,116 @@ def run_batching(args, B, synth, torch):
     print(json.dumps({"config": "batching", "batch": batch, "rows": rows}))
 
 
+def run_e2e(args, B, synth, torch):
+    """One training iteration of CaffeNet's layers that this library has (everything but dropout and
+    the loss): conv1-5 with ReLU, three max-pooling and two normalisation layers, fc6-8 as
+    convolutions, forward and backward (conv1's input gradient is not needed and not computed), batch
+    256.  The analogue of the paper's end-to-end timing (Sec. 3.2) and of its remark that the
+    convolutional layers take 70-90 % of the time (Sec. 1): per-kind shares from HIP events around
+    every call of a second, separately run, instrumented iteration."""
+    N = args.batch or 256
+    prec = B.PREC_F32 if args.precision == "f32" else B.PREC_BF16_IN_F32_ACC
+    convs = synth.caffenet(N)
+    fcs = [synth.Layer("fc6", N, 256, 6, 6, 4096, 6, 1, 0, 1, "relu_normal", 0.005, 0.0),
+           synth.Layer("fc7", N, 4096, 1, 1, 4096, 1, 1, 0, 1, "relu_normal", 0.005, 0.0),
+           synth.Layer("fc8", N, 4096, 1, 1, 1000, 1, 1, 0, 1, "relu_normal", 0.01, 0.0)]
+    pool_after = {"conv1": 55, "conv2": 27, "conv5": 13}
+    norm_after = ("conv1", "conv2")
+    dev = "cuda"
+    net, ws_bytes = [], 0
+    for L in convs + fcs:
+        d = B.make_desc(L.N, L.C, L.H, L.W, L.O, L.K, L.stride, L.pad, L.groups, 0, prec)
+        t = dict(L=L, d=d, kind="fc" if L.name.startswith("fc") else "conv",
+                 w=torch.from_numpy(synth.make_w(L)).cuda(), b=torch.from_numpy(synth.make_bias(L)).cuda(),
+                 y=torch.empty((N, L.O, L.Hout, L.Wout), device=dev))
+        t["dw"], t["db"] = torch.empty_like(t["w"]), torch.empty_like(t["b"])
+        t["gy"] = torch.empty_like(t["y"])              # gradient at the layer's output (before ReLU)
+        if L.name != "fc8":
+            t["a"] = torch.empty_like(t["y"])           # after ReLU
+            t["ga"] = torch.empty_like(t["y"])
+        if L.name in pool_after:
+            H = pool_after[L.name]
+            pd = B.make_pool_desc(N, L.O, H, H, 3, 2, 0)
+            ho, wo = B.cct_pool_output_dims(pd)
+            t.update(pd=pd, p=torch.empty((N, L.O, ho, wo), device=dev),
+                     am=torch.empty((N, L.O, ho, wo), dtype=torch.int32, device=dev))
+            t["gp"] = torch.empty_like(t["p"])
+            if L.name in norm_after:
+                t.update(ld=B.make_lrn_desc(N, L.O, ho, wo), n=torch.empty_like(t["p"]), gn=torch.empty_like(t["p"]))
+        for p_ in (B.PASS_FORWARD, B.PASS_BACKWARD_DATA, B.PASS_BACKWARD_WEIGHTS):
+            ws_bytes = max(ws_bytes, B.cct_conv_workspace_bytes(d, p_))
+        net.append(t)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    x0 = torch.from_numpy(synth.make_x(convs[0])).cuda()
+    g_out = torch.from_numpy(np.random.default_rng(7).standard_normal((N, 1000, 1, 1)).astype(np.float32)).cuda()
+    for i, t in enumerate(net):                       # wire inputs and input gradients
+        t["x"] = x0 if i == 0 else net[i - 1]["out"]
+        t["out"] = t.get("n", t.get("p", t.get("a", t["y"])))
+        if t["L"].name == "fc6":
+            t["x"] = t["x"].view(N, 256, 6, 6)
+        t["gx"] = None if i == 0 else torch.empty_like(t["x"])
+    flops = sum(3 * t["L"].flops for t in net) - convs[0].flops
+
+    def iteration(tick=lambda kind: None):
+        for t in net:                                  # ---- forward
+            B.cct_conv_forward(t["d"], t["x"], t["w"], t["b"], t["y"], ws); tick(t["kind"])
+            if "a" in t:
+                B.cct_relu_forward(t["y"], t["a"]); tick("relu")
+            if "pd" in t:
+                B.cct_maxpool_forward(t["pd"], t["a"], t["p"], t["am"]); tick("pool")
+            if "ld" in t:
+                B.cct_lrn_forward(t["ld"], t["p"], t["n"]); tick("norm")
+        g = g_out
+        for i in range(len(net) - 1, -1, -1):          # ---- backward
+            t = net[i]
+            if "ld" in t:
+                B.cct_lrn_backward(t["ld"], t["p"], g, t["gn"]); tick("norm"); g = t["gn"]
+            if "pd" in t:
+                B.cct_maxpool_backward(t["pd"], g.view_as(t["p"]), t["am"], t["ga"]); tick("pool"); g = t["ga"]
+            if "a" in t:
+                B.cct_relu_backward(t["y"], g.view_as(t["y"]), t["gy"]); tick("relu"); g = t["gy"]
+            g = g.view_as(t["y"])
+            B.cct_conv_backward_weights(t["d"], t["x"], g, t["dw"], t["db"], ws); tick(t["kind"])
+            if t["gx"] is not None:
+                B.cct_conv_backward_data(t["d"], t["w"], g, t["gx"], ws); tick(t["kind"])
+                g = t["gx"]
+
+    elapsed, per_step = time_steps(iteration, args.steps, args.warmup)
+    ms = elapsed / args.steps * 1e3
+    # shares: events after every call of one more iteration
+    marks = []
+    first = torch.cuda.Event(enable_timing=True)
+    first.record()
+
+    def tick(kind):
+        ev = torch.cuda.Event(enable_timing=True)
+        ev.record()
+        marks.append((kind, ev))
+    iteration(tick)
+    torch.cuda.synchronize()
+    share, prev = {}, first
+    for kind, ev in marks:
+        share[kind] = share.get(kind, 0.0) + prev.elapsed_time(ev)
+        prev = ev
+    total = sum(share.values())
+    print("# CaffeNet iteration (forward + backward, no dropout / loss), batch %d, %s: %.2f ms, %.0f images/s"
+          % (N, args.precision, ms, N / ms * 1e3), file=sys.stderr)
+    for k in sorted(share, key=lambda k: -share[k]):
+        print("#   %-6s %7.3f ms  %5.1f %%" % (k, share[k], 100 * share[k] / total), file=sys.stderr)
+    if args.per_kernel:
+        prof = profiled(B, iteration, 2)
+        for e in sorted(prof, key=lambda e: -e["total_ms"]):
+            msk = e["total_ms"] / e["launches"]
+            print("# %-44s launches/it %5.1f  avg %8.4f ms  %8.2f TFLOP/s  %8.1f GB/s" % (
+                e["name"], e["launches"] / 2, msk, e["flops"] / e["launches"] / msk / 1e9,
+                e["bytes"] / e["launches"] / msk / 1e6), file=sys.stderr)
+    print(json.dumps({"config": "e2e", "batch": N, "precision": args.precision, "ms_per_iteration": round(ms, 3),
+                      "images_per_s": round(N / ms * 1e3, 1), "gflop_per_iteration": round(flops / 1e9, 1),
+                      "tflops": round(flops / 1e9 / ms, 2), "step_time_spread": spread(per_step),
+                      "ms_by_kind": {k: round(v, 3) for k, v in share.items()},
+                      "conv_share_of_time": round(share.get("conv", 0.0) / total, 4)}))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -473,6 +588,8 @@ def main():
         run_sweep(args, B, synth, torch)
     elif args.config == "batching":
         run_batching(args, B, synth, torch)
+    elif args.config == "e2e":
+        run_e2e(args, B, synth, torch)
     else:
         run_caffenet(args, B, synth, torch)
 
