@@ -44,6 +44,7 @@ namespace {
 
 using namespace kc;
 constexpr int CS = CG + 4;  // floats between cells in LDS
+typedef float f32x4u __attribute__((ext_vector_type(4), aligned(4)));  // 16 bytes, dword aligned
 
 template <int BM, int WM, int WN>
 __global__ __launch_bounds__(NT) void conv_fused_kc_f32(GemmTN p, KcGeom fg, int tiles_m,
@@ -373,14 +374,37 @@ __global__ __launch_bounds__(NT) void conv_fused_kc_f32(GemmTN p, KcGeom fg, int
 #pragma unroll
       for (int i = 0; i < WM; ++i) {
 #pragma unroll
-        for (int r = 0; r < AR; ++r) {
-          const int m = mw + (M16 ? i * 16 + r : i * 32 + (r >> 2) * 8 + (r & 3)) + lane_hi * 4;
-          if (m < p.M) {
-            const int ci = fdiv_u(m, p.d_divSS_M, p.d_divSS_sh), rem = m - ci * ss;
-            const int rh = fdiv_u(rem, p.d_divS_M, p.d_divS_sh), rw = rem - rh * p.dS;
-            const int h = ga * p.dS + rh - p.dP, w = gb * p.dS + rw - p.dP;
-            if ((unsigned)h < (unsigned)p.dH && (unsigned)w < (unsigned)p.dW)
-              D[((img + (long long)ci * p.dH) + h) * p.dW + w] = acc[i][j][r];
+        for (int r4 = 0; r4 < AR; r4 += 4) {
+          // the lane's four consecutive rows m .. m+3 (m a multiple of 4)
+          const int m = mw + (M16 ? i * 16 : i * 32 + (r4 >> 2) * 8) + lane_hi * 4;
+          if (m >= p.M) continue;
+          const int ci = fdiv_u(m, p.d_divSS_M, p.d_divSS_sh), rem = m - ci * ss;
+          const int rh = fdiv_u(rem, p.d_divS_M, p.d_divS_sh), rw = rem - rh * p.dS;
+          const int h = ga * p.dS + rh - p.dP, w = gb * p.dS + rw - p.dP;
+          float* dst = D + ((img + (long long)ci * p.dH) + h) * p.dW + w;
+          if ((p.dS & 3) == 0) {
+            // stride a multiple of 4: the four rows are four consecutive pixels of one row of dx
+            if ((unsigned)h >= (unsigned)p.dH) continue;
+            if (w >= 0 && w + 3 < p.dW && m + 3 < p.M) {
+              f32x4u v = {acc[i][j][r4], acc[i][j][r4 + 1], acc[i][j][r4 + 2], acc[i][j][r4 + 3]};
+              *reinterpret_cast<f32x4u*>(dst) = v;  // 4-byte aligned
+            } else {
+#pragma unroll
+              for (int e = 0; e < 4; ++e)
+                if (m + e < p.M && (unsigned)(w + e) < (unsigned)p.dW) dst[e] = acc[i][j][r4 + e];
+            }
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const int me = m + e;
+              if (me < p.M) {
+                const int cie = fdiv_u(me, p.d_divSS_M, p.d_divSS_sh), reme = me - cie * ss;
+                const int rhe = fdiv_u(reme, p.d_divS_M, p.d_divS_sh), rwe = reme - rhe * p.dS;
+                const int he = ga * p.dS + rhe - p.dP, we = gb * p.dS + rwe - p.dP;
+                if ((unsigned)he < (unsigned)p.dH && (unsigned)we < (unsigned)p.dW)
+                  D[((img + (long long)cie * p.dH) + he) * p.dW + we] = acc[i][j][r4 + e];
+              }
+            }
           }
         }
       }
