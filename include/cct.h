@@ -141,6 +141,15 @@ int cct_lowering_cost(const cct_conv_desc_t* desc, cct_pass_t pass, cct_lowering
  * to process `images_per_chunk` images (1..N) at a time.  Any workspace at least as large
  * as the 1-image size is accepted by cct_conv_*; a larger one means larger chunks, up to
  * the whole batch.  desc->lowering == AUTO is resolved with cct_pick_lowering.  Host only.
+ *
+ * Fully connected layers (K == H == W, pad 0, groups 1, fp32, lowering AUTO or TYPE1: one output
+ * pixel per image, the m = 1 case of Sec. 2.1 where every lowering is a reshape of x) run as plain
+ * matrix products on x, w and dy in place, never chunked: the recommended workspace holds the
+ * split partial products of the forward pass (a few times N*O floats) or a packed copy of dy
+ * (about N*O floats).  With a smaller workspace the forward pass uses fewer splits, and a
+ * workspace below N*O floats sends the layer through the general, chunked path.  The forward
+ * pass of such a layer with C*K*K a multiple of 32 reads w with 16-byte loads: w must be 16-byte
+ * aligned (CCT_EINVAL otherwise; force another lowering for a misaligned tensor).
  */
 int cct_conv_workspace_bytes(const cct_conv_desc_t* desc, cct_pass_t pass, size_t* bytes);
 int cct_conv_workspace_bytes_for_chunk(const cct_conv_desc_t* desc, cct_pass_t pass,
@@ -158,9 +167,10 @@ int cct_conv_forward(const cct_conv_desc_t* desc, const float* x, const float* w
 /*
  * Forward pass for callers that cannot allocate or pass device memory of their own beyond the
  * tensors: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
- * Same computation, same kernels and same results as cct_conv_forward, but the workspace is a
- * fixed array of CCT_STATIC_SCRATCH_BYTES bytes inside the library's device image (every GPU
- * the library is used on holds its own copy until the process ends).  The call allocates and
+ * Same computation, same kernels and same results as cct_conv_forward with a workspace of
+ * CCT_STATIC_SCRATCH_BYTES bytes, but the workspace is a fixed array of that size inside the
+ * library's device image (every GPU the library is used on holds its own copy until the process
+ * ends).  The call allocates and
  * frees nothing, on the host side it only looks up that array's device address the first time it
  * runs on a device.  The batch is processed in chunks of as many images as fit the array;
  * CCT_ESCRATCH (nothing enqueued) if the buffers of a single image do not fit, which can only

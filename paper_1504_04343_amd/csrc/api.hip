@@ -460,6 +460,9 @@ double model_cost(const cct_conv_desc_t& d, int pass, int type) {
 int pick(const cct_conv_desc_t& d, int pass) {
   if (d.K == 1 && d.stride == 1 && d.pad == 0 && type_supported(d, pass, CCT_LOWER_TYPE1))
     return CCT_LOWER_TYPE1;
+  // one output pixel per image (a fully connected layer): every lowering is a reshape of x
+  if (d.K == d.H && d.K == d.W && d.pad == 0 && type_supported(d, pass, CCT_LOWER_TYPE1))
+    return CCT_LOWER_TYPE1;
   int best = 0;
   double best_cost = 0.0;
   for (int t = CCT_LOWER_TYPE1; t <= CCT_LOWER_FUSED; ++t) {
@@ -532,6 +535,11 @@ PackDesc make_pack(const cct_conv_desc_t& d, const Geom& g, const Layout& L, int
 }
 
 const ColMap kPlain = {kIntMax, 0};
+
+// a workspace size as the byte limit of a plan
+inline long long ws_cap(size_t bytes) {
+  return (long long)std::min<unsigned long long>(bytes, 1ULL << 62);
+}
 
 }  // namespace
 }  // namespace cct
@@ -609,6 +617,11 @@ int cct_conv_workspace_bytes_for_chunk(const cct_conv_desc_t* desc, cct_pass_t p
   const int rc = resolve(desc, pass, &type, &g);
   if (rc) return rc;
   if (images_per_chunk < 1 || images_per_chunk > desc->N) return CCT_EINVAL;
+  FcPlan fp;
+  if (images_per_chunk == desc->N && fc_plan(*desc, pass, -1, &fp)) {
+    *bytes = (size_t)fp.total;
+    return CCT_OK;
+  }
   Layout L;
   if (!make_layout(*desc, pass, type, g, images_per_chunk, &L)) return CCT_EUNSUPPORTED;
   *bytes = (size_t)L.total;
@@ -621,6 +634,11 @@ int cct_conv_workspace_bytes(const cct_conv_desc_t* desc, cct_pass_t pass, size_
   if (!bytes) return CCT_EINVAL;
   const int rc = resolve(desc, pass, &type, &g);
   if (rc) return rc;
+  FcPlan fp;
+  if (fc_plan(*desc, pass, -1, &fp)) {   // fully connected layers are never chunked
+    *bytes = (size_t)fp.total;
+    return CCT_OK;
+  }
   const long long nc = default_chunk(*desc, pass, type, g);
   Layout L;
   if (!make_layout(*desc, pass, type, g, nc, &L)) return CCT_EUNSUPPORTED;
@@ -688,13 +706,19 @@ int forward_on_workspace(const cct_conv_desc_t* desc, const float* x, const floa
   if (!x || !w || !y || (!static_scratch && !workspace)) return CCT_EINVAL;
   if (reinterpret_cast<uintptr_t>(workspace) % kAlign) return CCT_EINVAL;
   const cct_conv_desc_t& d = *desc;
+  // a fully connected layer whose plan fits the workspace: plain matrix products on x and w
+  FcPlan fp;
+  const bool fc = fc_plan(d, CCT_PASS_FORWARD, ws_cap(workspace_bytes), &fp);
   Layout L;
-  const long long nc = chunk_for_workspace(d, CCT_PASS_FORWARD, type, g, workspace_bytes, &L);
+  const long long nc =
+      fc ? d.N : chunk_for_workspace(d, CCT_PASS_FORWARD, type, g, workspace_bytes, &L);
   if (nc < 1) return static_scratch ? CCT_ESCRATCH : CCT_EWORKSPACE;
   if (static_scratch) {
     rc = scratch_address(&workspace);
     if (rc) return rc;
   }
+  if (fc)
+    return fc_forward(d, fp, x, w, bias, y, static_cast<char*>(workspace), (hipStream_t)hip_stream);
   hipStream_t st = (hipStream_t)hip_stream;
   char* ws = static_cast<char*>(workspace);
   const int bf16 = d.precision == CCT_PREC_BF16_IN_F32_ACC;
@@ -803,6 +827,9 @@ int cct_conv_backward_data(const cct_conv_desc_t* desc, const float* w, const fl
   if (!w || !dy || !dx || !workspace) return CCT_EINVAL;
   if (reinterpret_cast<uintptr_t>(workspace) % kAlign) return CCT_EINVAL;
   const cct_conv_desc_t& d = *desc;
+  FcPlan fp;
+  if (fc_plan(d, CCT_PASS_BACKWARD_DATA, ws_cap(workspace_bytes), &fp))
+    return fc_backward_data(d, fp, w, dy, dx, static_cast<char*>(workspace), (hipStream_t)hip_stream);
   Layout L;
   const long long nc = chunk_for_workspace(d, CCT_PASS_BACKWARD_DATA, type, g, workspace_bytes, &L);
   if (nc < 1) return CCT_EWORKSPACE;
@@ -931,6 +958,10 @@ int cct_conv_backward_weights(const cct_conv_desc_t* desc, const float* x, const
   if (!x || !dy || !dw || !workspace) return CCT_EINVAL;
   if (reinterpret_cast<uintptr_t>(workspace) % kAlign) return CCT_EINVAL;
   const cct_conv_desc_t& d = *desc;
+  FcPlan fp;
+  if (fc_plan(d, CCT_PASS_BACKWARD_WEIGHTS, ws_cap(workspace_bytes), &fp))
+    return fc_backward_weights(d, fp, x, dy, dw, dbias, static_cast<char*>(workspace),
+                               (hipStream_t)hip_stream);
   Layout L;
   const long long nc =
       chunk_for_workspace(d, CCT_PASS_BACKWARD_WEIGHTS, type, g, workspace_bytes, &L);

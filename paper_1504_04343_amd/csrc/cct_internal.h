@@ -83,6 +83,7 @@ struct GemmTN {
   // position (a, b) of image n is pixel (h, w) = (a*dS + rh - dP, b*dS + rw - dP) of channel
   // g*dCg + ci of the dCtot-channel, dH x dW tensor at C; pixels outside the tensor are dropped.
   int d2s, dS, dP, dH, dW, dCg, dCtot;
+  int force_bm;       // row tile to use (64 / 96 / 128; Mpad a multiple of it); 0 = gemm_tn_tile's choice
   double prof_flops;  // algorithmic flops to book for the launch when they differ from 2*M*N*K*G (else 0)
   unsigned d_divSS_M, d_divS_M;  // fast division by dS*dS and by dS
   int d_divSS_sh, d_divS_sh;
@@ -153,6 +154,26 @@ int launch_conv_bwdw_fused(const ConvBwdW& p, hipStream_t st);
 // Tile sizes the launchers will use for a problem (so that the planner can pad the packs).
 void gemm_tn_tile(int M, int Ncols, int* BM, int* BN, int* BK);
 void gemm_nt_tile(int M, int N, int* BM, int* BN, int* BK);
+
+// ---- fully connected layers (fully_connected.hip) ------------------------------------------
+// Plan of one pass of a layer with K = H = W, no padding, one group, fp32 and lowering AUTO or
+// TYPE1: plain matrix products over F = C*K*K features on the tensors in place.
+struct FcPlan {
+  int F;
+  long long pack_off, part_off, scratch_off, total;  // workspace layout (bytes)
+  int BM, Mpad, Kpad;   // packed dy of the two backward passes
+  int S, split_len;     // forward: splits of the contraction over F
+};
+// max_bytes < 0: the recommended plan; otherwise a plan within max_bytes of workspace (the forward
+// pass then uses fewer splits).  false = the descriptor is not such a layer, the pass cannot take
+// this path, or no plan fits.
+bool fc_plan(const cct_conv_desc_t& d, int pass, long long max_bytes, FcPlan* P);
+int fc_forward(const cct_conv_desc_t& d, const FcPlan& P, const float* x, const float* w,
+               const float* bias, float* y, char* ws, hipStream_t st);
+int fc_backward_data(const cct_conv_desc_t& d, const FcPlan& P, const float* w, const float* dy,
+                     float* dx, char* ws, hipStream_t st);
+int fc_backward_weights(const cct_conv_desc_t& d, const FcPlan& P, const float* x, const float* dy,
+                        float* dw, float* dbias, char* ws, hipStream_t st);
 
 // ---- index-map kernels (lowering / lifting and their adjoints) -----------------------------
 // dt[(ch*Ki+i)*Kj+j][col] = x[n, ch, h, w] or +0; col = n*Ha*Wb + a*Wb + b, n < nimg.

@@ -611,6 +611,7 @@ int launch_gemm_tn(const GemmTN& p0, hipStream_t st) {
   colmap_prepare(&p.cmap);
   int BM, BN, BK;
   gemm_tn_tile(p.M, p.Ncols, &BM, &BN, &BK);
+  if (p.force_bm == 64 || p.force_bm == 96 || p.force_bm == 128) BM = p.force_bm;
   if (p.Mpad % BM || p.Kpad % BK || p.Mpad < p.M || p.Kpad < p.Kdim) return CCT_EINVAL;
   if (p.bf16) {
     if (BM == 64) return launch_bf16<64, 128, 16, 1, 2>(p, st);

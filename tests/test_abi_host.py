@@ -254,3 +254,31 @@ def test_group_count_beyond_the_grid_limit_is_unsupported_not_a_late_failure(B):
     with pytest.raises(B.CctError) as e:
         B.cct_pick_lowering(d1, B.PASS_FORWARD)
     assert e.value.code == B.EUNSUPPORTED
+
+
+def test_fully_connected_layers_are_planned_as_matrix_products(B):
+    """K = H = W, no padding, one group, fp32, lowering AUTO or TYPE1: one output pixel per image,
+    every lowering is a reshape (Sec. 2.1 with m = 1).  The optimizer reports TYPE1 and the
+    workspace holds no lowered matrix and no kernel pack: the split partial products of the forward
+    pass (a multiple of N*O floats), the packed dy of the backward passes (about N*O floats)."""
+    N, C, K, O = 256, 256, 6, 4096
+    F = C * K * K
+    d = B.make_desc(N, C, K, K, O, K)
+    for p in (B.PASS_FORWARD, B.PASS_BACKWARD_DATA, B.PASS_BACKWARD_WEIGHTS):
+        assert B.cct_pick_lowering(d, p) == B.LOWER_TYPE1
+    fwd = B.cct_conv_workspace_bytes(d, B.PASS_FORWARD)
+    assert fwd % (4 * N * O) == 0 and 1 <= fwd // (4 * N * O) <= 64
+    assert fwd < 4 * O * F                                        # smaller than a copy of w
+    assert B.cct_conv_workspace_bytes_for_chunk(d, B.PASS_FORWARD, N) == fwd
+    for p in (B.PASS_BACKWARD_DATA, B.PASS_BACKWARD_WEIGHTS):
+        assert 4 * N * O <= B.cct_conv_workspace_bytes(d, p) <= 2 * 4 * N * O
+    # a forced layout other than TYPE1 keeps the general path and its buffers
+    for t in (B.LOWER_TYPE2, B.LOWER_TYPE3):
+        dt = B.make_desc(N, C, K, K, O, K, 1, 0, 1, t)
+        assert B.cct_conv_workspace_bytes(dt, B.PASS_FORWARD) > 4 * O * F
+    # so do groups, the bf16 variant and a feature count that is no multiple of the K tile: their
+    # workspace holds (at least) the packed kernel matrix
+    for dd in (B.make_desc(N, C, K, K, O, K, 1, 0, 2), B.make_desc(N, C, K, K, O, K, 1, 0, 1, 0, 1),
+               B.make_desc(N, 3, 5, 5, O, 5)):
+        Fg = (dd.C // dd.groups) * dd.K * dd.K
+        assert B.cct_conv_workspace_bytes(dd, B.PASS_FORWARD) >= 2 * dd.O * Fg

@@ -48,3 +48,91 @@ def test_fully_connected_as_convolution(B, L):
         assert np.abs(dw.ravel()[idx] - want).max() / np.abs(want).max() <= TOL_F32, ("backward-weights", lowering)
         db_want = dy.astype(np.float64).sum(axis=(0, 2, 3))
         assert np.abs(db - db_want).max() / np.abs(db_want).max() <= TOL_F32
+
+
+# Small layers with one output pixel, compared element by element: feature counts that are and are
+# not multiples of the GEMM's K tile (32) and column tile (128), image and kernel counts around the
+# row tiles (64 / 96 / 128), a stride that does not matter (one window), batch 1.
+SMALL_FC = [
+    layer("f48_n5", 5, 3, 4, 4, 7, 4),
+    layer("f32_n70", 70, 8, 2, 2, 33, 2),
+    layer("f64_n130", 130, 64, 1, 1, 200, 1),
+    layer("f256_o96", 64, 16, 4, 4, 96, 4),
+    layer("f288_s3", 33, 32, 3, 3, 65, 3, 3),
+    layer("f1024_n1", 1, 1024, 1, 1, 130, 1),
+    layer("f100_o1", 9, 4, 5, 5, 1, 5),
+]
+
+
+@pytest.mark.parametrize("L", SMALL_FC, ids=[L.name for L in SMALL_FC])
+@pytest.mark.parametrize("lowering", [0, 1, 2, 3, 4])
+def test_small_fully_connected_every_element(B, L, lowering):
+    assert (L.Hout, L.Wout) == (1, 1)
+    d = desc_of(B, L, lowering)
+    try:
+        for p in (B.PASS_FORWARD, B.PASS_BACKWARD_DATA, B.PASS_BACKWARD_WEIGHTS):
+            B.cct_conv_workspace_bytes(d, p)
+    except B.CctError as e:
+        assert e.code == B.EUNSUPPORTED
+        pytest.skip("lowering not offered for this shape")
+    x, w, b, dy = synth.make_x(L, 5), synth.make_w(L, 5), synth.make_bias(L, 5), synth.make_dy(L, 5)
+    od = odims(oracle, L)
+    want = oracle.conv_forward(od, x, w, b)
+    got = gpu_forward(B, L, x, w, b, lowering)
+    assert np.abs(got - want).max() / np.abs(want).max() <= TOL_F32
+    want = oracle.conv_backward_data(od, w, dy)
+    got = gpu_backward_data(B, L, w, dy, lowering)
+    assert np.abs(got - want).max() / np.abs(want).max() <= TOL_F32
+    dw_want, db_want = oracle.conv_backward_weights(od, x, dy)
+    dw, db = gpu_backward_weights(B, L, x, dy, lowering)
+    assert np.abs(dw - dw_want).max() / np.abs(dw_want).max() <= TOL_F32
+    assert np.abs(db - db_want).max() / np.abs(db_want).max() <= TOL_F32
+    dw2, _ = gpu_backward_weights(B, L, x, dy, lowering, want_dbias=False)
+    assert np.array_equal(dw, dw2)
+
+
+def test_fully_connected_without_bias_and_reproducible(B):
+    L = SMALL_FC[3]
+    x, w = synth.make_x(L, 6), synth.make_w(L, 6)
+    want = oracle.conv_forward(odims(oracle, L), x, w, None)
+    got = gpu_forward(B, L, x, w, None)
+    assert np.abs(got - want).max() / np.abs(want).max() <= TOL_F32
+    assert np.array_equal(got, gpu_forward(B, L, x, w, None))    # splits are summed in a fixed order
+
+
+@pytest.mark.parametrize("L", [layer("f1024_n512", 512, 64, 4, 4, 512, 4),
+                               layer("f32_n2048", 2048, 32, 1, 1, 256, 1)], ids=lambda L: L.name)
+def test_fully_connected_in_a_small_workspace(B, L):
+    """A workspace sized for one image per chunk is smaller than the recommended one: the forward
+    product then runs with fewer splits (first layer) or, when not even one split's partial
+    products fit, chunked through the general path (second layer), with the same result."""
+    import torch
+    x, w, b = synth.make_x(L, 7), synth.make_w(L, 7), synth.make_bias(L, 7)
+    d = desc_of(B, L)
+    full = B.cct_conv_workspace_bytes(d, B.PASS_FORWARD)
+    one = B.cct_conv_workspace_bytes_for_chunk(d, B.PASS_FORWARD, 1)
+    assert one < full
+    if L.name == "f32_n2048":
+        assert one < 4 * L.N * L.O
+    want = oracle.conv_forward(odims(oracle, L), x, w, b)
+    for nbytes in (full, one):
+        y = torch.full((L.N, L.O, 1, 1), float("nan"), device="cuda")
+        ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        B.cct_conv_forward(d, torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda(),
+                           torch.from_numpy(b).cuda(), y, ws)
+        torch.cuda.synchronize()
+        assert np.abs(y.cpu().numpy() - want).max() / np.abs(want).max() <= TOL_F32, nbytes
+
+
+def test_fully_connected_forward_needs_aligned_kernels(B):
+    """The split product reads w with 16-byte loads: a misaligned w is refused, not misread."""
+    import torch
+    L = SMALL_FC[1]
+    d = desc_of(B, L)
+    x = torch.zeros((L.N, L.C, L.H, L.W), device="cuda")
+    wbuf = torch.zeros(L.O * L.C * L.K * L.K + 1, device="cuda")
+    y = torch.empty((L.N, L.O, 1, 1), device="cuda")
+    ws = B.alloc_workspace(d, B.PASS_FORWARD)
+    with pytest.raises(B.CctError) as e:
+        B.cct_conv_forward(d, x, wbuf[1:].view(L.O, L.C, L.K, L.K), None, y, ws)
+    assert e.value.code == B.EINVAL

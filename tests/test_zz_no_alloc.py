@@ -76,3 +76,28 @@ def test_static_forward_rejects_an_image_that_does_not_fit(B):
     B.cct_conv_forward_static(desc_of(B, L, B.LOWER_FUSED), x, w, None, y)   # the fused layout fits
     torch.cuda.synchronize()
     assert bool((y == 0.0).all())
+
+
+def test_static_forward_of_fully_connected_layers(B):
+    """A fully connected layer (K = H = W) runs as a split matrix product whose partial products
+    live in the array: same bits as the ordinary entry point when the recommended plan fits, and
+    as the ordinary entry point given 32 MiB when it does not (fewer splits then)."""
+    import torch
+    got, ref, want = both(B, layer("static_fc", 64, 16, 4, 4, 96, 4), 0, 8)
+    assert got.tobytes() == ref.tobytes()
+    assert rel_err(got, want) <= TOL_F32
+    L = layer("static_fc_wide", 640, 1024, 1, 1, 4096, 1, 1, 0, 1, "relu_normal", 0.01, 0.1)
+    d = desc_of(B, L)
+    assert B.cct_conv_workspace_bytes(d, B.PASS_FORWARD) > B.STATIC_SCRATCH_BYTES
+    x, w, b = synth.make_x(L, 9), synth.make_w(L, 9), synth.make_bias(L, 9)
+    tx, tw, tb = dev(x), dev(w), dev(b)
+    y_ref = torch.full((L.N, L.O, 1, 1), float("nan"), device="cuda")
+    B.cct_conv_forward(d, tx, tw, tb, y_ref,
+                       torch.empty(B.STATIC_SCRATCH_BYTES, dtype=torch.uint8, device="cuda"))
+    y = torch.full_like(y_ref, float("nan"))
+    B.cct_conv_forward_static(d, tx, tw, tb, y)
+    torch.cuda.synchronize()
+    assert y.cpu().numpy().tobytes() == y_ref.cpu().numpy().tobytes()
+    idx = synth.sample_indices(L.N * L.O, 3000, 1)
+    want = oracle.conv_forward_at(odims(oracle, L), x, w, b, idx)
+    assert rel_err(y.cpu().numpy().ravel()[idx], want) <= TOL_F32
