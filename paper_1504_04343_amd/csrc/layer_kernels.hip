@@ -15,11 +15,11 @@
 //             receives the gradient.  The backward pass is a gather (no atomics): a pixel sums
 //             dy over the at most ceil(K/s)^2 windows that contain it and chose it.
 #include "cct_internal.h"
+#include "index_common.h"
 
 namespace cct {
 namespace {
 
-constexpr int TPB = 256;
 
 __global__ __launch_bounds__(TPB) void relu_forward_kernel(const float* __restrict__ x,
                                                            float* __restrict__ y, long long n4,
@@ -113,6 +113,45 @@ __global__ __launch_bounds__(TPB) void maxpool_backward_kernel(const float* __re
       if (argmax[o] == me) acc += dy[o];
     }
   dx[t] = acc;
+}
+
+// The same gather with the output planes staged in LDS: a workgroup owns `np` consecutive
+// (image, channel) planes, copies their dy and argmax (np*Ho*Wo values each, contiguous in memory)
+// into LDS with coalesced loads and then walks the np*H*W input pixels, which gather from LDS in
+// the same window order.  dy and argmax are read from memory once, and all index arithmetic is
+// 32-bit with multiplicative division.
+__global__ __launch_bounds__(TPB) void maxpool_backward_lds_kernel(
+    const float* __restrict__ dy, const int* __restrict__ argmax, float* __restrict__ dx,
+    long long planes, int np, PoolGeom g, FastDiv divP, FastDiv divW, FastDiv divS) {
+  extern __shared__ float pool_smem[];
+  const int Po = g.Ho * g.Wo, P = g.H * g.W;
+  const long long pl0 = (long long)blockIdx.x * np;
+  const int n_here = (int)min((long long)np, planes - pl0);
+  float* sdy = pool_smem;
+  int* sarg = reinterpret_cast<int*>(pool_smem + np * Po);
+  const float* __restrict__ dyp = dy + pl0 * Po;
+  const int* __restrict__ ap = argmax + pl0 * Po;
+  for (int i = threadIdx.x; i < n_here * Po; i += TPB) {
+    sdy[i] = dyp[i];
+    sarg[i] = ap[i];
+  }
+  __syncthreads();
+  float* __restrict__ dxp = dx + pl0 * P;
+  for (int i = threadIdx.x; i < n_here * P; i += TPB) {
+    const int pl = fdiv(i, divP), me = i - pl * P;
+    const int h = fdiv(me, divW), w = me - h * g.W;
+    const int rlo = h + g.p - g.K + 1 <= 0 ? 0 : fdiv(h + g.p - g.K + g.s, divS);
+    const int qlo = w + g.p - g.K + 1 <= 0 ? 0 : fdiv(w + g.p - g.K + g.s, divS);
+    const int rhi = min(fdiv(h + g.p, divS), g.Ho - 1), qhi = min(fdiv(w + g.p, divS), g.Wo - 1);
+    const int ob = pl * Po;
+    float acc = 0.f;
+    for (int r = rlo; r <= rhi; ++r)
+      for (int q = qlo; q <= qhi; ++q) {
+        const int o = ob + r * g.Wo + q;
+        if (sarg[o] == me) acc += sdy[o];
+      }
+    dxp[i] = acc;
+  }
 }
 
 bool pool_geom(const cct_pool_desc_t* d, PoolGeom* g) {
@@ -345,6 +384,20 @@ int cct_maxpool_backward(const cct_pool_desc_t* desc, const float* dy, const int
   hipStream_t st = (hipStream_t)hip_stream;
   ProfScope ps("maxpool_backward_kernel", 0.0,
                4.0 * (double)total + 8.0 * (double)desc->N * desc->C * g.Ho * g.Wo, st);
+  // planes whose dy and argmax fit 64 KiB of LDS: about 4096 input pixels per workgroup
+  const long long P = (long long)g.H * g.W, Po = (long long)g.Ho * g.Wo;
+  const long long planes = (long long)desc->N * desc->C;
+  if (Po * 8 <= 65536 && P <= 65536) {
+    long long np = std::max<long long>(1, 4096 / P);
+    np = std::min({np, 65536 / (Po * 8), planes});
+    const long long wgs = (planes + np - 1) / np;
+    if (wgs >= 2147483647LL) return CCT_EUNSUPPORTED;
+    hipLaunchKernelGGL(maxpool_backward_lds_kernel, dim3((unsigned)wgs), dim3(TPB),
+                       (size_t)(np * Po * 8), st, dy, argmax, dx, planes, (int)np, g,
+                       make_fastdiv((int)P), make_fastdiv(g.W), make_fastdiv(g.s));
+    CCT_CHECK_LAUNCH();
+    return CCT_OK;
+  }
   hipLaunchKernelGGL(maxpool_backward_kernel, dim3((unsigned)blocks), dim3(TPB), 0, st, dy, argmax,
                      dx, total, g);
   CCT_CHECK_LAUNCH();

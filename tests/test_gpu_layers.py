@@ -69,6 +69,8 @@ POOLS = [
     (2, 2, 8, 8, 3, 2, 1),
     (1, 1, 1, 1, 1, 1, 0),
     (1, 2, 5, 4, 5, 3, 2),
+    (5, 7, 13, 13, 3, 2, 0),      # 35 planes: the backward pass takes 24 per workgroup, then 11
+    (1, 2, 300, 290, 3, 2, 0),    # planes too large for the backward pass's LDS staging
 ]
 
 
