@@ -7,8 +7,10 @@
 //   ReLU      y = max(x, 0);  dx = dy where x > 0, else 0.
 //   LRN       across channels: scale = k + (alpha/size) * sum of x^2 over the `size` channels
 //             centred on the channel (zero padded), y = x * scale^(-beta); backward is the exact
-//             derivative.  A thread owns one pixel of one image and walks its channels once,
-//             keeping the window in registers: x (and dy) are read once, y (dx) written once.
+//             derivative.  A thread owns one pixel of one image and walks a segment of its
+//             channels (all of them when the batch has enough pixels to fill the chip), keeping
+//             the window in registers: x (and dy) are read once, apart from the few channels
+//             around a segment's ends, and y (dx) is written once.
 //   max pool  K x K windows with stride s and padding p, clipped to the image, output size
 //             ceil((H + 2p - K)/s) + 1 (minus one if the last window would start beyond the
 //             image); the FIRST maximum in row-major order of the window is the one that
@@ -187,9 +189,13 @@ inline unsigned stream_blocks(long long work_items) {
 // ---- local response normalisation -------------------------------------------------------------
 struct LrnGeom {
   int C;
+  int cs;  // channels per thread: blockIdx.y selects the segment [y*cs, min(C, (y+1)*cs))
   long long hw, pixels;  // H*W, N*H*W
   float a, beta, k, coef;  // alpha/size; 2*alpha*beta/size
 };
+
+constexpr long long kLrnThreads = 1 << 20;
+constexpr int kLrnMinSeg = 8;
 
 template <int SIZE>
 __global__ __launch_bounds__(TPB) void lrn_forward_kernel(const float* __restrict__ x,
@@ -200,13 +206,14 @@ __global__ __launch_bounds__(TPB) void lrn_forward_kernel(const float* __restric
   const long long n = t / g.hw, pix = t - n * g.hw;
   const float* xp = x + n * g.C * g.hw + pix;  // channel c of this pixel is xp[c*hw]
   float* yp = y + n * g.C * g.hw + pix;
+  const int c0 = blockIdx.y * g.cs, c1 = min(g.C, c0 + g.cs);
   float xs[SIZE];  // x of channels c-HALF .. c+HALF
 #pragma unroll
   for (int i = 0; i < SIZE; ++i) {
-    const int ch = i - HALF;
+    const int ch = c0 + i - HALF;
     xs[i] = (ch >= 0 && ch < g.C) ? xp[ch * g.hw] : 0.f;
   }
-  for (int c = 0; c < g.C; ++c) {
+  for (int c = c0; c < c1; ++c) {
     float sum = 0.f;
 #pragma unroll
     for (int i = 0; i < SIZE; ++i) sum += xs[i] * xs[i];
@@ -220,7 +227,7 @@ __global__ __launch_bounds__(TPB) void lrn_forward_kernel(const float* __restric
 
 // dx[c] = dy[c]*scale[c]^-beta - coef * x[c] * sum_{|c'-c| <= HALF} dy[c'] x[c'] scale[c']^(-beta-1).
 // Iteration j computes the terms of channel j and emits channel j - HALF, whose window is then
-// complete.
+// complete; a thread that owns channels c0 .. c1-1 therefore runs j over c0-HALF .. c1-1+HALF.
 template <int SIZE>
 __global__ __launch_bounds__(TPB) void lrn_backward_kernel(const float* __restrict__ x,
                                                            const float* __restrict__ dy,
@@ -232,25 +239,26 @@ __global__ __launch_bounds__(TPB) void lrn_backward_kernel(const float* __restri
   const float* xp = x + n * g.C * g.hw + pix;
   const float* gp = dy + n * g.C * g.hw + pix;
   float* op = dx + n * g.C * g.hw + pix;
+  const int c0 = blockIdx.y * g.cs, c1 = min(g.C, c0 + g.cs);
   float xs[SIZE];      // x of channels j-HALF .. j+HALF
   float tr[SIZE];      // cross terms of channels j-SIZE+1 .. j
   float ur[HALF + 1];  // direct terms dy*scale^-beta of channels j-HALF .. j
 #pragma unroll
   for (int i = 0; i < SIZE; ++i) {
-    const int ch = i - HALF;
+    const int ch = c0 - HALF + i - HALF;
     xs[i] = (ch >= 0 && ch < g.C) ? xp[ch * g.hw] : 0.f;
     tr[i] = 0.f;
   }
 #pragma unroll
   for (int i = 0; i <= HALF; ++i) ur[i] = 0.f;
-  for (int j = 0; j < g.C + HALF; ++j) {
+  for (int j = c0 - HALF; j < c1 + HALF; ++j) {
     // shift the term windows and append channel j
 #pragma unroll
     for (int i = 0; i + 1 < SIZE; ++i) tr[i] = tr[i + 1];
 #pragma unroll
     for (int i = 0; i < HALF; ++i) ur[i] = ur[i + 1];
     float tj = 0.f, uj = 0.f;
-    if (j < g.C) {
+    if (j >= 0 && j < g.C) {
       float sum = 0.f;
 #pragma unroll
       for (int i = 0; i < SIZE; ++i) sum += xs[i] * xs[i];
@@ -263,7 +271,7 @@ __global__ __launch_bounds__(TPB) void lrn_backward_kernel(const float* __restri
     tr[SIZE - 1] = tj;
     ur[HALF] = uj;
     const int c = j - HALF;
-    if (c >= 0) {
+    if (c >= c0) {
       float cross = 0.f;
 #pragma unroll
       for (int i = 0; i < SIZE; ++i) cross += tr[i];
@@ -272,7 +280,7 @@ __global__ __launch_bounds__(TPB) void lrn_backward_kernel(const float* __restri
 #pragma unroll
     for (int i = 0; i + 1 < SIZE; ++i) xs[i] = xs[i + 1];
     const int nx = j + HALF + 1;
-    xs[SIZE - 1] = nx < g.C ? xp[nx * g.hw] : 0.f;
+    xs[SIZE - 1] = (nx >= 0 && nx < g.C) ? xp[nx * g.hw] : 0.f;
   }
 }
 
@@ -291,11 +299,11 @@ bool lrn_geom(const cct_lrn_desc_t* d, LrnGeom* g) {
 
 template <int SIZE>
 void launch_lrn(bool backward, const float* x, const float* dy, float* out, const LrnGeom& g,
-                unsigned blocks, hipStream_t st) {
+                dim3 grid, hipStream_t st) {
   if (backward)
-    hipLaunchKernelGGL(lrn_backward_kernel<SIZE>, dim3(blocks), dim3(TPB), 0, st, x, dy, out, g);
+    hipLaunchKernelGGL(lrn_backward_kernel<SIZE>, grid, dim3(TPB), 0, st, x, dy, out, g);
   else
-    hipLaunchKernelGGL(lrn_forward_kernel<SIZE>, dim3(blocks), dim3(TPB), 0, st, x, out, g);
+    hipLaunchKernelGGL(lrn_forward_kernel<SIZE>, grid, dim3(TPB), 0, st, x, out, g);
 }
 
 int run_lrn(const cct_lrn_desc_t* desc, bool backward, const float* x, const float* dy, float* out,
@@ -307,12 +315,22 @@ int run_lrn(const cct_lrn_desc_t* desc, bool backward, const float* x, const flo
   const double elems = (double)g.pixels * g.C;
   ProfScope ps(backward ? "lrn_backward_kernel" : "lrn_forward_kernel", 0.0,
                (backward ? 12.0 : 8.0) * elems, st);
+  // A thread walks a segment of the channels of its pixel.  With few pixels (CaffeNet's norm2 has
+  // 43 264 at batch 256) one thread per pixel leaves most of the chip idle, so the channels are cut
+  // into segments of at least kLrnMinSeg until about kLrnThreads threads exist; a segment re-reads
+  // the size-1 (backward: 2*(size-1)) neighbouring channels of its ends.
+  const long long want = (kLrnThreads + g.pixels - 1) / g.pixels;
+  const long long nseg0 = std::max<long long>(1, std::min<long long>(want, g.C / kLrnMinSeg));
+  g.cs = (int)((g.C + nseg0 - 1) / nseg0);
+  const unsigned nseg = (unsigned)((g.C + g.cs - 1) / g.cs);
+  if (nseg > 65535) return CCT_EUNSUPPORTED;
+  const dim3 grid((unsigned)blocks, nseg);
   switch (desc->size) {
-    case 1: launch_lrn<1>(backward, x, dy, out, g, (unsigned)blocks, st); break;
-    case 3: launch_lrn<3>(backward, x, dy, out, g, (unsigned)blocks, st); break;
-    case 5: launch_lrn<5>(backward, x, dy, out, g, (unsigned)blocks, st); break;
-    case 7: launch_lrn<7>(backward, x, dy, out, g, (unsigned)blocks, st); break;
-    case 9: launch_lrn<9>(backward, x, dy, out, g, (unsigned)blocks, st); break;
+    case 1: launch_lrn<1>(backward, x, dy, out, g, grid, st); break;
+    case 3: launch_lrn<3>(backward, x, dy, out, g, grid, st); break;
+    case 5: launch_lrn<5>(backward, x, dy, out, g, grid, st); break;
+    case 7: launch_lrn<7>(backward, x, dy, out, g, grid, st); break;
+    case 9: launch_lrn<9>(backward, x, dy, out, g, grid, st); break;
     default: return CCT_EUNSUPPORTED;  // window sizes are compiled in: 1, 3, 5, 7, 9
   }
   CCT_CHECK_LAUNCH();
