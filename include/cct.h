@@ -145,9 +145,11 @@ int cct_lowering_cost(const cct_conv_desc_t* desc, cct_pass_t pass, cct_lowering
  * Fully connected layers (K == H == W, pad 0, groups 1, fp32, lowering AUTO or TYPE1: one output
  * pixel per image, the m = 1 case of Sec. 2.1 where every lowering is a reshape of x) run as plain
  * matrix products on x, w and dy in place, never chunked: the recommended workspace holds the
- * split partial products of the forward pass (a few times N*O floats) or a packed copy of dy
- * (about N*O floats).  With a smaller workspace the forward pass uses fewer splits, and a
- * workspace below N*O floats sends the layer through the general, chunked path.  The forward
+ * split partial products of the forward pass (a few times N*O floats), or a packed copy of dy
+ * (about N*O floats) and, for the backward-data pass, its split partial products (a few times
+ * N*C*K*K floats).  With a smaller workspace these two passes use fewer splits, and a workspace
+ * too small for the unsplit product (forward: N*O floats; backward: the packed dy) sends the layer
+ * through the general, chunked path.  The forward
  * pass of such a layer with C*K*K a multiple of 32 reads w with 16-byte loads: w must be 16-byte
  * aligned (CCT_EINVAL otherwise; force another lowering for a misaligned tensor).
  */

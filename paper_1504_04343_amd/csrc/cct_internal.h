@@ -161,8 +161,8 @@ void gemm_nt_tile(int M, int N, int* BM, int* BN, int* BK);
 struct FcPlan {
   int F;
   long long pack_off, part_off, scratch_off, total;  // workspace layout (bytes)
-  int BM, Mpad, Kpad;   // packed dy of the two backward passes
-  int S, split_len;     // forward: splits of the contraction over F
+  int BM, Mpad, Kpad;   // packed dy of the two backward passes (Kpad: rows of one split)
+  int S, split_len;     // splits of the contraction: forward over F, backward-data over O
 };
 // max_bytes < 0: the recommended plan; otherwise a plan within max_bytes of workspace (the forward
 // pass then uses fewer splits).  false = the descriptor is not such a layer, the pass cannot take

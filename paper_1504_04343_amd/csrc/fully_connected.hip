@@ -10,6 +10,8 @@
 // with no lowered copy, no kernel-matrix pack and no chunking.  The forward product has only
 // N*O outputs (few tiles) and a long contraction, so it is split over F into partial products
 // that a second kernel sums in split order together with the bias (bit-reproducible, no atomics).
+// The backward-data product has N*F outputs, still too few tiles at CaffeNet's batch, and is split
+// over O the same way when O has a suitable divisor (the splits run as the groups of one launch).
 #include <algorithm>
 #include <cstring>
 
@@ -26,35 +28,44 @@ constexpr int kDbiasBlocks = 64;
 constexpr int kFcTargetBlocks = 1024;
 constexpr int kFcMinSplit = 256;
 constexpr long long kFcMaxPartBytes = 256LL << 20;
+// backward-data: workgroups that fill the chip, and the fewest kernels a split may hold
+constexpr int kFcFillBlocks = 512;
+constexpr int kFcMinSplitRows = 128;
 
 inline long long align_up(long long v, long long a) { return (v + a - 1) / a * a; }
 
-// pack[k][m] (Kpad x Mpad, zero padded) = transposed ? src[m][k] : src[k][m], src compact.
-// 32 x 32 tiles through LDS so that reads and writes are both row-contiguous.
+// pack[r][m] (Kpad x Mpad, zero padded) = transposed ? src[m][k] : src[k][m], src compact, where
+// row r = g*Kpad_s + kk stands for k = g*Ks + kk (kk < Ks; the other rows of a split are zero):
+// the K indices are cut into splits of Ks, each padded to Kpad_s rows.  32 x 32 tiles through LDS
+// so that reads and writes are both row-contiguous.
 __global__ __launch_bounds__(TPB) void fc_pack_kernel(const float* __restrict__ src,
                                                       float* __restrict__ pack, int K, int M,
-                                                      int Kpad, int Mpad, int transposed) {
+                                                      int Kpad, int Mpad, int transposed, int Ks,
+                                                      int Kpad_s) {
   __shared__ float tile[32][33];
   const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
-  const int k0 = blockIdx.y * 32, m0 = blockIdx.x * 32;
+  const int r0 = blockIdx.y * 32, m0 = blockIdx.x * 32;
   if (transposed) {
+    const int r = r0 + tx, g = r / Kpad_s, kk = r - g * Kpad_s, k = g * Ks + kk;
+    const bool kok = r < Kpad && kk < Ks && k < K;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      const int m = m0 + ty + j * 8, k = k0 + tx;
-      tile[ty + j * 8][tx] = (m < M && k < K) ? src[(long long)m * K + k] : 0.0f;
+      const int m = m0 + ty + j * 8;
+      tile[ty + j * 8][tx] = (m < M && kok) ? src[(long long)m * K + k] : 0.0f;
     }
     __syncthreads();
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      const int k = k0 + ty + j * 8, m = m0 + tx;
-      if (k < Kpad && m < Mpad) pack[(long long)k * Mpad + m] = tile[tx][ty + j * 8];
+      const int rr = r0 + ty + j * 8, m = m0 + tx;
+      if (rr < Kpad && m < Mpad) pack[(long long)rr * Mpad + m] = tile[tx][ty + j * 8];
     }
   } else {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      const int k = k0 + ty + j * 8, m = m0 + tx;
-      if (k < Kpad && m < Mpad)
-        pack[(long long)k * Mpad + m] = (k < K && m < M) ? src[(long long)k * M + m] : 0.0f;
+      const int r = r0 + ty + j * 8, m = m0 + tx;
+      const int g = r / Kpad_s, kk = r - g * Kpad_s, k = g * Ks + kk;
+      if (r < Kpad && m < Mpad)
+        pack[(long long)r * Mpad + m] = (kk < Ks && k < K && m < M) ? src[(long long)k * M + m] : 0.0f;
     }
   }
 }
@@ -84,12 +95,25 @@ __global__ __launch_bounds__(TPB) void fc_sum_splits_kernel(const float* __restr
   y[t] = acc;
 }
 
+// Kpad = total rows of the pack = splits * Kpad_s
 int launch_fc_pack(const float* src, float* pack, int K, int M, int Kpad, int Mpad, int transposed,
-                   hipStream_t st) {
+                   int Ks, int Kpad_s, hipStream_t st) {
   dim3 grid((unsigned)((Mpad + 31) / 32), (unsigned)((Kpad + 31) / 32));
   if (grid.y > 65535) return CCT_EUNSUPPORTED;
   ProfScope ps("fc_pack_kernel", 0.0, 4.0 * ((double)K * M + (double)Kpad * Mpad), st);
-  hipLaunchKernelGGL(fc_pack_kernel, grid, dim3(TPB), 0, st, src, pack, K, M, Kpad, Mpad, transposed);
+  hipLaunchKernelGGL(fc_pack_kernel, grid, dim3(TPB), 0, st, src, pack, K, M, Kpad, Mpad, transposed,
+                     Ks, Kpad_s);
+  CCT_CHECK_LAUNCH();
+  return CCT_OK;
+}
+
+int launch_fc_sum_splits(const float* part, float* out, int S, long long total, int O,
+                         const float* bias, hipStream_t st) {
+  const long long blocks = (total + TPB - 1) / TPB;
+  if (!grid_ok(blocks) || (bias && total >= kIntMax)) return CCT_EUNSUPPORTED;
+  ProfScope ps("fc_sum_splits_kernel", 0.0, 4.0 * total * (S + 1), st);
+  hipLaunchKernelGGL(fc_sum_splits_kernel, dim3((unsigned)blocks), dim3(TPB), 0, st, part, out, S,
+                     total, make_fastdiv(O), bias);
   CCT_CHECK_LAUNCH();
   return CCT_OK;
 }
@@ -126,18 +150,32 @@ bool fc_plan(const cct_conv_desc_t& d, int pass, long long max_bytes, FcPlan* P)
     P->S = (int)((F + P->split_len - 1) / P->split_len);
     take(4LL * P->S * d.N * d.O, &P->part_off);
   } else if (pass == CCT_PASS_BACKWARD_DATA) {
-    // rows = images; 64-row tiles when that fills the chip better than 128-row ones
+    // rows = images.  Too few tiles to fill the chip: split the contraction into S equal parts
+    // (the smallest divisor S of O that gives kFcFillBlocks workgroups, else the largest one with
+    // parts of at least kFcMinSplitRows kernels) whose partial products are summed afterwards; with
+    // no such divisor, 64-row tiles when they fill the chip better.
     gemm_tn_tile(d.N, (int)F, &BM, &BN, &BK);
-    if (BM == 128 && d.N % 64 == 0 && (long long)(d.N / 128) * ((F + BN - 1) / BN) < 512) BM = 64;
+    const long long tiles = (long long)((d.N + BM - 1) / BM) * ((F + BN - 1) / BN);
+    const long long cap = max_bytes < 0 ? kFcMaxPartBytes : std::min(kFcMaxPartBytes, max_bytes);
+    int S = 1;
+    for (int sp = 2; sp <= 64 && tiles * S < kFcFillBlocks; ++sp)
+      if (d.O % sp == 0 && d.O / sp >= kFcMinSplitRows &&
+          sp * align_up(4LL * d.N * F, kAlign) + 4LL * align_up(d.N, BM) * (d.O + 16LL * sp) <= cap)
+        S = sp;
+    if (S == 1 && BM == 128 && d.N % 64 == 0 && tiles < 512) BM = 64;
     P->BM = BM;
+    P->S = S;
+    P->split_len = d.O / S;
     P->Mpad = (int)align_up(d.N, BM);
-    P->Kpad = (int)align_up(d.O, BK);
-    take(4LL * P->Kpad * P->Mpad, &P->pack_off);
+    P->Kpad = (int)align_up(P->split_len, BK);   // rows of one split
+    take(4LL * S * P->Kpad * P->Mpad, &P->pack_off);
+    if (S > 1) take(4LL * S * d.N * F, &P->part_off);
   } else {
     gemm_tn_tile(d.O, (int)F, &BM, &BN, &BK);
     P->BM = BM;
     P->Mpad = (int)align_up(d.O, BM);
     P->Kpad = (int)align_up(d.N, BK);
+    P->S = 1;
     take(4LL * P->Kpad * P->Mpad, &P->pack_off);
     take(4LL * d.O * kDbiasBlocks, &P->scratch_off);
   }
@@ -158,39 +196,40 @@ int fc_forward(const cct_conv_desc_t& d, const FcPlan& P, const float* x, const 
   q.G = 1; q.S = P.S; q.split_len = P.split_len;
   int rc = launch_gemm_nt(q, st);
   if (rc) return rc;
-  const long long total = (long long)d.N * d.O;
-  const long long blocks = (total + TPB - 1) / TPB;
-  if (!grid_ok(blocks)) return CCT_EUNSUPPORTED;
-  ProfScope ps("fc_sum_splits_kernel", 0.0, 4.0 * total * (P.S + 1), st);
-  hipLaunchKernelGGL(fc_sum_splits_kernel, dim3((unsigned)blocks), dim3(TPB), 0, st, q.Cpart, y, P.S,
-                     total, make_fastdiv(d.O), bias);
-  CCT_CHECK_LAUNCH();
-  return CCT_OK;
+  return launch_fc_sum_splits(q.Cpart, y, P.S, (long long)d.N * d.O, d.O, bias, st);
 }
 
 int fc_backward_data(const cct_conv_desc_t& d, const FcPlan& P, const float* w, const float* dy,
                      float* dx, char* ws, hipStream_t st) {
   float* pack = reinterpret_cast<float*>(ws + P.pack_off);
-  int rc = launch_fc_pack(dy, pack, d.O, d.N, P.Kpad, P.Mpad, 1, st);  // pack[o][n] = dy[n][o]
+  // pack[s][oo][n] = dy[n][s*split_len + oo]
+  int rc = launch_fc_pack(dy, pack, d.O, d.N, P.S * P.Kpad, P.Mpad, 1, P.split_len, P.Kpad, st);
   if (rc) return rc;
+  float* part = reinterpret_cast<float*>(ws + P.part_off);
   GemmTN p;
   std::memset(&p, 0, sizeof(p));
   p.A = pack;
+  p.a_gs = (long long)P.Kpad * P.Mpad;
   p.Mpad = P.Mpad; p.Kpad = P.Kpad;
   p.B = w; p.b_ks = P.F;
+  p.b_gs = (long long)P.split_len * P.F;     // a split = the next split_len kernels
   p.bmap = ColMap{kIntMax, 0};
   p.b_ld_guard = P.F % 128 == 0 ? P.F : 0;   // whole column tiles can be read as vectors
-  p.C = dx; p.c_ms = P.F;
+  p.C = P.S > 1 ? part : dx;
+  p.c_ms = P.F;
+  p.c_gs = (long long)d.N * P.F;
   p.cmap = ColMap{kIntMax, 0};
-  p.M = d.N; p.Ncols = P.F; p.Kdim = d.O; p.G = 1;
+  p.M = d.N; p.Ncols = P.F; p.Kdim = P.split_len; p.G = P.S;
   p.force_bm = P.BM;
-  return launch_gemm_tn(p, st);
+  rc = launch_gemm_tn(p, st);
+  if (rc || P.S == 1) return rc;
+  return launch_fc_sum_splits(part, dx, P.S, (long long)d.N * P.F, 1, nullptr, st);
 }
 
 int fc_backward_weights(const cct_conv_desc_t& d, const FcPlan& P, const float* x, const float* dy,
                         float* dw, float* dbias, char* ws, hipStream_t st) {
   float* pack = reinterpret_cast<float*>(ws + P.pack_off);
-  int rc = launch_fc_pack(dy, pack, d.N, d.O, P.Kpad, P.Mpad, 0, st);  // pack[n][o] = dy[n][o]
+  int rc = launch_fc_pack(dy, pack, d.N, d.O, P.Kpad, P.Mpad, 0, d.N, P.Kpad, st);  // pack[n][o] = dy[n][o]
   if (rc) return rc;
   GemmTN p;
   std::memset(&p, 0, sizeof(p));

@@ -260,7 +260,8 @@ def test_fully_connected_layers_are_planned_as_matrix_products(B):
     """K = H = W, no padding, one group, fp32, lowering AUTO or TYPE1: one output pixel per image,
     every lowering is a reshape (Sec. 2.1 with m = 1).  The optimizer reports TYPE1 and the
     workspace holds no lowered matrix and no kernel pack: the split partial products of the forward
-    pass (a multiple of N*O floats), the packed dy of the backward passes (about N*O floats)."""
+    pass (a multiple of N*O floats), the packed dy of the backward passes (about N*O floats) and the
+    split partial products of the backward-data pass (a multiple of N*C*K*K floats)."""
     N, C, K, O = 256, 256, 6, 4096
     F = C * K * K
     d = B.make_desc(N, C, K, K, O, K)
@@ -270,8 +271,12 @@ def test_fully_connected_layers_are_planned_as_matrix_products(B):
     assert fwd % (4 * N * O) == 0 and 1 <= fwd // (4 * N * O) <= 64
     assert fwd < 4 * O * F                                        # smaller than a copy of w
     assert B.cct_conv_workspace_bytes_for_chunk(d, B.PASS_FORWARD, N) == fwd
-    for p in (B.PASS_BACKWARD_DATA, B.PASS_BACKWARD_WEIGHTS):
-        assert 4 * N * O <= B.cct_conv_workspace_bytes(d, p) <= 2 * 4 * N * O
+    assert 4 * N * O <= B.cct_conv_workspace_bytes(d, B.PASS_BACKWARD_WEIGHTS) <= 2 * 4 * N * O
+    bwd = B.cct_conv_workspace_bytes(d, B.PASS_BACKWARD_DATA)
+    splits = bwd // (4 * N * F)
+    assert 2 <= splits <= 64 and O % splits == 0
+    assert 4 * N * O <= bwd - splits * 4 * N * F <= 2 * 4 * N * O
+    assert bwd < 4 * O * F
     # a forced layout other than TYPE1 keeps the general path and its buffers
     for t in (B.LOWER_TYPE2, B.LOWER_TYPE3):
         dt = B.make_desc(N, C, K, K, O, K, 1, 0, 1, t)

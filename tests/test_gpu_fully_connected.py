@@ -124,6 +124,34 @@ def test_fully_connected_in_a_small_workspace(B, L):
         assert np.abs(y.cpu().numpy() - want).max() / np.abs(want).max() <= TOL_F32, nbytes
 
 
+def test_fully_connected_backward_data_in_smaller_workspaces(B):
+    """The backward-data product is split over the kernels when the batch gives too few tiles; a
+    smaller workspace means fewer splits, then the unsplit product (first layer); a workspace below
+    the packed dy sends the layer through the general path (second layer)."""
+    import torch
+    for L, seed in ((layer("f512_o1024", 128, 512, 1, 1, 1024, 1), 8),
+                    (layer("f32_n2048", 2048, 32, 1, 1, 256, 1), 9)):
+        w, dy = synth.make_w(L, seed), synth.make_dy(L, seed)
+        d = desc_of(B, L)
+        full = B.cct_conv_workspace_bytes(d, B.PASS_BACKWARD_DATA)
+        part = 4 * L.N * L.C
+        if L.name == "f512_o1024":
+            assert full // part >= 4                                # several splits recommended
+            sizes = [full, full - part, 4 * L.N * L.O + 2 * part + 65536, 4 * L.N * L.O + 65536]
+        else:
+            one = B.cct_conv_workspace_bytes_for_chunk(d, B.PASS_BACKWARD_DATA, 1)
+            assert one < 4 * L.N * L.O
+            sizes = [full, one]
+        assert sizes == sorted(sizes, reverse=True)
+        want = oracle.conv_backward_data(odims(oracle, L), w, dy)
+        for nbytes in sizes:
+            dx = torch.full((L.N, L.C, 1, 1), float("nan"), device="cuda")
+            ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+            B.cct_conv_backward_data(d, torch.from_numpy(w).cuda(), torch.from_numpy(dy).cuda(), dx, ws)
+            torch.cuda.synchronize()
+            assert np.abs(dx.cpu().numpy() - want).max() / np.abs(want).max() <= TOL_F32, (L.name, nbytes)
+
+
 def test_fully_connected_forward_needs_aligned_kernels(B):
     """The split product reads w with 16-byte loads: a misaligned w is refused, not misread."""
     import torch
