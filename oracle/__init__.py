@@ -365,3 +365,40 @@ def lrn_backward(d: LrnDims, x, dy) -> np.ndarray:
     _check(_load().oracle_lrn_backward(ctypes.byref(d._c()), _p(x, ctypes.c_float), _p(dy, ctypes.c_float),
                                        _p(dx, ctypes.c_float)), "lrn_backward")
     return dx
+
+
+def dropout(x, mask, scale) -> np.ndarray:
+    """y = x * mask * scale (forward), or dx from dy (backward: the same map)."""
+    x = _f32(x)
+    mask = np.ascontiguousarray(mask, np.uint8)
+    _expect(mask, x.shape, "mask")
+    y = np.empty_like(x)
+    _check(_load().oracle_dropout(_p(x, ctypes.c_float), _p(mask, ctypes.c_uint8), ctypes.c_double(scale),
+                                  _p(y, ctypes.c_float), ctypes.c_int64(x.size)), "dropout")
+    return y
+
+
+def softmax_loss_forward(x, label):
+    """(prob fp32 [N, C], loss as a Python float): softmax over the C scores of each image and the
+    mean negative log-likelihood of the labels."""
+    x = _f32(x)
+    label = np.ascontiguousarray(label, np.int32)
+    N, C = x.shape
+    _expect(label, (N,), "label")
+    prob = np.empty_like(x)
+    loss = ctypes.c_double()
+    _check(_load().oracle_softmax_loss_forward(N, C, _p(x, ctypes.c_float), _p(label, ctypes.c_int32),
+                                               _p(prob, ctypes.c_float), ctypes.byref(loss)),
+           "softmax_loss_forward")
+    return prob, loss.value
+
+
+def softmax_loss_backward(prob, label) -> np.ndarray:
+    prob = _f32(prob)
+    label = np.ascontiguousarray(label, np.int32)
+    N, C = prob.shape
+    _expect(label, (N,), "label")
+    dx = np.empty_like(prob)
+    _check(_load().oracle_softmax_loss_backward(N, C, _p(prob, ctypes.c_float), _p(label, ctypes.c_int32),
+                                                _p(dx, ctypes.c_float)), "softmax_loss_backward")
+    return dx

@@ -1,6 +1,6 @@
 /*
- * CPU oracle for the two layers that sit between CaffeNet's convolutional layers: the rectified
- * linear unit and max pooling.  TEST INFRASTRUCTURE ONLY: nothing in the product path may call
+ * CPU oracle for the layers of CaffeNet other than the convolutions: the rectified linear unit,
+ * max pooling, local response normalisation, dropout and the softmax loss.  TEST INFRASTRUCTURE ONLY: nothing in the product path may call
  * this file, and it shares no code with the GPU path.
  *
  * The paper names these layers only collectively (Sec. 1: all layers are optimised with the
@@ -22,14 +22,30 @@
  *                     - (2*alpha*beta/size) * x[c] * sum over c' with |c'-c| <= (size-1)/2 of
  *                       dy[c'] * x[c'] * scale[c']^(-beta-1).
  *
+ *   dropout   (after fc6 and fc7 while training) y = x * mask * scale, mask in {0, 1} per element and
+ *             scale = 1 / (1 - ratio); backward dx = dy * mask * scale.  The random draw is the
+ *             caller's: the mask is an input, so both sides of a parity test see the same one.
+ *
+ *   softmax loss  (the last layer) over the C scores of each of N images:
+ *             prob[n,c] = exp(x[n,c] - max_c x[n,:]) / sum_c exp(x[n,c] - max_c x[n,:]),
+ *             loss = -(1/N) * sum_n log prob[n, label[n]]   (taken as x[l] - max - log(sum), so a
+ *             probability that underflows does not turn the loss into infinity),
+ *             backward dx[n,c] = (prob[n,c] - [c == label[n]]) / N, from the fp32 prob the forward
+ *             pass produced.
+ *
  * Plain loops, one output at a time, exact (comparisons and copies of fp32 values; the backward
- * sum of the few overlapping windows is done in fp64); LRN is computed in fp64 and rounded once.
+ * sum of the few overlapping windows is done in fp64); LRN, dropout's product and the softmax are
+ * computed in fp64 and rounded once.
  *
  * Pins (tests/test_oracle_pins.py): values worked out by hand, the output-size law at CaffeNet's
  * 55 -> 27 and 27 -> 13, torch's CPU max_pool2d (ceil mode) and its autograd on tie-free data,
  * the tie rule on a constant image; for LRN a hand-worked three-channel case, the closed form on a
  * constant tensor (edge channels see fewer neighbours), size 1 = a pointwise power law, torch's CPU
- * local_response_norm and its autograd, and a finite-difference check of the backward pass.
+ * local_response_norm and its autograd, and a finite-difference check of the backward pass; for
+ * dropout the identity and zero masks, torch's CPU dropout (its output fixes the mask and the scale)
+ * and the exact adjoint identity on dyadic data; for the softmax loss a hand-worked two-class case,
+ * uniform scores (prob = 1/C, loss = log C), shift invariance, torch's CPU softmax / cross_entropy
+ * and its autograd, and finite differences of the loss.
  */
 #include <math.h>
 #include <stdint.h>
@@ -182,5 +198,44 @@ int oracle_lrn_backward(const oracle_lrn_t* d, const float* x, const float* dy, 
                            2.0 * d->alpha * d->beta / d->size * (double)xp[c * hw] * cross);
     }
   }
+  return 0;
+}
+
+int oracle_dropout(const float* x, const uint8_t* mask, double scale, float* y, int64_t n) {
+  if (!x || !mask || !y || n < 0 || !(scale > 0.0)) return -1;
+  for (int64_t i = 0; i < n; ++i) y[i] = mask[i] ? (float)((double)x[i] * scale) : 0.0f;
+  return 0;
+}
+
+static int labels_ok(int N, int C, const int32_t* label) {
+  for (int n = 0; n < N; ++n)
+    if (label[n] < 0 || label[n] >= C) return 0;
+  return 1;
+}
+
+int oracle_softmax_loss_forward(int N, int C, const float* x, const int32_t* label, float* prob,
+                                double* loss) {
+  if (N <= 0 || C <= 0 || !x || !label || !prob || !loss || !labels_ok(N, C, label)) return -1;
+  double total = 0.0;
+  for (int n = 0; n < N; ++n) {
+    const float* xr = x + (int64_t)n * C;
+    double mx = xr[0], sum = 0.0;
+    for (int c = 1; c < C; ++c)
+      if (xr[c] > mx) mx = xr[c];
+    for (int c = 0; c < C; ++c) sum += exp((double)xr[c] - mx);
+    for (int c = 0; c < C; ++c) prob[(int64_t)n * C + c] = (float)(exp((double)xr[c] - mx) / sum);
+    total -= (double)xr[label[n]] - mx - log(sum);
+  }
+  *loss = total / N;
+  return 0;
+}
+
+int oracle_softmax_loss_backward(int N, int C, const float* prob, const int32_t* label, float* dx) {
+  if (N <= 0 || C <= 0 || !prob || !label || !dx || !labels_ok(N, C, label)) return -1;
+  for (int n = 0; n < N; ++n)
+    for (int c = 0; c < C; ++c) {
+      const int64_t i = (int64_t)n * C + c;
+      dx[i] = (float)(((double)prob[i] - (c == label[n] ? 1.0 : 0.0)) / N);
+    }
   return 0;
 }

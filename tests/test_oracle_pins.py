@@ -590,3 +590,103 @@ def test_lrn_backward_is_the_derivative_of_forward():
         want[idx] = ((f(xp) - f(xm)) * dy).sum() / (2 * h)
     got = oracle.lrn_backward(d, x.astype(np.float32), dy.astype(np.float32))
     np.testing.assert_allclose(got, want, rtol=2e-4, atol=2e-6)
+
+
+# ---- dropout and the softmax loss ------------------------------------------------------------
+
+def test_dropout_identity_zero_and_torch_cpu():
+    """mask of ones with scale 1 is the identity, a zero mask gives zeros; torch's CPU dropout
+    fixes the scale 1/(1-p): its output names the mask it drew, and the oracle on that mask must
+    give torch's output."""
+    import torch
+    rng = np.random.default_rng(3)
+    x = rng.standard_normal(1000).astype(np.float32) + 3.0          # no zeros in x
+    ones = np.ones(1000, np.uint8)
+    assert np.array_equal(oracle.dropout(x, ones, 1.0), x)
+    assert np.array_equal(oracle.dropout(x, np.zeros(1000, np.uint8), 2.0), np.zeros(1000, np.float32))
+    torch.manual_seed(5)
+    for p in (0.5, 0.25):
+        ty = torch.nn.functional.dropout(torch.from_numpy(x).double(), p=p, training=True).numpy()
+        mask = (ty != 0).astype(np.uint8)
+        assert 0 < mask.sum() < 1000
+        np.testing.assert_allclose(oracle.dropout(x, mask, 1.0 / (1.0 - p)), ty, rtol=1e-7)
+
+
+def test_dropout_backward_is_the_adjoint():
+    """<dropout(x), dy> == <x, dropout(dy)> exactly on small dyadic values."""
+    rng = np.random.default_rng(4)
+    x = rng.integers(-8, 9, 500).astype(np.float32) / 4
+    dy = rng.integers(-8, 9, 500).astype(np.float32) / 8
+    mask = (rng.random(500) < 0.5).astype(np.uint8)
+    lhs = (oracle.dropout(x, mask, 2.0).astype(np.float64) * dy).sum()
+    rhs = (x.astype(np.float64) * oracle.dropout(dy, mask, 2.0)).sum()
+    assert lhs == rhs
+
+
+def test_softmax_loss_hand_cases():
+    # two classes, scores (0, ln 3): probabilities 1/4 and 3/4
+    x = np.array([[0.0, np.log(3.0)]], np.float32)
+    prob, loss = oracle.softmax_loss_forward(x, [1])
+    np.testing.assert_allclose(prob, [[0.25, 0.75]], rtol=1e-6)
+    np.testing.assert_allclose(loss, -np.log(0.75), rtol=1e-6)
+    prob, loss = oracle.softmax_loss_forward(x, [0])
+    np.testing.assert_allclose(loss, np.log(4.0), rtol=1e-6)
+    np.testing.assert_allclose(oracle.softmax_loss_backward(prob, [0]), [[-0.75, 0.75]], rtol=1e-6)
+    # uniform scores: prob = 1/C whatever the level, loss = log C; the mean runs over the images
+    for C, level in ((10, 0.0), (1000, 50.0), (7, -200.0)):
+        x = np.full((3, C), level, np.float32)
+        prob, loss = oracle.softmax_loss_forward(x, [0, C - 1, C // 2])
+        np.testing.assert_allclose(prob, 1.0 / C, rtol=1e-6)
+        np.testing.assert_allclose(loss, np.log(C), rtol=1e-9)
+    # one certain image and one uniform one: the loss is their mean
+    x = np.array([[100.0, 0.0, 0.0, 0.0], [1.0, 1.0, 1.0, 1.0]], np.float32)
+    _, loss = oracle.softmax_loss_forward(x, [0, 2])
+    np.testing.assert_allclose(loss, 0.5 * np.log(4.0), rtol=1e-9)
+    with pytest.raises(ValueError):
+        oracle.softmax_loss_forward(x, [0, 4])                       # label out of range
+
+
+def test_softmax_shift_invariance_and_rows_sum_to_one():
+    rng = np.random.default_rng(6)
+    x = (rng.integers(-128, 129, (5, 33)) / 8.0).astype(np.float32)     # multiples of 1/8
+    label = rng.integers(0, 33, 5)
+    p0, l0 = oracle.softmax_loss_forward(x, label)
+    p1, l1 = oracle.softmax_loss_forward(x + np.float32(64.0), label)    # exact shift in fp32
+    np.testing.assert_allclose(p0, p1, rtol=1e-6)
+    np.testing.assert_allclose(l0, l1, rtol=1e-6)
+    np.testing.assert_allclose(p0.astype(np.float64).sum(axis=1), 1.0, rtol=1e-6)
+    # scores far apart: the losing probabilities underflow, the loss stays finite
+    x = np.array([[0.0, 200.0]], np.float32)
+    prob, loss = oracle.softmax_loss_forward(x, [0])
+    assert prob[0, 0] == 0.0 and np.isfinite(loss)
+    np.testing.assert_allclose(loss, 200.0, rtol=1e-9)
+
+
+@pytest.mark.parametrize("N,C", [(4, 10), (7, 1000), (1, 3)])
+def test_softmax_loss_against_torch_cpu(N, C):
+    import torch
+    rng = np.random.default_rng(7)
+    x = (rng.standard_normal((N, C)) * 3).astype(np.float32)
+    label = rng.integers(0, C, N)
+    tx = torch.tensor(x, dtype=torch.float64, requires_grad=True)
+    tl = torch.nn.functional.cross_entropy(tx, torch.from_numpy(label), reduction="mean")
+    tl.backward()
+    prob, loss = oracle.softmax_loss_forward(x, label)
+    np.testing.assert_allclose(prob, torch.softmax(tx.detach(), dim=1).numpy(), rtol=1e-6, atol=1e-12)
+    np.testing.assert_allclose(loss, tl.item(), rtol=1e-9)
+    np.testing.assert_allclose(oracle.softmax_loss_backward(prob, label), tx.grad.numpy(), rtol=1e-5, atol=1e-8)
+
+
+def test_softmax_loss_backward_is_the_derivative_of_the_loss():
+    rng = np.random.default_rng(9)
+    x = rng.standard_normal((3, 6)).astype(np.float32)
+    label = [5, 0, 2]
+    prob, _ = oracle.softmax_loss_forward(x, label)
+    got = oracle.softmax_loss_backward(prob, label)
+    h = np.float32(2.0 ** -7)
+    for idx in np.ndindex(*x.shape):
+        xp, xm = x.copy(), x.copy()
+        xp[idx] += h
+        xm[idx] -= h
+        fd = (oracle.softmax_loss_forward(xp, label)[1] - oracle.softmax_loss_forward(xm, label)[1]) / (2.0 * float(h))
+        np.testing.assert_allclose(got[idx], fd, rtol=2e-3, atol=2e-5)
