@@ -15,9 +15,9 @@ Other modes (tables on stdout, meant to be kept under profiles/):
                       (C,O) pairs, forward pass, Types 1/2/3, the fused layout and AUTO timed.
   --config batching   the batching study (Sec. 2.2): Type 1 forced, the whole step run with
                       1 .. N images per lowered matrix.
-  --config e2e        one training iteration of CaffeNet's layers that the library has (conv, ReLU,
-                      pooling, normalisation, fully connected as convolutions), with the share of
-                      time per kind of layer (Sec. 1 and 3.2 of the paper time whole iterations).
+  --config e2e        one training iteration of CaffeNet (conv, ReLU, pooling, normalisation, fully
+                      connected, dropout, softmax loss; no weight update), with the share of time
+                      per kind of layer (Sec. 1 and 3.2 of the paper time whole iterations).
 """
 import argparse
 import json
@@ -452,10 +452,10 @@ def run_batching(args, B, synth, torch):
 
 
 def run_e2e(args, B, synth, torch):
-    """One training iteration of CaffeNet's layers that this library has (everything but dropout and
-    the loss): conv1-5 with ReLU, three max-pooling and two normalisation layers, fc6-8 as
-    convolutions, forward and backward (conv1's input gradient is not needed and not computed), batch
-    256.  The analogue of the paper's end-to-end timing (Sec. 3.2) and of its remark that the
+    """One training iteration of CaffeNet: conv1-5 with ReLU, three max-pooling and two normalisation
+    layers, fc6-8 through the convolution entry points with ReLU and dropout (ratio 0.5, a fixed
+    seeded mask) after fc6 and fc7, the softmax loss on seeded labels; forward and backward (conv1's
+    input gradient is not needed and not computed; no weight update), batch 256.  The analogue of the paper's end-to-end timing (Sec. 3.2) and of its remark that the
     convolutional layers take 70-90 % of the time (Sec. 1): per-kind shares from HIP events around
     every call of a second, separately run, instrumented iteration."""
     N = args.batch or 256
@@ -487,15 +487,20 @@ def run_e2e(args, B, synth, torch):
             t["gp"] = torch.empty_like(t["p"])
             if L.name in norm_after:
                 t.update(ld=B.make_lrn_desc(N, L.O, ho, wo), n=torch.empty_like(t["p"]), gn=torch.empty_like(t["p"]))
+        if L.name in ("fc6", "fc7"):
+            keep = np.random.default_rng(len(net)).random((N, L.O, 1, 1)) >= 0.5
+            t.update(dm=torch.from_numpy(keep.astype(np.uint8)).cuda(), do=torch.empty_like(t["y"]))
         for p_ in (B.PASS_FORWARD, B.PASS_BACKWARD_DATA, B.PASS_BACKWARD_WEIGHTS):
             ws_bytes = max(ws_bytes, B.cct_conv_workspace_bytes(d, p_))
         net.append(t)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
     x0 = torch.from_numpy(synth.make_x(convs[0])).cuda()
-    g_out = torch.from_numpy(np.random.default_rng(7).standard_normal((N, 1000, 1, 1)).astype(np.float32)).cuda()
+    label = torch.from_numpy(np.random.default_rng(7).integers(0, 1000, N).astype(np.int32)).cuda()
+    prob = torch.empty((N, 1000), device=dev)
+    image_loss, loss = torch.empty(N, device=dev), torch.empty(1, device=dev)
     for i, t in enumerate(net):                       # wire inputs and input gradients
         t["x"] = x0 if i == 0 else net[i - 1]["out"]
-        t["out"] = t.get("n", t.get("p", t.get("a", t["y"])))
+        t["out"] = t.get("do", t.get("n", t.get("p", t.get("a", t["y"]))))
         if t["L"].name == "fc6":
             t["x"] = t["x"].view(N, 256, 6, 6)
         t["gx"] = None if i == 0 else torch.empty_like(t["x"])
@@ -510,9 +515,15 @@ def run_e2e(args, B, synth, torch):
                 B.cct_maxpool_forward(t["pd"], t["a"], t["p"], t["am"]); tick("pool")
             if "ld" in t:
                 B.cct_lrn_forward(t["ld"], t["p"], t["n"]); tick("norm")
-        g = g_out
+            if "dm" in t:
+                B.cct_dropout_forward(t["a"], t["dm"], 2.0, t["do"]); tick("drop")
+        B.cct_softmax_loss_forward(net[-1]["y"].view(N, 1000), label, prob, image_loss, loss); tick("loss")
+        g = net[-1]["gy"]
+        B.cct_softmax_loss_backward(prob, label, g.view(N, 1000)); tick("loss")
         for i in range(len(net) - 1, -1, -1):          # ---- backward
             t = net[i]
+            if "dm" in t:
+                B.cct_dropout_backward(g.view_as(t["do"]), t["dm"], 2.0, t["ga"]); tick("drop"); g = t["ga"]
             if "ld" in t:
                 B.cct_lrn_backward(t["ld"], t["p"], g, t["gn"]); tick("norm"); g = t["gn"]
             if "pd" in t:
@@ -543,7 +554,7 @@ def run_e2e(args, B, synth, torch):
         share[kind] = share.get(kind, 0.0) + prev.elapsed_time(ev)
         prev = ev
     total = sum(share.values())
-    print("# CaffeNet iteration (forward + backward, no dropout / loss), batch %d, %s: %.2f ms, %.0f images/s"
+    print("# CaffeNet iteration (forward + backward, every layer, no weight update), batch %d, %s: %.2f ms, %.0f images/s"
           % (N, args.precision, ms, N / ms * 1e3), file=sys.stderr)
     for k in sorted(share, key=lambda k: -share[k]):
         print("#   %-6s %7.3f ms  %5.1f %%" % (k, share[k], 100 * share[k] / total), file=sys.stderr)

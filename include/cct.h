@@ -230,7 +230,7 @@ int cct_lower(const cct_conv_desc_t* desc, cct_lowering_t lowering, const float*
               void* hip_stream);
 
 /*
- * The two layers between CaffeNet's convolutional layers (Sec. 1: the system optimises all layers
+ * The other layers of CaffeNet (Sec. 1: the system optimises all layers
  * with the same techniques and matches Caffe's output layer by layer; Sec. 2.2: whole-batch
  * processing applies to every layer).  The paper does not define them; the semantics are Caffe's.
  * All pointers are device pointers; outputs are overwritten; nothing is allocated.
@@ -279,6 +279,31 @@ typedef struct {
 int cct_lrn_forward(const cct_lrn_desc_t* desc, const float* x, float* y, void* hip_stream);
 int cct_lrn_backward(const cct_lrn_desc_t* desc, const float* x, const float* dy, float* dx,
                      void* hip_stream);
+
+/*
+ * Dropout, the layer CaffeNet puts after fc6 and fc7 while training (semantics are Caffe's):
+ * y[i] = x[i] * scale where mask[i] != 0, else 0, with scale = 1 / (1 - ratio); the backward pass is
+ * the same map applied to dy.  The random draw is the caller's: mask is an input (device, one byte
+ * per element), so the library holds no generator state.  y may alias x.  scale > 0 (CCT_EINVAL).
+ */
+int cct_dropout_forward(const float* x, const uint8_t* mask, float scale, float* y, int64_t n,
+                        void* hip_stream);
+int cct_dropout_backward(const float* dy, const uint8_t* mask, float scale, float* dx, int64_t n,
+                         void* hip_stream);
+
+/*
+ * Softmax with multinomial logistic loss, CaffeNet's last layer, on N x C scores (contiguous):
+ *   prob[n,c] = exp(x[n,c] - max_c x[n,:]) / sum_c exp(x[n,c] - max_c x[n,:]),
+ *   image_loss[n] = -(x[n,l] - max - log(sum)) with l = label[n],  loss[0] = mean of image_loss.
+ * Backward: dx[n,c] = (prob[n,c] - [c == label[n]]) / N.  All pointers are device pointers;
+ * prob (N*C), image_loss (N), loss (1) and dx (N*C) are overwritten; label holds N int32 values.
+ * A label outside [0, C) makes image_loss[n] and loss NaN and contributes no one-hot term; nothing
+ * is read out of bounds.  Sums run in a fixed order (bit-reproducible).  N*C < 2^31.
+ */
+int cct_softmax_loss_forward(int32_t N, int32_t C, const float* x, const int32_t* label, float* prob,
+                             float* image_loss, float* loss, void* hip_stream);
+int cct_softmax_loss_backward(int32_t N, int32_t C, const float* prob, const int32_t* label,
+                              float* dx, void* hip_stream);
 
 /*
  * Measurement aid (used by bench.py for the per-kernel roofline figures).  While enabled,

@@ -34,6 +34,8 @@ EXPORTS = [
     "cct_profile_read", "cct_calibration_copy", "cct_conv_forward_static",
     "cct_relu_forward", "cct_relu_backward", "cct_pool_output_dims", "cct_maxpool_forward",
     "cct_maxpool_backward", "cct_lrn_forward", "cct_lrn_backward",
+    "cct_dropout_forward", "cct_dropout_backward", "cct_softmax_loss_forward",
+    "cct_softmax_loss_backward",
 ]
 
 
@@ -89,6 +91,10 @@ _lib.cct_maxpool_forward.argtypes = [_pp, _vp, _vp, _vp, _vp]
 _lib.cct_maxpool_backward.argtypes = [_pp, _vp, _vp, _vp, _vp]
 _lib.cct_lrn_forward.argtypes = [ctypes.POINTER(LrnDesc), _vp, _vp, _vp]
 _lib.cct_lrn_backward.argtypes = [ctypes.POINTER(LrnDesc), _vp, _vp, _vp, _vp]
+_lib.cct_dropout_forward.argtypes = [_vp, _vp, ctypes.c_float, _vp, _i64, _vp]
+_lib.cct_dropout_backward.argtypes = [_vp, _vp, ctypes.c_float, _vp, _i64, _vp]
+_lib.cct_softmax_loss_forward.argtypes = [_i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp]
+_lib.cct_softmax_loss_backward.argtypes = [_i32, _i32, _vp, _vp, _vp, _vp]
 
 
 class ProfileEntry(ctypes.Structure):
@@ -342,3 +348,36 @@ def cct_lrn_backward(desc: LrnDesc, x, dy, dx) -> None:
     shape = (desc.N, desc.C, desc.H, desc.W)
     _check(_lib.cct_lrn_backward(ctypes.byref(desc), _ptr(x, "x", shape), _ptr(dy, "dy", shape),
                                  _ptr(dx, "dx", shape), _stream()), "cct_lrn_backward")
+
+
+def _u8ptr(t, name, shape):
+    import torch
+    if not isinstance(t, torch.Tensor) or not t.is_cuda or t.dtype != torch.uint8 or \
+            not t.is_contiguous() or tuple(t.shape) != tuple(shape):
+        raise TypeError("%s must be a contiguous uint8 GPU tensor of shape %s" % (name, tuple(shape)))
+    return t.data_ptr()
+
+
+def cct_dropout_forward(x, mask, scale, y) -> None:
+    _check(_lib.cct_dropout_forward(_ptr(x, "x"), _u8ptr(mask, "mask", x.shape), scale,
+                                    _ptr(y, "y", x.shape), x.numel(), _stream()), "cct_dropout_forward")
+
+
+def cct_dropout_backward(dy, mask, scale, dx) -> None:
+    _check(_lib.cct_dropout_backward(_ptr(dy, "dy"), _u8ptr(mask, "mask", dy.shape), scale,
+                                     _ptr(dx, "dx", dy.shape), dy.numel(), _stream()),
+           "cct_dropout_backward")
+
+
+def cct_softmax_loss_forward(x, label, prob, image_loss, loss) -> None:
+    """x, prob: [N, C] fp32; label: [N] int32; image_loss: [N] fp32; loss: [1] fp32."""
+    N, C = x.shape
+    _check(_lib.cct_softmax_loss_forward(N, C, _ptr(x, "x"), _iptr(label, "label", (N,)),
+                                         _ptr(prob, "prob", (N, C)), _ptr(image_loss, "image_loss", (N,)),
+                                         _ptr(loss, "loss", (1,)), _stream()), "cct_softmax_loss_forward")
+
+
+def cct_softmax_loss_backward(prob, label, dx) -> None:
+    N, C = prob.shape
+    _check(_lib.cct_softmax_loss_backward(N, C, _ptr(prob, "prob"), _iptr(label, "label", (N,)),
+                                          _ptr(dx, "dx", (N, C)), _stream()), "cct_softmax_loss_backward")

@@ -11,6 +11,9 @@
 //             channels (all of them when the batch has enough pixels to fill the chip), keeping
 //             the window in registers: x (and dy) are read once, apart from the few channels
 //             around a segment's ends, and y (dx) is written once.
+//   dropout   y = x * scale where the caller's mask is set, else 0 (both directions).
+//   softmax loss  softmax over the classes of each image, mean negative log-likelihood of the
+//             labels; backward (prob - onehot) / N.  One workgroup per image, fixed-order sums.
 //   max pool  K x K windows with stride s and padding p, clipped to the image, output size
 //             ceil((H + 2p - K)/s) + 1 (minus one if the last window would start beyond the
 //             image); the FIRST maximum in row-major order of the window is the one that
@@ -337,6 +340,89 @@ int run_lrn(const cct_lrn_desc_t* desc, bool backward, const float* x, const flo
   return CCT_OK;
 }
 
+// Dropout with the caller's mask: y = x * scale where mask != 0, else 0 (both directions).
+__global__ __launch_bounds__(TPB) void dropout_kernel(const float* __restrict__ x,
+                                                      const unsigned char* __restrict__ mask,
+                                                      float scale, float* __restrict__ y,
+                                                      long long n) {
+  const long long stride = (long long)gridDim.x * TPB;
+  for (long long i = (long long)blockIdx.x * TPB + threadIdx.x; i < n; i += stride)
+    y[i] = mask[i] ? x[i] * scale : 0.f;
+}
+
+// Combines one value per thread over the workgroup, always in the same order: lanes by
+// shuffles, the four waves through LDS.  Every thread gets the result.
+template <bool MAX>
+__device__ __forceinline__ float block_combine(float v, float* red) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    const float o = __shfl_xor(v, off, 64);
+    v = MAX ? fmaxf(v, o) : v + o;
+  }
+  __syncthreads();   // red may still be read from an earlier call
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  const float a = red[0], b = red[1], c = red[2], d = red[3];
+  return MAX ? fmaxf(fmaxf(a, b), fmaxf(c, d)) : (a + b) + (c + d);
+}
+
+// Softmax over the C scores of image blockIdx.x and its loss term
+// -(x[label] - max - log(sum exp(x - max))); NaN for a label outside [0, C).
+__global__ __launch_bounds__(TPB) void softmax_loss_forward_kernel(const float* __restrict__ x,
+                                                                   const int* __restrict__ label,
+                                                                   float* __restrict__ prob,
+                                                                   float* __restrict__ image_loss,
+                                                                   int C) {
+  __shared__ float red[4];
+  const float* xr = x + (long long)blockIdx.x * C;
+  float* pr = prob + (long long)blockIdx.x * C;
+  float mx = -__builtin_inff();
+  for (int c = threadIdx.x; c < C; c += TPB) mx = fmaxf(mx, xr[c]);
+  mx = block_combine<true>(mx, red);
+  float sum = 0.f;
+  for (int c = threadIdx.x; c < C; c += TPB) sum += expf(xr[c] - mx);
+  sum = block_combine<false>(sum, red);
+  const float inv = 1.0f / sum;
+  for (int c = threadIdx.x; c < C; c += TPB) pr[c] = expf(xr[c] - mx) * inv;
+  if (threadIdx.x == 0) {
+    const int l = label[blockIdx.x];
+    image_loss[blockIdx.x] =
+        (l >= 0 && l < C) ? -(xr[l] - mx - logf(sum)) : __builtin_nanf("");
+  }
+}
+
+// loss = (1/N) * sum of the per-image terms, added in a fixed order by one workgroup.
+__global__ __launch_bounds__(TPB) void mean_kernel(const float* __restrict__ v,
+                                                   float* __restrict__ out, int N) {
+  __shared__ float red[4];
+  float acc = 0.f;
+  for (int i = threadIdx.x; i < N; i += TPB) acc += v[i];
+  acc = block_combine<false>(acc, red);
+  if (threadIdx.x == 0) out[0] = acc / (float)N;
+}
+
+__global__ __launch_bounds__(TPB) void softmax_loss_backward_kernel(const float* __restrict__ prob,
+                                                                    const int* __restrict__ label,
+                                                                    float* __restrict__ dx,
+                                                                    long long total, FastDiv divC,
+                                                                    float inv_n) {
+  const long long t = (long long)blockIdx.x * TPB + threadIdx.x;
+  if (t >= total) return;
+  const int n = fdiv((int)t, divC), c = (int)t - n * divC.d;
+  dx[t] = (prob[t] - (c == label[n] ? 1.f : 0.f)) * inv_n;
+}
+
+int run_dropout(const float* x, const unsigned char* mask, float scale, float* y, long long n,
+                hipStream_t st) {
+  if (!x || !mask || !y || n < 0 || !(scale > 0.f)) return CCT_EINVAL;
+  if (n == 0) return CCT_OK;
+  const long long blocks = std::min<long long>((n + TPB - 1) / TPB, 1 << 16);
+  ProfScope ps("dropout_kernel", 0.0, 9.0 * (double)n, st);
+  hipLaunchKernelGGL(dropout_kernel, dim3((unsigned)blocks), dim3(TPB), 0, st, x, mask, scale, y, n);
+  CCT_CHECK_LAUNCH();
+  return CCT_OK;
+}
+
 }  // namespace
 }  // namespace cct
 
@@ -429,6 +515,42 @@ int cct_lrn_forward(const cct_lrn_desc_t* desc, const float* x, float* y, void* 
 int cct_lrn_backward(const cct_lrn_desc_t* desc, const float* x, const float* dy, float* dx,
                      void* hip_stream) {
   return run_lrn(desc, true, x, dy, dx, (hipStream_t)hip_stream);
+}
+
+int cct_dropout_forward(const float* x, const uint8_t* mask, float scale, float* y, int64_t n,
+                        void* hip_stream) {
+  return run_dropout(x, mask, scale, y, n, (hipStream_t)hip_stream);
+}
+
+int cct_dropout_backward(const float* dy, const uint8_t* mask, float scale, float* dx, int64_t n,
+                         void* hip_stream) {
+  return run_dropout(dy, mask, scale, dx, n, (hipStream_t)hip_stream);
+}
+
+int cct_softmax_loss_forward(int32_t N, int32_t C, const float* x, const int32_t* label, float* prob,
+                             float* image_loss, float* loss, void* hip_stream) {
+  if (N <= 0 || C <= 0 || !x || !label || !prob || !image_loss || !loss) return CCT_EINVAL;
+  hipStream_t st = (hipStream_t)hip_stream;
+  ProfScope ps("softmax_loss_forward_kernel", 0.0, 8.0 * (double)N * C, st);
+  hipLaunchKernelGGL(softmax_loss_forward_kernel, dim3((unsigned)N), dim3(TPB), 0, st, x, label, prob,
+                     image_loss, C);
+  CCT_CHECK_LAUNCH();
+  hipLaunchKernelGGL(mean_kernel, dim3(1), dim3(TPB), 0, st, image_loss, loss, N);
+  CCT_CHECK_LAUNCH();
+  return CCT_OK;
+}
+
+int cct_softmax_loss_backward(int32_t N, int32_t C, const float* prob, const int32_t* label,
+                              float* dx, void* hip_stream) {
+  if (N <= 0 || C <= 0 || !prob || !label || !dx) return CCT_EINVAL;
+  const long long total = (long long)N * C;
+  if (total >= 2147483647LL) return CCT_EUNSUPPORTED;
+  hipStream_t st = (hipStream_t)hip_stream;
+  ProfScope ps("softmax_loss_backward_kernel", 0.0, 8.0 * (double)total, st);
+  hipLaunchKernelGGL(softmax_loss_backward_kernel, dim3((unsigned)((total + TPB - 1) / TPB)), dim3(TPB),
+                     0, st, prob, label, dx, total, make_fastdiv(C), 1.0f / (float)N);
+  CCT_CHECK_LAUNCH();
+  return CCT_OK;
 }
 
 }  // extern "C"

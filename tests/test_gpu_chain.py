@@ -134,3 +134,77 @@ def test_caffenet_conv_stack_as_a_chain(B, N, precision):
         B.cct_relu_backward(prev["y"], g, gy)
         g = gy
         assert bool(torch.isfinite(g).all())
+
+
+def test_caffenet_classifier_head_as_a_chain(B):
+    """The layers after pool5 as a real chain at their CaffeNet sizes, batch 64: fc6 -> ReLU -> dropout
+    -> fc7 -> ReLU -> dropout -> fc8 -> softmax loss, and the gradient back to pool5's output.  Every
+    layer is teacher-forced against the oracle on the exact fp32 tensors the GPU layer consumed."""
+    import torch
+    from gpu_util import layer
+    N = 64
+    fcs = [layer("fc6", N, 256, 6, 6, 4096, 6, 1, 0, 1, "relu_normal", 0.005, 0.1),
+           layer("fc7", N, 4096, 1, 1, 4096, 1, 1, 0, 1, "relu_normal", 0.005, 0.1),
+           layer("fc8", N, 4096, 1, 1, 1000, 1, 1, 0, 1, "relu_normal", 0.01, 0.1)]
+    rng = np.random.default_rng(11)
+    W = {L.name: torch.from_numpy(synth.make_w(L, 3)).cuda() for L in fcs}
+    bias = {L.name: torch.from_numpy(synth.make_bias(L, 3)).cuda() for L in fcs}
+    masks = {n: torch.from_numpy((rng.random((N, 4096, 1, 1)) >= 0.5).astype(np.uint8)).cuda()
+             for n in ("fc6", "fc7")}
+    label_h = rng.integers(0, 1000, N).astype(np.int32)
+    label = torch.from_numpy(label_h).cuda()
+    x = torch.from_numpy(synth.make_x(fcs[0], 3)).cuda()
+    ins, pre = {}, {}
+    for L in fcs:                                                   # ---- forward
+        print("forward", L.name, flush=True)
+        d = desc_of(B, L)
+        ins[L.name] = x
+        y = torch.full((N, L.O, 1, 1), float("nan"), device="cuda")
+        B.cct_conv_forward(d, x, W[L.name], bias[L.name], y, B.alloc_workspace(d, B.PASS_FORWARD))
+        torch.cuda.synchronize()
+        want = oracle.conv_forward(odims(oracle, L), host(x), host(W[L.name]), host(bias[L.name]))
+        check(L.name + " forward", host(y), want.ravel(), np.arange(y.numel()), TOL_F32)
+        pre[L.name] = y
+        if L.name != "fc8":
+            a, o = torch.empty_like(y), torch.empty_like(y)
+            B.cct_relu_forward(y, a)
+            B.cct_dropout_forward(a, masks[L.name], 2.0, o)
+            torch.cuda.synchronize()
+            assert host(a).tobytes() == oracle.relu_forward(host(y)).tobytes()
+            assert host(o).tobytes() == oracle.dropout(host(a), host(masks[L.name]), 2.0).tobytes()
+            x = o.view(N, 4096, 1, 1)
+    scores = pre["fc8"].view(N, 1000)
+    prob, il, loss = torch.empty_like(scores), torch.empty(N, device="cuda"), torch.empty(1, device="cuda")
+    B.cct_softmax_loss_forward(scores, label, prob, il, loss)
+    g = torch.full((N, 1000), float("nan"), device="cuda")
+    B.cct_softmax_loss_backward(prob, label, g)
+    torch.cuda.synchronize()
+    want_prob, want_loss = oracle.softmax_loss_forward(host(scores), label_h)
+    assert np.abs(host(prob) - want_prob).max() <= 1e-5 * want_prob.max()
+    assert abs(float(loss.item()) - want_loss) <= 1e-5 * want_loss
+    print("  loss %.5f (oracle %.5f; log 1000 = %.5f)" % (float(loss.item()), want_loss, np.log(1000.0)), flush=True)
+    want_g = oracle.softmax_loss_backward(host(prob), label_h)
+    assert np.abs(host(g) - want_g).max() <= 1e-6 * np.abs(want_g).max()
+    g = g.view(N, 1000, 1, 1)
+    for L in reversed(fcs):                                         # ---- backward
+        print("backward", L.name, flush=True)
+        d = desc_of(B, L)
+        if L.name != "fc8":
+            ga, gy = torch.empty_like(pre[L.name]), torch.empty_like(pre[L.name])
+            B.cct_dropout_backward(g.view_as(ga), masks[L.name], 2.0, ga)
+            B.cct_relu_backward(pre[L.name], ga, gy)
+            torch.cuda.synchronize()
+            assert host(ga).tobytes() == oracle.dropout(host(g).reshape(ga.shape), host(masks[L.name]), 2.0).tobytes()
+            assert host(gy).tobytes() == oracle.relu_backward(host(pre[L.name]), host(ga)).tobytes()
+            g = gy
+        dw, db = torch.empty_like(W[L.name]), torch.empty_like(bias[L.name])
+        B.cct_conv_backward_weights(d, ins[L.name], g, dw, db, B.alloc_workspace(d, B.PASS_BACKWARD_WEIGHTS))
+        gx = torch.full_like(ins[L.name], float("nan"))
+        B.cct_conv_backward_data(d, W[L.name], g, gx, B.alloc_workspace(d, B.PASS_BACKWARD_DATA))
+        torch.cuda.synchronize()
+        idx = synth.sample_indices(dw.numel(), 3000, 2)
+        want = oracle.conv_backward_weights_at(odims(oracle, L), host(ins[L.name]), host(g), idx)
+        check(L.name + " backward-weights", host(dw), want, idx, TOL_F32)
+        want = oracle.conv_backward_data(odims(oracle, L), host(W[L.name]), host(g))
+        check(L.name + " backward-data", host(gx), want.ravel(), np.arange(gx.numel()), TOL_F32)
+        g = gx

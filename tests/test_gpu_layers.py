@@ -207,3 +207,72 @@ def test_lrn_rejects_bad_descriptors(B):
         with pytest.raises(B.CctError) as e:
             B.cct_lrn_forward(B.make_lrn_desc(1, 4, 2, 2, **kw), t, torch.empty_like(t))
         assert e.value.code == code, bad
+
+
+@pytest.mark.parametrize("n,ratio", [(1, 0.5), (1001, 0.5), (256 * 4096, 0.5), (70001, 0.25)])
+def test_dropout_forward_backward_bit_exact(B, n, ratio):
+    """One fp32 product per kept element: the oracle's fp64 product with the same fp32 scale rounds
+    to the same bits."""
+    import torch
+    rng = np.random.default_rng(n)
+    x = rng.standard_normal(n).astype(np.float32)
+    dy = rng.standard_normal(n).astype(np.float32)
+    mask = (rng.random(n) >= ratio).astype(np.uint8)
+    scale = float(np.float32(1.0 / (1.0 - ratio)))
+    tm = torch.from_numpy(mask).cuda()
+    y = torch.full((n,), float("nan"), device="cuda")
+    dx = torch.full((n,), float("nan"), device="cuda")
+    B.cct_dropout_forward(dev(x), tm, scale, y)
+    B.cct_dropout_backward(dev(dy), tm, scale, dx)
+    torch.cuda.synchronize()
+    assert y.cpu().numpy().tobytes() == oracle.dropout(x, mask, scale).tobytes()
+    assert dx.cpu().numpy().tobytes() == oracle.dropout(dy, mask, scale).tobytes()
+    with pytest.raises(B.CctError) as e:
+        B.cct_dropout_forward(dev(x), tm, 0.0, y)
+    assert e.value.code == B.EINVAL
+
+
+@pytest.mark.parametrize("N,C,spread", [(256, 1000, 3.0), (7, 10, 1.0), (1, 1, 1.0), (33, 300, 30.0),
+                                        (5, 2049, 0.1)])
+def test_softmax_loss_forward_backward(B, N, C, spread):
+    """fp32 expf / logf against the fp64 oracle; the backward pass on the GPU's own fp32 prob is one
+    subtraction and one product per element."""
+    import torch
+    rng = np.random.default_rng(N * 7 + C)
+    x = (rng.standard_normal((N, C)) * spread).astype(np.float32)
+    label = rng.integers(0, C, N).astype(np.int32)
+    tx, tl = dev(x), torch.from_numpy(label).cuda()
+    prob = torch.full((N, C), float("nan"), device="cuda")
+    il = torch.full((N,), float("nan"), device="cuda")
+    loss = torch.full((1,), float("nan"), device="cuda")
+    B.cct_softmax_loss_forward(tx, tl, prob, il, loss)
+    dx = torch.full((N, C), float("nan"), device="cuda")
+    B.cct_softmax_loss_backward(prob, tl, dx)
+    torch.cuda.synchronize()
+    want_prob, want_loss = oracle.softmax_loss_forward(x, label)
+    got_prob = prob.cpu().numpy()
+    assert np.abs(got_prob - want_prob).max() <= 1e-5 * want_prob.max()
+    assert abs(float(loss.item()) - want_loss) <= 1e-5 * max(abs(want_loss), 1.0)
+    _, one = oracle.softmax_loss_forward(x[:1], label[:1])
+    assert abs(float(il[0].item()) - one) <= 1e-5 * max(abs(one), 1.0)
+    want_dx = oracle.softmax_loss_backward(got_prob, label)          # from the prob the GPU consumed
+    assert np.abs(dx.cpu().numpy() - want_dx).max() <= 1e-6 * np.abs(want_dx).max()
+    # same bits on a second run (fixed-order sums)
+    prob2, il2, loss2 = torch.empty_like(prob), torch.empty_like(il), torch.empty_like(loss)
+    B.cct_softmax_loss_forward(tx, tl, prob2, il2, loss2)
+    torch.cuda.synchronize()
+    assert torch.equal(prob, prob2) and torch.equal(loss, loss2)
+
+
+def test_softmax_loss_label_out_of_range_gives_nan_not_a_fault(B):
+    import torch
+    x = torch.zeros((3, 5), device="cuda")
+    label = torch.tensor([0, 7, -1], dtype=torch.int32, device="cuda")
+    prob, il, loss = torch.empty_like(x), torch.empty(3, device="cuda"), torch.empty(1, device="cuda")
+    B.cct_softmax_loss_forward(x, label, prob, il, loss)
+    dx = torch.empty_like(x)
+    B.cct_softmax_loss_backward(prob, label, dx)
+    torch.cuda.synchronize()
+    assert bool(torch.isnan(il[1])) and bool(torch.isnan(il[2])) and bool(torch.isnan(loss[0]))
+    assert abs(float(il[0]) - np.log(5.0)) < 1e-5
+    assert torch.allclose(dx[1], torch.full((5,), 0.2 / 3, device="cuda"))
