@@ -145,7 +145,9 @@ bool fc_plan(const cct_conv_desc_t& d, int pass, long long max_bytes, FcPlan* P)
                                                              F / kFcMinSplit));
     // fewer, longer splits when the partial products would not fit
     const long long cap = max_bytes < 0 ? kFcMaxPartBytes : std::min(kFcMaxPartBytes, max_bytes);
-    S = std::min(S, std::max<long long>(1, cap / align_up(4LL * d.N * d.O, kAlign)));
+    long long smax = cap / (4LL * d.N * d.O);
+    while (smax > 1 && align_up(4LL * smax * d.N * d.O, kAlign) > cap) --smax;
+    S = std::min(S, std::max<long long>(1, smax));
     P->split_len = (int)align_up((F + S - 1) / S, BK);
     P->S = (int)((F + P->split_len - 1) / P->split_len);
     take(4LL * P->S * d.N * d.O, &P->part_off);

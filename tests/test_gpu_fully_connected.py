@@ -152,6 +152,29 @@ def test_fully_connected_backward_data_in_smaller_workspaces(B):
             assert np.abs(dx.cpu().numpy() - want).max() / np.abs(want).max() <= TOL_F32, (L.name, nbytes)
 
 
+@pytest.mark.parametrize("L", [layer("f1024_n256", 256, 1024, 1, 1, 1024, 1), layer("f288_n33", 33, 32, 3, 3, 65, 3),
+                               layer("f2048_n5", 5, 128, 4, 4, 7, 4)], ids=lambda L: L.name)
+def test_recommended_workspace_runs_the_recommended_plan(B, L):
+    """The number of splits decides the rounding order, so the bits tell which plan ran: a workspace
+    of exactly the recommended size must give the bits of a much larger one (which cannot be short
+    of room for the recommended plan)."""
+    import torch
+    x, w, b, dy = synth.make_x(L, 4), synth.make_w(L, 4), synth.make_bias(L, 4), synth.make_dy(L, 4)
+    d = desc_of(B, L)
+    tx, tw, tb, tdy = (torch.from_numpy(a).cuda() for a in (x, w, b, dy))
+    outs = {}
+    for extra in (0, 64 << 20):
+        y = torch.full((L.N, L.O, 1, 1), float("nan"), device="cuda")
+        ws = torch.empty(B.cct_conv_workspace_bytes(d, B.PASS_FORWARD) + extra, dtype=torch.uint8, device="cuda")
+        B.cct_conv_forward(d, tx, tw, tb, y, ws)
+        dx = torch.full((L.N, L.C, L.H, L.W), float("nan"), device="cuda")
+        ws = torch.empty(B.cct_conv_workspace_bytes(d, B.PASS_BACKWARD_DATA) + extra, dtype=torch.uint8, device="cuda")
+        B.cct_conv_backward_data(d, tw, tdy, dx, ws)
+        torch.cuda.synchronize()
+        outs[extra] = (y.cpu().numpy().tobytes(), dx.cpu().numpy().tobytes())
+    assert outs[0] == outs[64 << 20]
+
+
 def test_fully_connected_forward_needs_aligned_kernels(B):
     """The split product reads w with 16-byte loads: a misaligned w is refused, not misread."""
     import torch
