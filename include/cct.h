@@ -126,7 +126,9 @@ int cct_lowered_shape(const cct_conv_desc_t* desc, cct_lowering_t lowering, int6
  * measured MFMA rate, both calibrated on MI355X) for each layout that the library can
  * run for `pass` on this shape and returns the cheapest.  Never returns a layout that
  * cct_conv_* would reject for the same descriptor; for K == 1, stride == 1, pad == 0 all
- * three layouts coincide and TYPE1 is returned.  desc->lowering is ignored.
+ * three layouts coincide and TYPE1 is returned, as it is for a fully connected layer
+ * (K == H == W, pad 0, one group, fp32), where every lowering is a reshape.  desc->lowering is
+ * ignored.
  */
 int cct_pick_lowering(const cct_conv_desc_t* desc, cct_pass_t pass, cct_lowering_t* picked);
 

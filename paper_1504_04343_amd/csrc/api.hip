@@ -460,8 +460,10 @@ double model_cost(const cct_conv_desc_t& d, int pass, int type) {
 int pick(const cct_conv_desc_t& d, int pass) {
   if (d.K == 1 && d.stride == 1 && d.pad == 0 && type_supported(d, pass, CCT_LOWER_TYPE1))
     return CCT_LOWER_TYPE1;
-  // one output pixel per image (a fully connected layer): every lowering is a reshape of x
-  if (d.K == d.H && d.K == d.W && d.pad == 0 && type_supported(d, pass, CCT_LOWER_TYPE1))
+  // one output pixel per image (a fully connected layer): every lowering is a reshape of x, and
+  // AUTO / TYPE1 run it as plain matrix products (fully_connected.hip)
+  if (d.K == d.H && d.K == d.W && d.pad == 0 && d.groups == 1 && d.precision == CCT_PREC_F32 &&
+      type_supported(d, pass, CCT_LOWER_TYPE1))
     return CCT_LOWER_TYPE1;
   int best = 0;
   double best_cost = 0.0;
